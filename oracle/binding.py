@@ -1,0 +1,186 @@
+"""ctypes wrapper around libpp_oracle.so (built from pp_oracle.cpp with g++)."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "pp_oracle.cpp")
+_SO = os.path.join(_HERE, "libpp_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the checker (host compiler only)."""
+    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
+        subprocess.check_call(["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-pthread", "-o", _SO, _SRC])
+    return _SO
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        build()
+        L = C.CDLL(_SO)
+        vp, i32, i64 = C.c_void_p, C.c_int, C.c_int64
+        L.oracle_expand_weights.argtypes = [i32, i32, i32, vp, vp, vp, vp, i32, vp]
+        L.oracle_expand_weights.restype = i32
+        L.oracle_conv.argtypes = [i32] * 5 + [vp, vp, vp, i32, vp, vp, vp, i32]
+        L.oracle_conv.restype = None
+        L.oracle_conv_at.argtypes = [i32] * 5 + [vp, vp, i32, i32, vp, i64, vp, vp, vp, vp, i32]
+        L.oracle_conv_at.restype = None
+        L.oracle_brute.argtypes = [i32] * 6 + [vp] * 6 + [i32, vp]
+        L.oracle_brute.restype = None
+        L.oracle_maxpool2.argtypes = [i32] * 4 + [vp, vp]
+        L.oracle_maxpool2.restype = None
+        L.oracle_round_f16.argtypes = [i64, vp, vp]
+        L.oracle_round_f16.restype = None
+        L.oracle_widen_f16.argtypes = [i64, vp, vp]
+        L.oracle_widen_f16.restype = None
+        L.oracle_plan_ref.argtypes = [i32, i32, i32] + [vp] * 8
+        L.oracle_plan_ref.restype = i64
+        _lib = L
+    return _lib
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _c(a, dt):
+    return np.ascontiguousarray(a, dtype=dt)
+
+
+def default_threads() -> int:
+    try:
+        return max(1, len(os.sched_getaffinity(0)))
+    except AttributeError:
+        return os.cpu_count() or 1
+
+
+def expand_weights(c_in, c_out, masks, pattern_id, conn, weights, taps=4) -> np.ndarray:
+    """Masked dense weights Wd [c_out, c_in, 3, 3] (float64)."""
+    masks = _c(masks, np.uint16)
+    pid = _c(pattern_id, np.int32)
+    cm = _c(conn, np.uint8)
+    w = _c(weights, np.float64).reshape(-1)
+    wd = np.empty((c_out, c_in, 3, 3), dtype=np.float64)
+    rc = lib().oracle_expand_weights(c_in, c_out, len(masks), _p(masks), _p(pid), _p(cm), _p(w), taps, _p(wd))
+    if rc != 0:
+        raise ValueError(f"invalid pruned-layer description (code {rc})")
+    return wd
+
+
+def conv(x, wd, bias=None, relu=False, want_pre=False, want_scale=False, threads=None):
+    """Full-tensor reference result.  Returns y, or (y, pre, scale) with the extras asked for."""
+    x = _c(x, np.float64)
+    wd = _c(wd, np.float64)
+    n, c_in, h, w = x.shape
+    c_out = wd.shape[0]
+    assert wd.shape == (c_out, c_in, 3, 3)
+    b = None if bias is None else _c(bias, np.float64)
+    y = np.empty((n, c_out, h, w), dtype=np.float64)
+    pre = np.empty_like(y) if want_pre else None
+    sc = np.empty_like(y) if want_scale else None
+    lib().oracle_conv(n, c_in, c_out, h, w, _p(x), _p(wd), _p(b), int(relu), _p(y), _p(pre), _p(sc),
+                      threads or default_threads())
+    if want_pre or want_scale:
+        return y, pre, sc
+    return y
+
+
+def conv_at(x, wd, pts, bias=None, relu=False, threads=None):
+    """Reference result at sampled outputs.  x is float32 or float16 [n,c_in,h,w];
+    pts int32 [npts, 4] of (n, co, oy, ox).  Returns (y, pre, scale)."""
+    assert x.dtype in (np.float32, np.float16) and x.flags.c_contiguous
+    wd = _c(wd, np.float64)
+    n, c_in, h, w = x.shape
+    c_out = wd.shape[0]
+    pts = _c(pts, np.int32)
+    npts = pts.shape[0]
+    b = None if bias is None else _c(bias, np.float64)
+    y = np.empty(npts, dtype=np.float64)
+    pre = np.empty(npts, dtype=np.float64)
+    sc = np.empty(npts, dtype=np.float64)
+    lib().oracle_conv_at(n, c_in, c_out, h, w, _p(wd), _p(b), int(relu), int(x.dtype == np.float16), _p(x), npts,
+                         _p(pts), _p(y), _p(pre), _p(sc), threads or default_threads())
+    return y, pre, sc
+
+
+def brute(x, masks, pattern_id, conn, weights, c_out, bias=None, relu=False):
+    x = _c(x, np.float64)
+    n, c_in, h, w = x.shape
+    masks = _c(masks, np.uint16)
+    pid = _c(pattern_id, np.int32)
+    cm = _c(conn, np.uint8)
+    wt = _c(weights, np.float64).reshape(-1)
+    b = None if bias is None else _c(bias, np.float64)
+    y = np.empty((n, c_out, h, w), dtype=np.float64)
+    lib().oracle_brute(n, c_in, c_out, h, w, len(masks), _p(masks), _p(pid), _p(cm), _p(wt), _p(x), _p(b),
+                       int(relu), _p(y))
+    return y
+
+
+def maxpool2(x):
+    x = _c(x, np.float64)
+    n, c, h, w = x.shape
+    y = np.empty((n, c, h // 2, w // 2), dtype=np.float64)
+    lib().oracle_maxpool2(n, c, h, w, _p(x), _p(y))
+    return y
+
+
+def round_f16(v) -> np.ndarray:
+    """Round float64 values to IEEE binary16 (nearest even); returns uint16 bit patterns."""
+    v = _c(v, np.float64)
+    out = np.empty(v.shape, dtype=np.uint16)
+    lib().oracle_round_f16(v.size, _p(v), _p(out))
+    return out
+
+
+def widen_f16(bits) -> np.ndarray:
+    bits = _c(bits, np.uint16)
+    out = np.empty(bits.shape, dtype=np.float64)
+    lib().oracle_widen_f16(bits.size, _p(bits), _p(out))
+    return out
+
+
+def plan_ref(c_in, c_out, num_patterns, pattern_id, conn):
+    """Reference filter-kernel ordering; dict of canonical arrays."""
+    pid = _c(pattern_id, np.int32)
+    cm = _c(conn, np.uint8)
+    kk = int(np.count_nonzero(cm))
+    perm = np.empty(c_out, np.int32)
+    kcount = np.empty(c_out, np.int32)
+    pat_off = np.empty(c_out * (num_patterns + 1), np.int32)
+    kidx = np.empty(kk, np.int32)
+    kpat = np.empty(kk, np.uint8)
+    wsel = np.empty(kk, np.int64)
+    got = lib().oracle_plan_ref(c_in, c_out, num_patterns, _p(pid), _p(cm), _p(perm), _p(kcount), _p(pat_off),
+                                _p(kidx), _p(kpat), _p(wsel))
+    assert got == kk
+    return dict(perm=perm, kcount=kcount, pat_off=pat_off.reshape(c_out, num_patterns + 1), kidx=kidx, kpat=kpat,
+                wsel=wsel, k_kept=kk)
+
+
+# -- conveniences over a synthetic layer description (duck-typed: any object with the
+#    fields of synth.Layer) ---------------------------------------------------------
+
+def layer_dense_weights(layer) -> np.ndarray:
+    """Wd of a layer, with the weights first rounded to binary16 when the layer stores fp16."""
+    w = np.asarray(layer.weights, dtype=np.float64)
+    if layer.dtype == "f16":
+        w = widen_f16(round_f16(w))
+    return expand_weights(layer.c_in, layer.c_out, layer.pattern_masks, layer.pattern_id, layer.conn_mask, w,
+                          taps=9 if layer.dense else 4)
+
+
+def layer_reference(layer, x, relu=None, threads=None):
+    """(y, pre, scale) of the whole layer on input x (already in the storage dtype)."""
+    wd = layer_dense_weights(layer)
+    relu = layer.relu if relu is None else relu
+    return conv(np.asarray(x, dtype=np.float64), wd, layer.bias, relu, want_pre=True, want_scale=True,
+                threads=threads)

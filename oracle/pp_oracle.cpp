@@ -1,0 +1,324 @@
+// CPU checker for the pattern-pruned 3x3 convolution.  TEST INFRASTRUCTURE ONLY.
+//
+// This file is the yardstick the GPU library is compared against.  It is slow
+// on purpose and shares no code, header, table or helper with the library.
+// Only the tests, the smoke check and the benchmark's CPU-baseline leg may call
+// it; nothing in the product path does.
+//
+// What it computes.  Pattern-based pruning (paper, section 2.1.1 "Pattern-Based
+// Pruning") keeps, in every 3x3 kernel of a CONV filter, a fixed number of
+// weights (four in the 4-entry case) at positions taken from a small set of
+// predefined patterns; connectivity pruning (same section, and panel (b) of the
+// figure "pattern_connectivity") removes whole kernels, i.e. the link between
+// one input channel and one output channel.  Pruned weights are zeros of an
+// ordinary CONV layer, and the compiler techniques of section 2.3.1
+// (filter-kernel reorder, FKW storage, load-redundancy elimination) change
+// storage and code, never the arithmetic.  So the result has a plain
+// definition, and this file is that definition written out:
+//
+//   Wd[co][ci][r][c] = the kernel's j-th weight  if kernel (co,ci) is kept and
+//                      tap t = 3r+c is the j-th set bit of its pattern's mask
+//                    = 0                         otherwise
+//   pre[n][co][oy][ox] = bias[co] + sum_ci sum_r sum_c Wd[co][ci][r][c] * X(n,ci,oy+r-1,ox+c-1)
+//   X = x inside the image, 0 outside     (stride 1, zero padding 1, no kernel flip)
+//   y = max(pre, 0) when ReLU is fused (the one-to-one fusion case of section
+//       2.2 "DNNFusion", Table 1), else pre.
+//
+// The paper prints no formula for the CONV layer and no pattern set; the
+// readings taken here (cross-correlation, zero padding, ascending tap order of
+// the stored weights, ids of pruned kernels ignored) are the ones any of the
+// frameworks the paper names gives a CONV layer.  All arithmetic is in double.
+//
+// Pins (tests/test_oracle_*.py): brute-force gather per output, float64
+// library convolution, all-taps/all-kernels = dense conv, empty mask = bias,
+// impulse and constant-input closed forms, linearity, centre-only = matrix
+// product, filter-permutation equivariance, a hand-worked fixture.
+// The reference filter ordering (oracle_plan_ref) is pinned by structural
+// invariants and a hand-worked fixture; the ordering keys themselves are this
+// repository's reading of "filters with similar kernels together" (section
+// 2.3.1), which the paper does not spell out: parity unpinned against the paper
+// for the key choice.
+
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <thread>
+#include <vector>
+
+namespace {
+
+int popcount9(unsigned m) {
+    int n = 0;
+    for (int t = 0; t < 9; ++t) n += (m >> t) & 1u;
+    return n;
+}
+
+template <class Fn>
+void parallel_for(int64_t count, int threads, Fn fn) {
+    if (threads <= 1 || count <= 1) {
+        for (int64_t i = 0; i < count; ++i) fn(i);
+        return;
+    }
+    std::vector<std::thread> pool;
+    int nt = (int)std::min<int64_t>(threads, count);
+    for (int t = 0; t < nt; ++t)
+        pool.emplace_back([=]() {
+            for (int64_t i = t; i < count; i += nt) fn(i);
+        });
+    for (auto& th : pool) th.join();
+}
+
+}  // namespace
+
+extern "C" {
+
+// Expand the pruned description into explicitly masked dense weights
+// Wd[c_out][c_in][3][3] (section 2.1.1: pruned positions are zero weights).
+// taps_per_kernel is 4 (pattern-pruned) or 9 (unpruned layer: w holds all nine
+// taps in ascending order and pattern ids are not read).
+// Returns 0, or a negative code for an invalid description.
+int oracle_expand_weights(int c_in, int c_out, int num_patterns, const uint16_t* masks, const int32_t* pattern_id,
+                          const uint8_t* conn, const double* w, int taps_per_kernel, double* Wd) {
+    if (taps_per_kernel != 4 && taps_per_kernel != 9) return -1;
+    if (taps_per_kernel == 4)
+        for (int p = 0; p < num_patterns; ++p)
+            if (masks[p] >= 512 || popcount9(masks[p]) != 4) return -2;
+    for (int64_t k = 0; k < (int64_t)c_in * c_out; ++k) {
+        double* d = Wd + k * 9;
+        for (int t = 0; t < 9; ++t) d[t] = 0.0;
+        if (!conn[k]) continue;
+        if (taps_per_kernel == 9) {
+            for (int t = 0; t < 9; ++t) d[t] = w[k * 9 + t];
+            continue;
+        }
+        int p = pattern_id[k];
+        if (p < 0 || p >= num_patterns) return -3;
+        int j = 0;
+        for (int t = 0; t < 9; ++t)
+            if ((masks[p] >> t) & 1u) d[t] = w[k * 4 + j++];
+    }
+    return 0;
+}
+
+// The definition, as seven plain nested loops over the masked dense weights.
+// x [n][c_in][h][w], Wd [c_out][c_in][3][3], bias [c_out] or null,
+// y [n][c_out][h][w]; pre (pre-activation) and scale (|bias| + sum |Wd||X|, the
+// magnitude against which rounding error of a dot product is judged) may be null.
+void oracle_conv(int n, int c_in, int c_out, int h, int w, const double* x, const double* Wd, const double* bias,
+                 int relu, double* y, double* pre, double* scale, int threads) {
+    parallel_for((int64_t)n * c_out, threads, [=](int64_t job) {
+        int img = (int)(job / c_out), co = (int)(job % c_out);
+        for (int oy = 0; oy < h; ++oy)
+            for (int ox = 0; ox < w; ++ox) {
+                double acc = bias ? bias[co] : 0.0;
+                double mag = bias ? std::fabs(bias[co]) : 0.0;
+                for (int ci = 0; ci < c_in; ++ci)
+                    for (int r = 0; r < 3; ++r)
+                        for (int c = 0; c < 3; ++c) {
+                            int iy = oy + r - 1, ix = ox + c - 1;
+                            if (iy < 0 || iy >= h || ix < 0 || ix >= w) continue;
+                            double wt = Wd[(((int64_t)co * c_in + ci) * 3 + r) * 3 + c];
+                            double xv = x[(((int64_t)img * c_in + ci) * h + iy) * w + ix];
+                            acc += wt * xv;
+                            mag += std::fabs(wt) * std::fabs(xv);
+                        }
+                int64_t o = (((int64_t)img * c_out + co) * h + oy) * w + ox;
+                if (pre) pre[o] = acc;
+                if (scale) scale[o] = mag;
+                y[o] = (relu && acc < 0.0) ? 0.0 : acc;
+            }
+    });
+}
+
+// The same definition evaluated at chosen outputs only: pts holds npts
+// quadruples (n, co, oy, ox).  For layers too large to evaluate whole.
+void oracle_conv_at(int n, int c_in, int c_out, int h, int w, const double* Wd, const double* bias, int relu,
+                    int x_is_f16, const void* x, int64_t npts, const int32_t* pts, double* y, double* pre,
+                    double* scale, int threads);
+
+// Brute-force pin for oracle_conv on tiny shapes.  Written against the pruned
+// description itself (mask bits and the j-th stored weight), not against Wd:
+// for each output it first gathers every (weight, input) pair that the
+// definition says contributes, then sums the products.
+void oracle_brute(int n, int c_in, int c_out, int h, int w, int num_patterns, const uint16_t* masks,
+                  const int32_t* pattern_id, const uint8_t* conn, const double* wts, const double* x,
+                  const double* bias, int relu, double* y) {
+    (void)num_patterns;
+    std::vector<double> ws, xs;
+    for (int img = 0; img < n; ++img)
+        for (int co = 0; co < c_out; ++co)
+            for (int oy = 0; oy < h; ++oy)
+                for (int ox = 0; ox < w; ++ox) {
+                    ws.clear();
+                    xs.clear();
+                    for (int ci = 0; ci < c_in; ++ci) {
+                        int64_t k = (int64_t)co * c_in + ci;
+                        if (!conn[k]) continue;
+                        unsigned m = masks[pattern_id[k]];
+                        int j = 0;
+                        for (int t = 0; t < 9; ++t) {
+                            if (!((m >> t) & 1u)) continue;
+                            double wt = wts[k * 4 + j];
+                            ++j;
+                            int dy = t / 3 - 1, dx = t % 3 - 1;
+                            int iy = oy + dy, ix = ox + dx;
+                            if (iy < 0 || iy >= h || ix < 0 || ix >= w) continue;   // zero padding
+                            ws.push_back(wt);
+                            xs.push_back(x[(((int64_t)img * c_in + ci) * h + iy) * w + ix]);
+                        }
+                    }
+                    long double s = bias ? (long double)bias[co] : 0.0L;
+                    for (size_t i = 0; i < ws.size(); ++i) s += (long double)ws[i] * (long double)xs[i];
+                    double v = (double)s;
+                    y[(((int64_t)img * c_out + co) * h + oy) * w + ox] = (relu && v < 0.0) ? 0.0 : v;
+                }
+}
+
+// 2x2 max-pool, stride 2 (only used to chain the layers of a VGG-shaped stack).
+void oracle_maxpool2(int n, int c, int h, int w, const double* x, double* y) {
+    int ho = h / 2, wo = w / 2;
+    for (int64_t p = 0; p < (int64_t)n * c; ++p)
+        for (int oy = 0; oy < ho; ++oy)
+            for (int ox = 0; ox < wo; ++ox) {
+                const double* s = x + (p * h + 2 * oy) * w + 2 * ox;
+                double m = std::max(std::max(s[0], s[1]), std::max(s[w], s[w + 1]));
+                y[(p * ho + oy) * wo + ox] = m;
+            }
+}
+
+// IEEE binary16 <-> wider types, round to nearest even, subnormals kept,
+// overflow to infinity.  Written from the format definition: 1 sign bit,
+// 5 exponent bits (bias 15), 10 fraction bits.
+uint16_t oracle_f64_to_f16_bits(double v) {
+    uint16_t sign = std::signbit(v) ? 0x8000u : 0u;
+    double a = std::fabs(v);
+    if (std::isnan(v)) return (uint16_t)(sign | 0x7E00u);
+    if (a == 0.0) return sign;
+    // spacing of representable values at magnitude a: 2^(e-10), e = floor(log2 a) clamped below at -14
+    int e;
+    std::frexp(a, &e);          // a = f * 2^e, f in [0.5, 1)  ->  floor(log2 a) = e - 1
+    int fl = e - 1;
+    if (fl < -14) fl = -14;
+    double ulp = std::ldexp(1.0, fl - 10);
+    double q = a / ulp;         // exact: division by a power of two
+    double fq = std::floor(q);
+    double rem = q - fq;
+    if (rem > 0.5 || (rem == 0.5 && std::fmod(fq, 2.0) == 1.0)) fq += 1.0;
+    double r = fq * ulp;        // rounded magnitude (may have carried into the next binade)
+    if (r >= 65520.0) return (uint16_t)(sign | 0x7C00u);
+    if (r < std::ldexp(1.0, -14)) return (uint16_t)(sign | (uint16_t)(r / std::ldexp(1.0, -24)));   // subnormal
+    int e2;
+    double f2 = std::frexp(r, &e2);      // r = f2 * 2^e2, f2 in [0.5,1)
+    int expo = e2 - 1 + 15;
+    uint16_t frac = (uint16_t)((f2 * 2.0 - 1.0) * 1024.0);
+    return (uint16_t)(sign | (expo << 10) | frac);
+}
+
+double oracle_f16_bits_to_f64(uint16_t b) {
+    int sign = b >> 15, expo = (b >> 10) & 31, frac = b & 1023;
+    double v;
+    if (expo == 0) v = std::ldexp((double)frac, -24);
+    else if (expo == 31) v = frac ? NAN : INFINITY;
+    else v = std::ldexp(1.0 + frac / 1024.0, expo - 15);
+    return sign ? -v : v;
+}
+
+void oracle_round_f16(int64_t count, const double* in, uint16_t* out) {
+    for (int64_t i = 0; i < count; ++i) out[i] = oracle_f64_to_f16_bits(in[i]);
+}
+
+void oracle_widen_f16(int64_t count, const uint16_t* in, double* out) {
+    for (int64_t i = 0; i < count; ++i) out[i] = oracle_f16_bits_to_f64(in[i]);
+}
+
+void oracle_conv_at(int n, int c_in, int c_out, int h, int w, const double* Wd, const double* bias, int relu,
+                    int x_is_f16, const void* x, int64_t npts, const int32_t* pts, double* y, double* pre,
+                    double* scale, int threads) {
+    (void)n;
+    const float* xf = (const float*)x;
+    const uint16_t* xh = (const uint16_t*)x;
+    parallel_for(npts, threads, [=](int64_t i) {
+        int img = pts[4 * i], co = pts[4 * i + 1], oy = pts[4 * i + 2], ox = pts[4 * i + 3];
+        double acc = bias ? bias[co] : 0.0;
+        double mag = bias ? std::fabs(bias[co]) : 0.0;
+        for (int ci = 0; ci < c_in; ++ci)
+            for (int r = 0; r < 3; ++r)
+                for (int c = 0; c < 3; ++c) {
+                    int iy = oy + r - 1, ix = ox + c - 1;
+                    if (iy < 0 || iy >= h || ix < 0 || ix >= w) continue;
+                    int64_t xi = (((int64_t)img * c_in + ci) * h + iy) * w + ix;
+                    double xv = x_is_f16 ? oracle_f16_bits_to_f64(xh[xi]) : (double)xf[xi];
+                    double wt = Wd[(((int64_t)co * c_in + ci) * 3 + r) * 3 + c];
+                    acc += wt * xv;
+                    mag += std::fabs(wt) * std::fabs(xv);
+                }
+        if (pre) pre[i] = acc;
+        if (scale) scale[i] = mag;
+        y[i] = (relu && acc < 0.0) ? 0.0 : acc;
+    });
+}
+
+// Reference filter-kernel ordering (section 2.3.1, "Filter Kernel Reorder":
+// same-pattern kernels of a filter together, filters with similar kernels
+// together).  The paper names no sort keys; the keys used are
+//   inside a filter : ascending (pattern id, input channel);
+//   between filters : kept-kernel count descending, then the per-pattern
+//                     histogram compared lexicographically, larger first,
+//                     then original filter index ascending.
+// Outputs, all by position in the new filter order:
+//   perm[c_out]             original filter index
+//   kcount[c_out]           kept kernels of that filter
+//   pat_off[c_out*(P+1)]    prefix sums of the per-pattern counts
+//   kidx[k_kept], kpat[k_kept]   input channel and pattern of each kernel, filters
+//                           concatenated in the new order
+//   wsel[k_kept]            index (co*c_in+ci) of the kernel in the caller's arrays
+// Returns k_kept.
+int64_t oracle_plan_ref(int c_in, int c_out, int num_patterns, const int32_t* pattern_id, const uint8_t* conn,
+                        int32_t* perm, int32_t* kcount, int32_t* pat_off, int32_t* kidx, uint8_t* kpat,
+                        int64_t* wsel) {
+    struct Kern { int pat, ci; };
+    std::vector<std::vector<Kern>> kept(c_out);
+    std::vector<std::vector<int>> hist(c_out, std::vector<int>(num_patterns, 0));
+    for (int co = 0; co < c_out; ++co)
+        for (int ci = 0; ci < c_in; ++ci) {
+            int64_t k = (int64_t)co * c_in + ci;
+            if (!conn[k]) continue;
+            kept[co].push_back({pattern_id[k], ci});
+            hist[co][pattern_id[k]] += 1;
+        }
+    for (int co = 0; co < c_out; ++co)
+        std::stable_sort(kept[co].begin(), kept[co].end(), [](const Kern& a, const Kern& b) {
+            if (a.pat != b.pat) return a.pat < b.pat;
+            return a.ci < b.ci;
+        });
+    std::vector<int> order(c_out);
+    for (int co = 0; co < c_out; ++co) order[co] = co;
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) {
+        if (kept[a].size() != kept[b].size()) return kept[a].size() > kept[b].size();
+        for (int p = 0; p < num_patterns; ++p)
+            if (hist[a][p] != hist[b][p]) return hist[a][p] > hist[b][p];
+        return a < b;
+    });
+    int64_t out = 0;
+    for (int pos = 0; pos < c_out; ++pos) {
+        int co = order[pos];
+        perm[pos] = co;
+        kcount[pos] = (int32_t)kept[co].size();
+        int run = 0;
+        for (int p = 0; p < num_patterns; ++p) {
+            pat_off[(int64_t)pos * (num_patterns + 1) + p] = run;
+            run += hist[co][p];
+        }
+        pat_off[(int64_t)pos * (num_patterns + 1) + num_patterns] = run;
+        for (const Kern& k : kept[co]) {
+            kidx[out] = k.ci;
+            kpat[out] = (uint8_t)k.pat;
+            wsel[out] = (int64_t)co * c_in + k.ci;
+            ++out;
+        }
+    }
+    return out;
+}
+
+}  // extern "C"
