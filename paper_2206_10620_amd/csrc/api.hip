@@ -1,0 +1,332 @@
+// C ABI of the library (declared in include/pp_conv.h): plan creation and upload, kernel
+// selection and launch, the generic any-pattern kernel and the 2x2 max-pool helper.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <new>
+
+#include "k1_tiled.hpp"
+#include "plan.hpp"
+#include "pp_conv.h"
+
+namespace ppc {
+
+k1_launch_fn k1_lookup_f32_p8_r1(int f, int lw);
+k1_launch_fn k1_lookup_f32_p8_r2(int f, int lw);
+k1_launch_fn k1_lookup_f32_p16_r1(int f, int lw);
+k1_launch_fn k1_lookup_f32_p16_r2(int f, int lw);
+k1_launch_fn k1_lookup_f16_p8_r1(int f, int lw);
+k1_launch_fn k1_lookup_f16_p8_r2(int f, int lw);
+k1_launch_fn k1_lookup_f16_p16_r1(int f, int lw);
+k1_launch_fn k1_lookup_f16_p16_r2(int f, int lw);
+
+k1_launch_fn k1_lookup(int dtype, int np, int r, int f, int lw) {
+    if (dtype == PP_F32) {
+        if (np == 8) return r == 1 ? k1_lookup_f32_p8_r1(f, lw) : k1_lookup_f32_p8_r2(f, lw);
+        return r == 1 ? k1_lookup_f32_p16_r1(f, lw) : k1_lookup_f32_p16_r2(f, lw);
+    }
+    if (np == 8) return r == 1 ? k1_lookup_f16_p8_r1(f, lw) : k1_lookup_f16_p8_r2(f, lw);
+    return r == 1 ? k1_lookup_f16_p16_r1(f, lw) : k1_lookup_f16_p16_r2(f, lw);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Generic kernel: any pattern table (and the unpruned nine-tap case).  One lane per output
+// pixel, one filter per blockIdx.y; walks the filter's reordered kernel list (same-pattern
+// kernels consecutive) with wave-uniform indices and reads the input straight from global
+// memory with bounds checks.  It is the correctness path for pattern sets the tiled kernel has no
+// specialised code for, not a fast path.
+struct K0Args {
+    const void* x;
+    void* y;
+    const int32_t* filt_off;   // [c_out+1]
+    const int32_t* kidx;       // [k_kept]
+    const uint8_t* kpat;       // [k_kept]
+    const float* w;            // [k_kept*taps] (binary16-rounded values for an fp16 plan)
+    const int8_t* tap_dyx;     // [P*taps*2]
+    const int32_t* perm;       // [c_out]
+    const float* bias;         // [c_out] by original index
+    int32_t n, c_in, c_out, h, w_, taps, relu;
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void k0_generic(const K0Args a) {
+    const int pos = blockIdx.y;
+    const int64_t pix = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t hw = (int64_t)a.h * a.w_;
+    if (pix >= (int64_t)a.n * hw) return;
+    const int img = (int)(pix / hw);
+    const int rem = (int)(pix - (int64_t)img * hw);
+    const int oy = rem / a.w_, ox = rem - oy * a.w_;
+    const T* __restrict__ x = static_cast<const T*>(a.x);
+    float acc = 0.0f;
+    const int beg = a.filt_off[pos], end = a.filt_off[pos + 1];
+    for (int e = beg; e < end; ++e) {
+        const int ci = a.kidx[e];
+        const int8_t* tp = a.tap_dyx + (int)a.kpat[e] * a.taps * 2;
+        const float* wv = a.w + (int64_t)e * a.taps;
+        const T* xc = x + ((int64_t)img * a.c_in + ci) * hw;
+        for (int j = 0; j < a.taps; ++j) {
+            const int iy = oy + tp[2 * j], ix = ox + tp[2 * j + 1];
+            if (iy >= 0 && iy < a.h && ix >= 0 && ix < a.w_) acc = __builtin_fmaf(wv[j], (float)xc[iy * a.w_ + ix], acc);
+        }
+    }
+    const int co = a.perm[pos];
+    acc += a.bias[co];
+    if (a.relu) acc = acc > 0.0f ? acc : 0.0f;
+    static_cast<T*>(a.y)[((int64_t)img * a.c_out + co) * hw + rem] = (T)acc;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void maxpool2x2(const T* __restrict__ x, T* __restrict__ y, int64_t planes, int h, int w) {
+    const int ho = h / 2, wo = w / 2;
+    const int64_t total = planes * ho * wo;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+        const int ox = (int)(i % wo);
+        const int64_t t = i / wo;
+        const int oy = (int)(t % ho);
+        const int64_t p = t / ho;
+        const T* s = x + (p * h + 2 * oy) * w + 2 * ox;
+        const float a0 = (float)s[0], a1 = (float)s[1], a2 = (float)s[w], a3 = (float)s[w + 1];
+        const float m0 = a0 > a1 ? a0 : a1, m1 = a2 > a3 ? a2 : a3;
+        y[i] = (T)(m0 > m1 ? m0 : m1);
+    }
+}
+
+}  // namespace ppc
+
+using namespace ppc;
+
+struct pp_conv_plan {
+    HostPlan hp;
+    bool on_device = false;
+    // tiled kernel
+    uint32_t* d_stream = nullptr;
+    int32_t* d_wave_off = nullptr;
+    int32_t* d_perm_pad = nullptr;
+    float* d_bias_pad = nullptr;
+    k1_launch_fn launch = nullptr;
+    // generic kernel
+    int32_t* d_filt_off = nullptr;
+    int32_t* d_kidx = nullptr;
+    uint8_t* d_kpat = nullptr;
+    float* d_w = nullptr;
+    int8_t* d_tap = nullptr;
+    int32_t* d_perm = nullptr;
+    float* d_bias = nullptr;
+};
+
+namespace {
+
+template <typename T>
+bool upload(T** dst, const void* src, size_t bytes) {
+    if (bytes == 0) bytes = 16;
+    if (hipMalloc(reinterpret_cast<void**>(dst), bytes) != hipSuccess) {
+        *dst = nullptr;
+        return false;
+    }
+    if (src && hipMemcpy(*dst, src, bytes, hipMemcpyHostToDevice) != hipSuccess) return false;
+    return true;
+}
+
+void free_device(pp_conv_plan_t* p) {
+    void* bufs[] = {p->d_stream, p->d_wave_off, p->d_perm_pad, p->d_bias_pad, p->d_filt_off, p->d_kidx,
+                    p->d_kpat,   p->d_w,        p->d_tap,      p->d_perm,     p->d_bias};
+    for (void* b : bufs)
+        if (b) (void)hipFree(b);
+}
+
+int staging_vec(int w, int tw, int elem_bytes) {
+    int v = 16 / elem_bytes;
+    while (v > 1 && (w % v != 0 || tw % v != 0)) v /= 2;
+    return v;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* pp_status_string(pp_status_t s) {
+    switch (s) {
+        case PP_OK: return "ok";
+        case PP_ERR_NULL: return "null pointer";
+        case PP_ERR_SHAPE: return "bad shape";
+        case PP_ERR_PATTERN: return "bad pattern mask or id";
+        case PP_ERR_UNSUPPORTED: return "unsupported request";
+        case PP_ERR_ALLOC: return "host allocation failed";
+        case PP_ERR_DEVICE: return "device error";
+    }
+    return "unknown status";
+}
+
+pp_status_t pp_conv_plan(const pp_conv_desc_t* desc, pp_conv_plan_t** out_plan) {
+    if (out_plan) *out_plan = nullptr;
+    if (!desc || !out_plan) return PP_ERR_NULL;
+    pp_status_t st = validate(*desc);
+    if (st != PP_OK) return st;
+    pp_conv_plan_t* p = new (std::nothrow) pp_conv_plan_t();
+    if (!p) return PP_ERR_ALLOC;
+    try {
+        build_canonical(*desc, p->hp);
+        st = build_layouts(*desc, p->hp);
+    } catch (const std::bad_alloc&) {
+        st = PP_ERR_ALLOC;
+    }
+    if (st != PP_OK) {
+        delete p;
+        return st;
+    }
+    HostPlan& hp = p->hp;
+    if (hp.tiled) {
+        p->launch = k1_lookup(hp.dtype, hp.tl.np, hp.tl.r, hp.tl.f, hp.tl.lw);
+        if (!p->launch) {
+            delete p;
+            return PP_ERR_UNSUPPORTED;
+        }
+    } else if (hp.c_out > 65535) {
+        delete p;
+        return PP_ERR_UNSUPPORTED;
+    }
+    if (desc->flags & PP_FLAG_HOST_ONLY) {
+        *out_plan = p;
+        return PP_OK;
+    }
+    bool ok = true;
+    if (hp.tiled) {
+        const TiledLayout& tl = hp.tl;
+        ok = ok && upload(&p->d_stream, tl.stream.data(), tl.stream.size() * 4);
+        ok = ok && upload(&p->d_wave_off, tl.wave_off.data(), tl.wave_off.size() * 4);
+        ok = ok && upload(&p->d_perm_pad, tl.perm_pad.data(), tl.perm_pad.size() * 4);
+        ok = ok && upload(&p->d_bias_pad, tl.bias_pad.data(), tl.bias_pad.size() * 4);
+    } else {
+        const Canonical& cn = hp.canon;
+        std::vector<float> w = cn.wpacked;
+        if (hp.dtype == PP_F16)
+            for (float& v : w) v = f16_to_f32(f32_to_f16_rne(v));
+        ok = ok && upload(&p->d_filt_off, hp.filt_off.data(), hp.filt_off.size() * 4);
+        ok = ok && upload(&p->d_kidx, cn.kidx.data(), cn.kidx.size() * 4);
+        ok = ok && upload(&p->d_kpat, cn.kpat.data(), cn.kpat.size());
+        ok = ok && upload(&p->d_w, w.data(), w.size() * 4);
+        ok = ok && upload(&p->d_tap, hp.tap_dyx.data(), hp.tap_dyx.size());
+        ok = ok && upload(&p->d_perm, cn.perm.data(), cn.perm.size() * 4);
+        ok = ok && upload(&p->d_bias, hp.bias.data(), hp.bias.size() * 4);
+    }
+    if (!ok) {
+        free_device(p);
+        delete p;
+        (void)hipGetLastError();
+        return PP_ERR_DEVICE;
+    }
+    p->on_device = true;
+    *out_plan = p;
+    return PP_OK;
+}
+
+pp_status_t pp_conv_run(const pp_conv_plan_t* plan, const void* x_dev, void* y_dev, int32_t n, void* hip_stream) {
+    if (!plan || !x_dev || !y_dev) return PP_ERR_NULL;
+    if (!plan->on_device) return PP_ERR_UNSUPPORTED;
+    const HostPlan& hp = plan->hp;
+    if (n <= 0) return PP_ERR_SHAPE;
+    const int64_t hw = (int64_t)hp.h * hp.w;
+    if ((int64_t)n * hp.c_in * hw >= ((int64_t)1 << 31) || (int64_t)n * hp.c_out * hw >= ((int64_t)1 << 31) ||
+        (int64_t)n * (hp.h + 1) >= ((int64_t)1 << 30))
+        return PP_ERR_SHAPE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int relu = (hp.flags & PP_FLAG_RELU) ? 1 : 0;
+    if (!hp.tiled) {
+        K0Args a{x_dev, y_dev, plan->d_filt_off, plan->d_kidx, plan->d_kpat, plan->d_w, plan->d_tap, plan->d_perm,
+                 plan->d_bias, n, hp.c_in, hp.c_out, hp.h, hp.w, hp.taps, relu};
+        const int64_t blocks = ((int64_t)n * hw + 255) / 256;
+        if (blocks >= ((int64_t)1 << 31)) return PP_ERR_SHAPE;
+        dim3 grid((unsigned)blocks, (unsigned)hp.c_out);
+        if (hp.dtype == PP_F16) hipLaunchKernelGGL(k0_generic<_Float16>, grid, dim3(256), 0, stream, a);
+        else hipLaunchKernelGGL(k0_generic<float>, grid, dim3(256), 0, stream, a);
+        return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_DEVICE;
+    }
+    const TiledLayout& tl = hp.tl;
+    const int eb = hp.dtype == PP_F16 ? 2 : 4;
+    const TileGeom tg = tile_geom(tl.lw, tl.r, eb);
+    K1Args a{};
+    a.x = x_dev;
+    a.y = y_dev;
+    a.stream = plan->d_stream;
+    a.wave_off = plan->d_wave_off;
+    a.bias_pad = plan->d_bias_pad;
+    a.perm_pad = plan->d_perm_pad;
+    a.n = n;
+    a.c_in = hp.c_in;
+    a.c_out = hp.c_out;
+    a.h = hp.h;
+    a.w = hp.w;
+    a.vh = n * (hp.h + 1) - 1;
+    a.mrows = (a.vh + tl.r - 1) / tl.r;
+    a.wg_per_strip = (int)(((int64_t)a.mrows * tl.lw + 63) / 64);
+    a.strips = (hp.w + tg.tw - 1) / tg.tw;
+    a.groups = tl.groups;
+    a.wf = tl.wf;
+    a.ks = tl.ks;
+    a.cc = tl.cc;
+    a.chunks = tl.chunks;
+    a.vec = staging_vec(hp.w, tg.tw, eb);
+    a.relu = relu;
+    const int nfb = (tl.groups + tl.wf - 1) / tl.wf;
+    const int64_t blocks = (int64_t)a.strips * a.wg_per_strip * nfb;
+    if (blocks >= ((int64_t)1 << 31)) return PP_ERR_SHAPE;
+    const int lds = k1_lds_bytes(tl.lw, tl.r, tl.f, tl.wf, tl.ks, tl.cc, eb);
+    plan->launch(a, (int)blocks, 64 * tl.wf * tl.ks, lds, stream);
+    return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_DEVICE;
+}
+
+pp_status_t pp_conv_destroy(pp_conv_plan_t* plan) {
+    if (!plan) return PP_OK;
+    free_device(plan);
+    delete plan;
+    return PP_OK;
+}
+
+pp_status_t pp_conv_plan_query(const pp_conv_plan_t* plan, pp_plan_info_t* out) {
+    if (!plan || !out) return PP_ERR_NULL;
+    const HostPlan& hp = plan->hp;
+    out->c_out = hp.c_out;
+    out->c_in = hp.c_in;
+    out->num_patterns = hp.num_patterns;
+    out->taps = hp.taps;
+    out->k_kept = hp.canon.k_kept;
+    out->perm = hp.canon.perm.data();
+    out->kcount = hp.canon.kcount.data();
+    out->pat_off = hp.canon.pat_off.data();
+    out->kidx = hp.canon.kidx.data();
+    out->kpat = hp.canon.kpat.data();
+    out->wpacked = hp.canon.wpacked.data();
+    out->chosen = hp.chosen;
+    return PP_OK;
+}
+
+pp_status_t pp_conv_plan_unpack(const pp_conv_plan_t* plan, int32_t* kidx_out, uint8_t* kpat_out, float* w_out) {
+    if (!plan || !kidx_out || !kpat_out || !w_out) return PP_ERR_NULL;
+    try {
+        return unpack_stream(plan->hp, kidx_out, kpat_out, w_out);
+    } catch (const std::bad_alloc&) {
+        return PP_ERR_ALLOC;
+    }
+}
+
+pp_status_t pp_maxpool2x2_run(const void* x_dev, void* y_dev, int32_t n, int32_t c, int32_t h, int32_t w, int32_t dtype,
+                              void* hip_stream) {
+    if (!x_dev || !y_dev) return PP_ERR_NULL;
+    if (n < 1 || c < 1 || h < 2 || w < 2 || (h & 1) || (w & 1)) return PP_ERR_SHAPE;
+    if (dtype != PP_F32 && dtype != PP_F16) return PP_ERR_UNSUPPORTED;
+    const int64_t planes = (int64_t)n * c;
+    const int64_t total = planes * (h / 2) * (w / 2);
+    int64_t blocks = (total + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (dtype == PP_F16)
+        hipLaunchKernelGGL(maxpool2x2<_Float16>, dim3((unsigned)blocks), dim3(256), 0, stream,
+                           static_cast<const _Float16*>(x_dev), static_cast<_Float16*>(y_dev), planes, h, w);
+    else
+        hipLaunchKernelGGL(maxpool2x2<float>, dim3((unsigned)blocks), dim3(256), 0, stream,
+                           static_cast<const float*>(x_dev), static_cast<float*>(y_dev), planes, h, w);
+    return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_DEVICE;
+}
+
+}  // extern "C"

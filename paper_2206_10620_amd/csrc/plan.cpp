@@ -1,0 +1,385 @@
+// Host-side planning: validation, filter kernel reorder, weight-stream packing.
+// Paper section 2.3.1: the sparsity of a layer is fully known before deployment, so the order
+// in which kernels are visited, and the code that visits them, is fixed ahead of time.
+#include "plan.hpp"
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <numeric>
+
+namespace ppc {
+
+namespace {
+
+int popcount16(uint32_t v) {
+    int n = 0;
+    while (v) {
+        v &= v - 1;
+        ++n;
+    }
+    return n;
+}
+
+int builtin_slot(uint16_t mask) {
+    for (int s = 0; s < kBuiltinPatterns; ++s)
+        if (kBuiltinMasks[s] == mask) return s;
+    return -1;
+}
+
+}  // namespace
+
+uint16_t f32_to_f16_rne(float v) {
+    uint32_t u;
+    std::memcpy(&u, &v, 4);
+    uint32_t sign = (u >> 16) & 0x8000u;
+    uint32_t mag = u & 0x7FFFFFFFu;
+    if (mag >= 0x7F800000u) return (uint16_t)(sign | (mag > 0x7F800000u ? 0x7E00u : 0x7C00u));   // nan / inf
+    if (mag >= 0x477FF000u) return (uint16_t)(sign | 0x7C00u);       // rounds to >= 65520: overflow to inf
+    if (mag < 0x33000001u) return (uint16_t)sign;                    // <= 2^-25: rounds to zero (tie to even)
+    int32_t e = (int32_t)(mag >> 23) - 127;                          // unbiased exponent
+    uint32_t man = (mag & 0x7FFFFFu) | 0x800000u;                    // 24-bit significand
+    int shift = (e < -14) ? (13 + (-14 - e)) : 13;                   // bits dropped; more for subnormal results
+    uint32_t kept = man >> shift;
+    uint32_t rem = man & ((1u << shift) - 1u);
+    uint32_t half = 1u << (shift - 1);
+    if (rem > half || (rem == half && (kept & 1u))) ++kept;
+    uint32_t out;
+    if (e < -14) out = kept;                                         // subnormal (a carry lands on the smallest normal)
+    else out = ((uint32_t)(e + 15) << 10) + (kept - 0x400u);         // a mantissa carry bumps the exponent
+    return (uint16_t)(sign | out);
+}
+
+float f16_to_f32(uint16_t b) {
+    uint32_t sign = (uint32_t)(b & 0x8000u) << 16;
+    int e = (b >> 10) & 31;
+    uint32_t m = b & 1023u;
+    float v;
+    if (e == 0) v = std::ldexp((float)m, -24);
+    else if (e == 31) v = m ? NAN : INFINITY;
+    else v = std::ldexp(1.0f + (float)m / 1024.0f, e - 15);
+    uint32_t u;
+    std::memcpy(&u, &v, 4);
+    u |= sign;
+    std::memcpy(&v, &u, 4);
+    return v;
+}
+
+pp_status_t validate(const pp_conv_desc_t& d) {
+    const bool dense = (d.flags & PP_FLAG_DENSE) != 0;
+    if (!d.weights) return PP_ERR_NULL;
+    if (!dense && (!d.pattern_masks || !d.pattern_id)) return PP_ERR_NULL;
+    if (d.c_in < 1 || d.c_out < 1 || d.h < 1 || d.w < 1) return PP_ERR_SHAPE;
+    if ((int64_t)d.c_in * d.c_out >= (int64_t)1 << 28) return PP_ERR_SHAPE;
+    if ((int64_t)std::max(d.c_in, d.c_out) * d.h * d.w >= (int64_t)1 << 31) return PP_ERR_SHAPE;
+    if (d.flags & ~(uint32_t)(PP_FLAG_RELU | PP_FLAG_DENSE | PP_FLAG_HOST_ONLY)) return PP_ERR_UNSUPPORTED;
+    if (d.dtype != PP_F32 && d.dtype != PP_F16) return PP_ERR_UNSUPPORTED;
+    if (dense) return PP_OK;
+    if (d.num_patterns < 1 || d.num_patterns > 255) return PP_ERR_PATTERN;
+    for (int p = 0; p < d.num_patterns; ++p)
+        if (d.pattern_masks[p] >= 512 || popcount16(d.pattern_masks[p]) != 4) return PP_ERR_PATTERN;
+    const int64_t k_total = (int64_t)d.c_in * d.c_out;
+    for (int64_t k = 0; k < k_total; ++k) {
+        if (d.conn_mask && !d.conn_mask[k]) continue;
+        if (d.pattern_id[k] < 0 || d.pattern_id[k] >= d.num_patterns) return PP_ERR_PATTERN;
+    }
+    return PP_OK;
+}
+
+void build_canonical(const pp_conv_desc_t& d, HostPlan& hp) {
+    const bool dense = (d.flags & PP_FLAG_DENSE) != 0;
+    hp.c_in = d.c_in;
+    hp.c_out = d.c_out;
+    hp.h = d.h;
+    hp.w = d.w;
+    hp.n_hint = d.n_hint > 0 ? d.n_hint : 1;
+    hp.flags = d.flags;
+    hp.dtype = d.dtype;
+    hp.taps = dense ? 9 : 4;
+    hp.num_patterns = dense ? 1 : d.num_patterns;
+    hp.masks.assign(hp.num_patterns, 0x1FF);
+    if (!dense) hp.masks.assign(d.pattern_masks, d.pattern_masks + d.num_patterns);
+    hp.bias.assign(d.c_out, 0.0f);
+    if (d.bias) hp.bias.assign(d.bias, d.bias + d.c_out);
+
+    const int P = hp.num_patterns, ci_n = d.c_in, co_n = d.c_out;
+    auto kept = [&](int co, int ci) { return !d.conn_mask || d.conn_mask[(int64_t)co * ci_n + ci] != 0; };
+    auto pat = [&](int co, int ci) { return dense ? 0 : d.pattern_id[(int64_t)co * ci_n + ci]; };
+
+    // per-filter pattern histograms
+    std::vector<int32_t> hist((size_t)co_n * P, 0), count(co_n, 0);
+    for (int co = 0; co < co_n; ++co)
+        for (int ci = 0; ci < ci_n; ++ci)
+            if (kept(co, ci)) {
+                ++hist[(size_t)co * P + pat(co, ci)];
+                ++count[co];
+            }
+    // filter order: heavier filters first (they set the critical path of a workgroup), equal
+    // counts ordered by pattern signature so that neighbours run the same code mix
+    Canonical& cn = hp.canon;
+    cn.perm.resize(co_n);
+    std::iota(cn.perm.begin(), cn.perm.end(), 0);
+    std::sort(cn.perm.begin(), cn.perm.end(), [&](int a, int b) {
+        if (count[a] != count[b]) return count[a] > count[b];
+        for (int p = 0; p < P; ++p) {
+            int ha = hist[(size_t)a * P + p], hb = hist[(size_t)b * P + p];
+            if (ha != hb) return ha > hb;
+        }
+        return a < b;
+    });
+    cn.k_kept = std::accumulate(count.begin(), count.end(), (int64_t)0);
+    cn.kcount.resize(co_n);
+    cn.pat_off.assign((size_t)co_n * (P + 1), 0);
+    cn.kidx.resize(cn.k_kept);
+    cn.kpat.resize(cn.k_kept);
+    cn.wpacked.resize((size_t)cn.k_kept * hp.taps);
+    // kernels of a filter: counting sort by pattern, channels ascending inside a pattern
+    int64_t base = 0;
+    std::vector<int32_t> cursor(P + 1);
+    for (int pos = 0; pos < co_n; ++pos) {
+        const int co = cn.perm[pos];
+        cn.kcount[pos] = count[co];
+        int32_t* po = &cn.pat_off[(size_t)pos * (P + 1)];
+        for (int p = 0; p < P; ++p) po[p + 1] = po[p] + hist[(size_t)co * P + p];
+        std::copy(po, po + P + 1, cursor.begin());
+        for (int ci = 0; ci < ci_n; ++ci) {
+            if (!kept(co, ci)) continue;
+            const int p = pat(co, ci);
+            const int64_t slot = base + cursor[p]++;
+            cn.kidx[slot] = ci;
+            cn.kpat[slot] = (uint8_t)p;
+            const float* src = d.weights + ((int64_t)co * ci_n + ci) * hp.taps;
+            std::copy(src, src + hp.taps, &cn.wpacked[(size_t)slot * hp.taps]);
+        }
+        base += count[co];
+    }
+    hp.filt_off.resize(co_n + 1);
+    hp.filt_off[0] = 0;
+    for (int pos = 0; pos < co_n; ++pos) hp.filt_off[pos + 1] = hp.filt_off[pos] + cn.kcount[pos];
+    hp.tap_dyx.clear();
+    for (int p = 0; p < P; ++p)
+        for (int t = 0; t < 9; ++t)
+            if ((hp.masks[p] >> t) & 1u) {
+                hp.tap_dyx.push_back((int8_t)(t / 3 - 1));
+                hp.tap_dyx.push_back((int8_t)(t % 3 - 1));
+            }
+}
+
+namespace {
+
+bool valid_lw(int lw) { return lw == 2 || lw == 4 || lw == 7 || lw == 8 || lw == 14 || lw == 16; }
+
+int pick_lw(int w) {
+    const int cand[] = {16, 14, 8, 7, 4, 2};
+    int best = 16;
+    double best_waste = 1e30;
+    for (int lw : cand) {
+        int tw = lw * kPW;
+        int strips = (w + tw - 1) / tw;
+        double waste = (double)strips * tw / w;
+        if (waste < best_waste - 1e-9) {
+            best_waste = waste;
+            best = lw;
+        }
+    }
+    return best;
+}
+
+int64_t spatial_waves(int n, int h, int w, int lw, int r) {
+    int64_t vh = (int64_t)n * (h + 1) - 1;
+    int64_t mrows = (vh + r - 1) / r;
+    int strips = (w + lw * kPW - 1) / (lw * kPW);
+    return strips * ((mrows * lw + 63) / 64);
+}
+
+}  // namespace
+
+pp_status_t build_layouts(const pp_conv_desc_t& d, HostPlan& hp) {
+    pp_conv_tuning_t t{};
+    if (d.tuning) t = *d.tuning;
+    if (t.variant < 0 || t.variant > 2) return PP_ERR_UNSUPPORTED;
+
+    // can the tiled kernel express this layer's pattern table?
+    std::vector<int> slot_of(hp.num_patterns, -1);
+    bool builtin = (hp.taps == 4);
+    int max_slot = -1;
+    if (builtin) {
+        std::vector<char> used(hp.num_patterns, 0);
+        for (uint8_t p : hp.canon.kpat) used[p] = 1;
+        for (int p = 0; p < hp.num_patterns; ++p) {
+            slot_of[p] = builtin_slot(hp.masks[p]);
+            if (used[p] && slot_of[p] < 0) builtin = false;
+            if (used[p]) max_slot = std::max(max_slot, slot_of[p]);
+        }
+    }
+    if (t.variant == 2 && !builtin) return PP_ERR_UNSUPPORTED;
+    hp.tiled = builtin && t.variant != 1;
+    hp.chosen = pp_conv_tuning_t{};
+    hp.chosen.variant = hp.tiled ? 2 : 1;
+    if (!hp.tiled) return PP_OK;
+
+    TiledLayout& tl = hp.tl;
+    const int eb = hp.dtype == PP_F16 ? 2 : 4;
+    tl.np = max_slot < 8 ? 8 : 16;
+    tl.entry_words = 8;
+
+    // ---- parameters ("tuning-decided parameters" of the layer-wise representation) ----
+    tl.lw = t.lanes_x ? t.lanes_x : pick_lw(hp.w);
+    if (!valid_lw(tl.lw)) return PP_ERR_UNSUPPORTED;
+    tl.f = t.filters_per_wave ? t.filters_per_wave : 8;
+    if (tl.f != 4 && tl.f != 8 && tl.f != 16) return PP_ERR_UNSUPPORTED;
+    if (tl.f * tl.np > 256) return PP_ERR_UNSUPPORTED;
+    const int groups_f = (hp.c_out + tl.f - 1) / tl.f;
+    tl.r = t.rows_per_lane;
+    if (tl.r == 0) tl.r = spatial_waves(hp.n_hint, hp.h, hp.w, tl.lw, 2) * groups_f >= 2048 ? 2 : 1;
+    if (tl.r != 1 && tl.r != 2) return PP_ERR_UNSUPPORTED;
+    const int64_t base_waves = spatial_waves(hp.n_hint, hp.h, hp.w, tl.lw, tl.r) * groups_f;
+    tl.ks = t.split_c;
+    if (tl.ks == 0) {
+        tl.ks = 1;
+        while (tl.ks < 8 && base_waves * tl.ks < 2048 && hp.c_in >= 16 * tl.ks) tl.ks *= 2;
+    }
+    if (tl.ks < 1 || tl.ks > 16) return PP_ERR_UNSUPPORTED;
+    tl.wf = t.waves_f;
+    if (tl.wf == 0) {
+        tl.wf = std::min(groups_f, std::max(1, 32 / tl.f));
+        while (tl.wf * tl.ks > 16) tl.wf = std::max(1, tl.wf / 2);
+    }
+    if (tl.wf < 1 || tl.wf * tl.ks > 16) return PP_ERR_UNSUPPORTED;
+    // the split-channel partial sums are exchanged through LDS: wf * f * r * 4 accumulators * 64 lanes
+    auto reduce_bytes = [&]() { return tl.ks > 1 ? tl.wf * tl.f * tl.r * 4 * 64 * 4 : 0; };
+    while (!t.waves_f && tl.wf > 1 && reduce_bytes() > 60 * 1024) tl.wf /= 2;
+    if (reduce_bytes() > 60 * 1024) return PP_ERR_UNSUPPORTED;
+    const TileGeom tg = tile_geom(tl.lw, tl.r, eb);
+    tl.cc = t.chunk_c;
+    if (tl.cc == 0) {
+        int fit = (32 * 1024) / (tg.chs * eb);
+        fit = std::min(fit, 32);
+        fit = std::min(fit, (hp.c_in + tl.ks - 1) / tl.ks * tl.ks);
+        tl.cc = std::max(tl.ks, fit / tl.ks * tl.ks);
+    }
+    if (tl.cc < tl.ks || tl.cc % tl.ks != 0 || tl.cc > 64) return PP_ERR_UNSUPPORTED;
+    if ((int64_t)tl.cc * tg.chs * eb > 60 * 1024) return PP_ERR_UNSUPPORTED;
+    tl.groups = groups_f;
+    tl.chunks = (hp.c_in + tl.cc - 1) / tl.cc;
+    hp.chosen.filters_per_wave = tl.f;
+    hp.chosen.rows_per_lane = tl.r;
+    hp.chosen.lanes_x = tl.lw;
+    hp.chosen.waves_f = tl.wf;
+    hp.chosen.split_c = tl.ks;
+    hp.chosen.chunk_c = tl.cc;
+
+    // ---- weight stream: one sequence of entries per (filter group, channel split) wavefront ----
+    const Canonical& cn = hp.canon;
+    const int G = tl.groups, F = tl.f, KS = tl.ks, CC = tl.cc, Q = tl.chunks, CS = CC / KS, EW = tl.entry_words;
+    tl.perm_pad.assign((size_t)G * F, -1);
+    tl.bias_pad.assign((size_t)G * F, 0.0f);
+    for (int pos = 0; pos < hp.c_out; ++pos) {
+        tl.perm_pad[pos] = cn.perm[pos];
+        tl.bias_pad[pos] = hp.bias[cn.perm[pos]];
+    }
+    struct Item { int32_t ci; int32_t fl; int32_t slot; int64_t src; };
+    tl.stream.clear();
+    tl.wave_off.assign((size_t)G * KS, 0);
+    std::vector<Item> items;
+    auto push_entry = [&](uint32_t header, const float* w4) {
+        size_t at = tl.stream.size();
+        tl.stream.resize(at + EW, 0u);
+        tl.stream[at] = header;
+        if (!w4) return;
+        float wv[4] = {w4[0], w4[1], w4[2], w4[3]};
+        if (hp.dtype == PP_F16)      // binary16 storage: the stream carries the rounded values, widened
+            for (float& v : wv) v = f16_to_f32(f32_to_f16_rne(v));
+        std::memcpy(&tl.stream[at + 4], wv, 16);
+    };
+    for (int g = 0; g < G; ++g) {
+        items.clear();
+        for (int fl = 0; fl < F; ++fl) {
+            int pos = g * F + fl;
+            if (pos >= hp.c_out) break;
+            for (int64_t e = hp.filt_off[pos]; e < hp.filt_off[pos + 1]; ++e)
+                items.push_back(Item{cn.kidx[e], fl, slot_of[cn.kpat[e]], e});
+        }
+        std::sort(items.begin(), items.end(), [](const Item& a, const Item& b) {
+            if (a.ci != b.ci) return a.ci < b.ci;
+            return a.fl < b.fl;
+        });
+        for (int s = 0; s < KS; ++s) {
+            tl.wave_off[(size_t)g * KS + s] = (int32_t)(tl.stream.size() / EW);
+            size_t it = 0;
+            for (int q = 0; q < Q; ++q) {
+                const int lo = q * CC + s * CS, hi = lo + CS;      // this wavefront's channels of chunk q
+                while (it < items.size() && items[it].ci < lo) ++it;
+                size_t j = it;
+                int prev_ci = -1;
+                for (; j < items.size() && items[j].ci < hi; ++j) {
+                    const Item& k = items[j];
+                    uint32_t header = (uint32_t)(k.fl * tl.np + k.slot);
+                    if (k.ci != prev_ci) header |= kFlagNewChannel;
+                    header |= (uint32_t)(k.ci - q * CC) << kChanShift;
+                    prev_ci = k.ci;
+                    push_entry(header, &cn.wpacked[(size_t)k.src * 4]);
+                }
+                push_entry(kFlagEnd, nullptr);
+            }
+        }
+    }
+    push_entry(kFlagEnd, nullptr);     // the walker prefetches one entry ahead
+    if (tl.stream.size() / EW >= ((size_t)1 << 31)) return PP_ERR_SHAPE;
+    return PP_OK;
+}
+
+pp_status_t unpack_stream(const HostPlan& hp, int32_t* kidx, uint8_t* kpat, float* w) {
+    if (!hp.tiled) return PP_ERR_UNSUPPORTED;
+    const TiledLayout& tl = hp.tl;
+    const int EW = tl.entry_words;
+    // slot -> lowest pattern id carrying that mask
+    std::vector<int> pid_of(kBuiltinPatterns, -1);
+    for (int p = hp.num_patterns - 1; p >= 0; --p) {
+        int s = builtin_slot(hp.masks[p]);
+        if (s >= 0) pid_of[s] = p;
+    }
+    struct Rec { int pat, ci; float w[4]; };
+    std::vector<std::vector<Rec>> per_filter(hp.c_out);
+    for (int g = 0; g < tl.groups; ++g)
+        for (int s = 0; s < tl.ks; ++s) {
+            size_t e = (size_t)tl.wave_off[(size_t)g * tl.ks + s];
+            for (int q = 0; q < tl.chunks; ++q) {
+                int ci = -1;
+                for (;; ++e) {
+                    const uint32_t* ent = &tl.stream[e * EW];
+                    if (ent[0] & kFlagEnd) {
+                        ++e;
+                        break;
+                    }
+                    if (ent[0] & kFlagNewChannel) ci = q * tl.cc + (int)(ent[0] >> kChanShift);
+                    int code = (int)(ent[0] & kCodeMask);
+                    int pos = g * tl.f + code / tl.np;
+                    if (pos >= hp.c_out || ci < 0) return PP_ERR_UNSUPPORTED;
+                    Rec r;
+                    r.pat = pid_of[code % tl.np];
+                    r.ci = ci;
+                    std::memcpy(r.w, &ent[4], 16);
+                    per_filter[pos].push_back(r);
+                }
+            }
+        }
+    int64_t out = 0;
+    for (int pos = 0; pos < hp.c_out; ++pos) {
+        auto& v = per_filter[pos];
+        std::sort(v.begin(), v.end(), [](const Rec& a, const Rec& b) {
+            if (a.pat != b.pat) return a.pat < b.pat;
+            return a.ci < b.ci;
+        });
+        for (const Rec& r : v) {
+            if (out >= hp.canon.k_kept) return PP_ERR_UNSUPPORTED;
+            kidx[out] = r.ci;
+            kpat[out] = (uint8_t)r.pat;
+            std::memcpy(&w[out * 4], r.w, 16);
+            ++out;
+        }
+    }
+    return out == hp.canon.k_kept ? PP_OK : PP_ERR_UNSUPPORTED;
+}
+
+}  // namespace ppc

@@ -1,0 +1,204 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU checker on the same seeded inputs.
+
+Tolerances (max over outputs of |gpu - ref| / max(|ref|, rms of the reference pre-activations)):
+1e-5 for fp32 storage, 2e-3 for fp16 storage with fp32 accumulation.  Plan metadata is compared
+bit-exactly in the host tests."""
+import copy
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+import paper_2206_10620_amd as pp
+from gpu_util import check_layer, run_layer, to_device
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def T(**kw):
+    return pp.Tuning(**kw)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+@pytest.mark.parametrize("relu", [True, False])
+def test_config1_small_layer(seed, relu):
+    lay = synth.config1(seed)
+    say(f"config1 seed={seed} relu={relu}")
+    rep, _ = check_layer(lay, relu=relu, label="cfg1")
+    say(f"  E={rep['E']:.2e} {rep['chosen']}")
+
+
+@pytest.mark.parametrize("relu", [True, False])
+def test_config1_generic_kernel(relu):
+    lay = synth.config1(0)
+    rep, _ = check_layer(lay, tuning=T(variant=1), relu=relu, label="cfg1-generic")
+    assert rep["chosen"]["variant"] == 1
+
+
+# (n, c_in, c_out, h, w): ragged widths, single rows/columns, channel counts that are not multiples of
+# the chunk, filter counts that are not multiples of the filters per wave, several images per tile.
+SHAPES = [(1, 3, 5, 1, 1), (2, 5, 9, 1, 7), (3, 4, 4, 9, 1), (2, 7, 13, 7, 7), (3, 9, 10, 14, 14), (1, 6, 6, 5, 30),
+          (2, 10, 17, 11, 33), (1, 19, 8, 28, 28), (5, 8, 24, 3, 56), (1, 12, 8, 20, 130), (2, 33, 40, 6, 64)]
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_ragged_shapes(shape, dtype):
+    n, c_in, c_out, h, w = shape
+    say(f"ragged {shape} {dtype}")
+    lay = synth.random_pruned_layer("ragged", n, c_in, c_out, h, w, dtype, synth.PSET16, 0.6, 0.3, seed=n + w)
+    for relu in (True, False):
+        rep, _ = check_layer(lay, relu=relu, label=f"ragged{shape}")
+    say(f"  E={rep['E']:.2e} {rep['chosen']}")
+
+
+TUNINGS = [dict(filters_per_wave=4, rows_per_lane=1, lanes_x=2), dict(filters_per_wave=8, rows_per_lane=2, lanes_x=4),
+           dict(filters_per_wave=16, rows_per_lane=1, lanes_x=7), dict(filters_per_wave=8, rows_per_lane=2, lanes_x=8),
+           dict(filters_per_wave=4, rows_per_lane=2, lanes_x=14), dict(filters_per_wave=8, rows_per_lane=1, lanes_x=16),
+           dict(filters_per_wave=8, rows_per_lane=2, lanes_x=16, waves_f=2, split_c=4, chunk_c=8),
+           dict(filters_per_wave=4, rows_per_lane=1, lanes_x=8, waves_f=1, split_c=8, chunk_c=16),
+           dict(filters_per_wave=8, rows_per_lane=2, lanes_x=7, waves_f=3, split_c=2, chunk_c=6),
+           dict(filters_per_wave=8, rows_per_lane=1, lanes_x=14, waves_f=16, split_c=1, chunk_c=1)]
+
+
+@pytest.mark.parametrize("tune", TUNINGS)
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_every_tile_geometry(tune, dtype):
+    say(f"tuning {tune} {dtype}")
+    for (n, c_in, c_out, h, w) in [(2, 21, 37, 19, 45), (3, 16, 16, 8, 8)]:
+        lay = synth.random_pruned_layer("tune", n, c_in, c_out, h, w, dtype, synth.PSET16, 0.5, 0.3, seed=7)
+        rep, _ = check_layer(lay, tuning=T(variant=2, **tune), label=f"tune{tune}")
+        for k, v in tune.items():
+            assert rep["chosen"][k] == v
+    say(f"  E={rep['E']:.2e}")
+
+
+def test_degenerate_sparsity():
+    base = synth.random_pruned_layer("deg", 2, 12, 20, 10, 12, "f32", synth.PSET8, 0.5, 0.3, seed=3)
+    # empty mask: bias only
+    lay = copy.copy(base)
+    lay.conn_mask = np.zeros_like(base.conn_mask)
+    _, y = check_layer(lay, relu=False, label="empty")
+    assert np.array_equal(y, np.broadcast_to(base.bias[None, :, None, None], y.shape))
+    # some empty filters, one full filter
+    lay = copy.copy(base)
+    m = base.conn_mask.copy().reshape(20, 12)
+    m[[0, 7, 19]] = 0
+    m[4] = 1
+    lay.conn_mask = m.reshape(-1)
+    check_layer(lay, label="empty-filters")
+    # a single pattern everywhere; and every pattern present in one filter
+    lay = copy.copy(base)
+    lay.pattern_id = np.full_like(base.pattern_id, 5)
+    check_layer(lay, label="single-pattern")
+    lay = copy.copy(base)
+    lay.conn_mask = np.ones_like(base.conn_mask)
+    lay.pattern_id = (np.arange(base.pattern_id.size) % 8).astype(np.int32)
+    check_layer(lay, label="all-kept")
+    # no bias
+    lay = copy.copy(base)
+    lay.bias = None
+    check_layer(lay, label="no-bias")
+
+
+def test_foreign_patterns_and_dense_layer():
+    lay = synth.random_pruned_layer("foreign", 2, 6, 10, 9, 11, "f32", np.array([0x00F, 0x1E0, 0x03A, 0x145], dtype=np.uint16),
+                                    0.7, 0.3, seed=1)
+    rep, _ = check_layer(lay, label="foreign")
+    assert rep["chosen"]["variant"] == 1
+    for dtype in ("f32", "f16"):
+        lay = synth.dense_layer("dense", 2, 3, 16, 12, 20, dtype, 0.3, seed=2)
+        rep, _ = check_layer(lay, label="dense")
+
+
+def test_filter_reordering_invariance_and_determinism():
+    lay = synth.random_pruned_layer("perm", 2, 16, 24, 12, 16, "f32", synth.PSET8, 0.5, 0.3, seed=11)
+    x = lay.make_input()
+    y1, _ = run_layer(lay, x)
+    y2, _ = run_layer(lay, x)
+    assert np.array_equal(y1, y2)                              # no atomics: runs are bit-identical
+    perm = np.random.RandomState(0).permutation(24)
+    rows = (perm[:, None] * 16 + np.arange(16)[None, :]).reshape(-1)
+    lay2 = copy.copy(lay)
+    lay2.pattern_id, lay2.conn_mask, lay2.weights, lay2.bias = lay.pattern_id[rows], lay.conn_mask[rows], lay.weights[rows], lay.bias[perm]
+    y3, _ = run_layer(lay2, x)
+    assert np.array_equal(y3, y1[:, perm])                     # same per-filter summation order: bit-identical
+    # waves per workgroup and filters per wave do not change any output's summation order either
+    y4, _ = run_layer(lay, x, tuning=T(variant=2, filters_per_wave=4, waves_f=3))
+    assert np.array_equal(y4, y1)
+
+
+def test_maxpool():
+    for dt, tdt in ((np.float32, 0), (np.float16, 1)):
+        x = np.random.RandomState(2).standard_normal((3, 5, 8, 12)).astype(dt)
+        xd = to_device(x)
+        yd = torch.empty((3, 5, 4, 6), dtype=xd.dtype, device="cuda")
+        assert pp.pp_maxpool2x2_run(xd.data_ptr(), yd.data_ptr(), 3, 5, 8, 12, tdt, torch.cuda.current_stream().cuda_stream) == pp.PP_OK
+        torch.cuda.synchronize()
+        assert np.array_equal(yd.cpu().numpy().astype(np.float64), oracle.maxpool2(x.astype(np.float64)))
+
+
+# ---- the benchmark configurations at full size -------------------------------------------------
+
+def test_config2_full_size():
+    lay = synth.config2()
+    say("config2")
+    for relu in (True, False):
+        rep, _ = check_layer(lay, relu=relu, label="cfg2")
+    say(f"  E={rep['E']:.2e} E_scale={rep['E_scale']:.2e} {rep['chosen']}")
+
+
+@pytest.mark.parametrize("batch", [1, 32])
+def test_config3_resnet_shapes(batch):
+    for lay in synth.config3(batch):
+        say(lay.name)
+        for relu in (True, False):
+            rep, _ = check_layer(lay, relu=relu, label="cfg3")
+        say(f"  E={rep['E']:.2e} E_scale={rep['E_scale']:.2e} {rep['chosen']}")
+
+
+def test_config4_vgg_stack_per_layer():
+    """Each layer is gated on its own: the checker is fed the GPU's input to that layer."""
+    layers = synth.config4()
+    x = layers[0].make_input()
+    xd = to_device(x)
+    stream = torch.cuda.current_stream().cuda_stream
+    for lay in layers:
+        say(lay.name)
+        plan = pp.plan_from_layer(lay)
+        yd = plan.run(xd)
+        torch.cuda.synchronize()
+        plan.close()
+        x_np, y_np = xd.cpu().numpy(), yd.cpu().numpy()
+        wd = oracle.layer_dense_weights(lay)
+        from oracle.compare import error_report, sample_points, TOL
+        pts = sample_points(lay.n, lay.c_out, lay.h, lay.w, 2048, seed=lay.seed)
+        ref, pre, scale = oracle.conv_at(x_np, wd, pts, lay.bias, lay.relu)
+        rep = error_report(y_np[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]], ref, pre, scale)
+        say(f"  E={rep['E']:.2e} sigma={rep['sigma']:.3f}")
+        assert rep["E"] <= TOL["f16"], (lay.name, rep)
+        if lay.meta["pool_after"]:
+            pd = torch.empty((lay.n, lay.c_out, lay.h // 2, lay.w // 2), dtype=yd.dtype, device="cuda")
+            assert pp.pp_maxpool2x2_run(yd.data_ptr(), pd.data_ptr(), lay.n, lay.c_out, lay.h, lay.w, pp.PP_F16, stream) == pp.PP_OK
+            torch.cuda.synchronize()
+            xd = pd
+        else:
+            xd = yd
+    assert tuple(xd.shape) == (8, 512, 14, 14)
+
+
+def test_config5_large_image():
+    lay = synth.config5()
+    say("config5")
+    x = lay.make_input()
+    for relu in (True, False):
+        rep, _ = check_layer(lay, x, relu=relu, points=8192, label="cfg5")
+    say(f"  E={rep['E']:.2e} {rep['chosen']}")
