@@ -90,6 +90,7 @@ def main():
     ap.add_argument("--workload", default="cfg2_vgg_mid")
     ap.add_argument("--all", action="store_true", help="also time the other benchmark layers (reported under 'others')")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-baseline leg and the parity check")
+    ap.add_argument("--tuning", default="", help="f,r,wf,ks,cc overrides for the timed workload (0 = automatic)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this library runs on ONE GPU (no collectives, no sharding); run with --gpus 1")
@@ -102,7 +103,11 @@ def main():
 
     table = workloads()
     lay = table[args.workload]()
-    t = time_layer(lay, args.steps, args.warmup)
+    tuning = None
+    if args.tuning:
+        f, r, wf, ks, cc = (int(v) for v in args.tuning.split(","))
+        tuning = pp.Tuning(variant=2, filters_per_wave=f, rows_per_lane=r, waves_f=wf, split_c=ks, chunk_c=cc)
+    t = time_layer(lay, args.steps, args.warmup, tuning)
     s = summarize(lay, t)
     sec_wall = t["wall_ms_per_step"] * 1e-3
 

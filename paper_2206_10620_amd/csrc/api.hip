@@ -13,20 +13,32 @@ namespace ppc {
 
 k1_launch_fn k1_lookup_f32_p8_r1(int f, int lw);
 k1_launch_fn k1_lookup_f32_p8_r2(int f, int lw);
+k1_launch_fn k1_lookup_f32_p8_r4(int f, int lw);
 k1_launch_fn k1_lookup_f32_p16_r1(int f, int lw);
 k1_launch_fn k1_lookup_f32_p16_r2(int f, int lw);
+k1_launch_fn k1_lookup_f32_p16_r4(int f, int lw);
 k1_launch_fn k1_lookup_f16_p8_r1(int f, int lw);
 k1_launch_fn k1_lookup_f16_p8_r2(int f, int lw);
+k1_launch_fn k1_lookup_f16_p8_r4(int f, int lw);
 k1_launch_fn k1_lookup_f16_p16_r1(int f, int lw);
 k1_launch_fn k1_lookup_f16_p16_r2(int f, int lw);
+k1_launch_fn k1_lookup_f16_p16_r4(int f, int lw);
 
 k1_launch_fn k1_lookup(int dtype, int np, int r, int f, int lw) {
-    if (dtype == PP_F32) {
-        if (np == 8) return r == 1 ? k1_lookup_f32_p8_r1(f, lw) : k1_lookup_f32_p8_r2(f, lw);
-        return r == 1 ? k1_lookup_f32_p16_r1(f, lw) : k1_lookup_f32_p16_r2(f, lw);
+#define PPC_PICK(DT, NP)                                   \
+    switch (r) {                                           \
+        case 1: return k1_lookup_##DT##_p##NP##_r1(f, lw); \
+        case 2: return k1_lookup_##DT##_p##NP##_r2(f, lw); \
+        case 4: return k1_lookup_##DT##_p##NP##_r4(f, lw); \
+        default: return nullptr;                           \
     }
-    if (np == 8) return r == 1 ? k1_lookup_f16_p8_r1(f, lw) : k1_lookup_f16_p8_r2(f, lw);
-    return r == 1 ? k1_lookup_f16_p16_r1(f, lw) : k1_lookup_f16_p16_r2(f, lw);
+    if (dtype == PP_F32) {
+        if (np == 8) { PPC_PICK(f32, 8) }
+        PPC_PICK(f32, 16)
+    }
+    if (np == 8) { PPC_PICK(f16, 8) }
+    PPC_PICK(f16, 16)
+#undef PPC_PICK
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -137,7 +149,7 @@ void free_device(pp_conv_plan_t* p) {
 
 int staging_vec(int w, int tw, int elem_bytes) {
     int v = 16 / elem_bytes;
-    while (v > 1 && (w % v != 0 || tw % v != 0)) v /= 2;
+    while (v > 1 && (w % v != 0 || tw % v != 0 || tw / v < 2)) v /= 2;
     return v;
 }
 

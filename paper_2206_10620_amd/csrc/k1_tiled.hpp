@@ -68,14 +68,62 @@ template <typename T, int N> __device__ __forceinline__ T vec_elem(const typenam
     else return v[i];
 }
 
-// A lane's input window for one channel: rows 0..R+1, columns -1..4.
-template <typename T, int R> struct Window {
-    typename VecOf<T, 4>::type mid[R + 2];    // columns 0..3
-    typename VecOf<T, 2>::type halo[R + 2];   // (column -1, column 4)
-    template <int ROW, int COL> __device__ __forceinline__ float get() const {
-        if constexpr (COL < 0) return (float)halo[ROW][0];
-        else if constexpr (COL > 3) return (float)halo[ROW][1];
-        else return (float)mid[ROW][COL];
+// A lane's input window for one channel: rows 0..R+1, columns -1..4, and the multiply-accumulate
+// of one of its elements with a wave-uniform weight.
+template <typename T, int R> struct Window;
+
+template <int R> struct Window<float, R> {
+    f32x4 mid[R + 2];    // columns 0..3
+    f32x2 halo[R + 2];   // (column -1, column 4)
+    __device__ __forceinline__ void clear() {
+#pragma unroll
+        for (int rr = 0; rr < R + 2; ++rr) {
+            mid[rr] = f32x4(0);
+            halo[rr] = f32x2(0);
+        }
+    }
+    __device__ __forceinline__ void load(const float* pm, const float* ph, int rs) {
+#pragma unroll
+        for (int rr = 0; rr < R + 2; ++rr) {
+            mid[rr] = *reinterpret_cast<const f32x4*>(pm + rr * rs);
+            halo[rr] = *reinterpret_cast<const f32x2*>(ph + rr * rs);
+        }
+    }
+    template <int ROW, int COL> __device__ __forceinline__ void fma(float& acc, float w) const {
+        if constexpr (COL < 0) acc = __builtin_fmaf(w, halo[ROW][0], acc);
+        else if constexpr (COL > 3) acc = __builtin_fmaf(w, halo[ROW][1], acc);
+        else acc = __builtin_fmaf(w, mid[ROW][COL], acc);
+    }
+};
+
+// fp16 storage: the window stays packed, two halves per register, and every multiply-accumulate
+// is one v_fma_mix_f32 (fp16 input selected from the low or high half, fp32 weight from a scalar
+// register, fp32 accumulator).  Written as inline assembly because the compiler otherwise
+// unpacks halves that are used several times with extra conversion instructions.
+template <int R> struct Window<_Float16, R> {
+    uint32_t mid[R + 2][2];   // columns (0,1), (2,3)
+    uint32_t halo[R + 2];     // (column -1, column 4)
+    __device__ __forceinline__ void clear() {
+#pragma unroll
+        for (int rr = 0; rr < R + 2; ++rr) mid[rr][0] = mid[rr][1] = halo[rr] = 0u;
+    }
+    __device__ __forceinline__ void load(const _Float16* pm, const _Float16* ph, int rs) {
+        typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+        for (int rr = 0; rr < R + 2; ++rr) {
+            const u32x2 m = *reinterpret_cast<const u32x2*>(pm + rr * rs);
+            mid[rr][0] = m[0];
+            mid[rr][1] = m[1];
+            halo[rr] = *reinterpret_cast<const uint32_t*>(ph + rr * rs);
+        }
+    }
+    template <int ROW, int COL> __device__ __forceinline__ void fma(float& acc, float w) const {
+        constexpr bool hi = (COL < 0) ? false : (COL > 3) ? true : (COL & 1) != 0;
+        const uint32_t src = (COL < 0 || COL > 3) ? halo[ROW] : mid[ROW][(COL < 0 ? 0 : COL) >> 1];
+        if constexpr (hi)
+            asm("v_fma_mix_f32 %0, %1, %2, %0 op_sel:[0,1,0] op_sel_hi:[0,1,0]" : "+v"(acc) : "s"(w), "v"(src));
+        else
+            asm("v_fma_mix_f32 %0, %1, %2, %0 op_sel_hi:[0,1,0]" : "+v"(acc) : "s"(w), "v"(src));
     }
 };
 
@@ -84,17 +132,18 @@ template <typename T, int R> struct Window {
 template <typename T, int R, int F, int FS, int RR, int TAP>
 __device__ __forceinline__ void mac_row(float (&acc)[F][R][4], const Window<T, R>& win, float wj) {
     constexpr int dr = TAP / 3, dc = TAP % 3 - 1;
-    acc[FS][RR][0] = __builtin_fmaf(wj, win.template get<RR + dr, 0 + dc>(), acc[FS][RR][0]);
-    acc[FS][RR][1] = __builtin_fmaf(wj, win.template get<RR + dr, 1 + dc>(), acc[FS][RR][1]);
-    acc[FS][RR][2] = __builtin_fmaf(wj, win.template get<RR + dr, 2 + dc>(), acc[FS][RR][2]);
-    acc[FS][RR][3] = __builtin_fmaf(wj, win.template get<RR + dr, 3 + dc>(), acc[FS][RR][3]);
+    win.template fma<RR + dr, 0 + dc>(acc[FS][RR][0], wj);
+    win.template fma<RR + dr, 1 + dc>(acc[FS][RR][1], wj);
+    win.template fma<RR + dr, 2 + dc>(acc[FS][RR][2], wj);
+    win.template fma<RR + dr, 3 + dc>(acc[FS][RR][3], wj);
 }
 
-template <typename T, int R, int F, int FS, int TAP>
+template <typename T, int R, int F, int FS, int TAP, int RR = 0>
 __device__ __forceinline__ void mac_tap(float (&acc)[F][R][4], const Window<T, R>& win, float wj) {
-    static_assert(R == 1 || R == 2, "rows per lane");
-    mac_row<T, R, F, FS, 0, TAP>(acc, win, wj);
-    if constexpr (R > 1) mac_row<T, R, F, FS, 1, TAP>(acc, win, wj);
+    if constexpr (RR < R) {
+        mac_row<T, R, F, FS, RR, TAP>(acc, win, wj);
+        mac_tap<T, R, F, FS, TAP, RR + 1>(acc, win, wj);
+    }
 }
 
 constexpr int nth_tap(uint32_t mask, int j) {
@@ -132,60 +181,73 @@ __device__ __forceinline__ void dispatch(int code, float (&acc)[F][R][4], const 
 }
 
 // ---------------------------------------------------------------------------------------------
-// Stage the rows of one channel chunk into LDS (zero-filled outside the images), VEC elements
-// per global load.  Interior columns go to [row][0..TW), and the elements that are some
-// micro-tile's left/right neighbour are also written to that micro-tile's halo pair.
+// Stage one channel chunk into LDS (zero-filled outside the images), VEC elements per global
+// load.  The chunk is a list of ccn*trn tile rows of VPR vectors each; thread t takes vectors
+// t, t + nthreads, ...  Interior columns go to [row][0..TW); an element that is some micro-tile's
+// left or right neighbour is also written to that micro-tile's (left, right) halo pair, which
+// sits behind the interior at [row][HOFF + 2*mcol].  The pair array has one dummy pair on each
+// side so that these writes need no bounds test.  Loads are issued U at a time before any of
+// their LDS writes, and out-of-image vectors load a valid dummy address and are zeroed by a
+// select, so the loop body has no divergent branches.
 template <typename T, int VEC, int LW, int R>
 __device__ __forceinline__ void stage_chunk(const T* __restrict__ x, T* tile, const int* rowtab, int c0, int ccn,
-                                            int trn, int x0, int W, int64_t hw, int wave, int nwaves, int lane) {
+                                            int trn, uint32_t trn_magic, int x0, int W, int hw, int tid,
+                                            int nthreads) {
     constexpr TileGeom tg = tile_geom(LW, R, (int)sizeof(T));
-    constexpr int TW = tg.tw, VPR = TW / VEC, RS = tg.rs, CHS = tg.chs;
+    constexpr int TW = tg.tw, VPR = TW / VEC, RS = tg.rs, CHS = tg.chs, HOFF = tg.hoff;
     constexpr int U = 2;
+    static_assert(VPR >= 2, "a tile row must span at least two staging vectors");
     typedef typename VecOf<T, VEC>::type vec_t;
-    const int per_ch = trn * VPR;
-    for (int c = wave; c < ccn; c += nwaves) {
-        const T* xc = x + (int64_t)(c0 + c) * hw;
-        T* tc = tile + c * CHS;
-        for (int j0 = 0; j0 < per_ch; j0 += 64 * U) {
-            vec_t reg[U];
-            T edge_l[U], edge_r[U];
-            int dst[U];
+    const int total = ccn * trn * VPR;
+    const T* xc0 = x + (int64_t)c0 * hw;
+    for (int i0 = tid; i0 < total; i0 += nthreads * U) {
+        vec_t reg[U];
+        T edge[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int j = j0 + u * 64 + lane;
-                const int tr = j / VPR, v = j - tr * VPR;
-                dst[u] = -1;
-                reg[u] = vec_t(0);
-                edge_l[u] = T(0);
-                edge_r[u] = T(0);
-                if (j < per_ch) {
-                    dst[u] = tr * RS + v * VEC;
-                    const int rb = rowtab[tr];
-                    const int col = x0 + v * VEC;
-                    if (rb >= 0) {
-                        if (col < W) reg[u] = *reinterpret_cast<const vec_t*>(xc + (uint32_t)(rb + col));
-                        if (v == 0 && x0 > 0) edge_l[u] = xc[(uint32_t)(rb + x0 - 1)];
-                        if (v == VPR - 1 && x0 + TW < W) edge_r[u] = xc[(uint32_t)(rb + x0 + TW)];
-                    }
+        for (int u = 0; u < U; ++u) {
+            const int i = i0 + u * nthreads;
+            const int row = i / VPR, v = i - row * VPR;              // VPR is a compile-time constant
+            const int c = (int)__umulhi((uint32_t)row, trn_magic);   // row / trn (exact for row < 2^16)
+            const int tr = row - c * trn;
+            const bool live = i < total;
+            const int rb = live ? rowtab[tr] : -1;
+            const int col = x0 + v * VEC;
+            const bool in_img = rb >= 0;
+            const uint32_t chan = (uint32_t)(c * hw);
+            const uint32_t goff = (in_img && col < W) ? chan + (uint32_t)(rb + col) : 0u;
+            const vec_t val = *reinterpret_cast<const vec_t*>(xc0 + goff);
+            reg[u] = (in_img && col < W) ? val : vec_t(0);
+            // the two elements just outside the strip, fetched by the first / last vector of a row
+            const bool left = v == 0, right = v == VPR - 1;
+            const int ecol = left ? x0 - 1 : x0 + TW;
+            const bool e_ok = in_img && (left || right) && ecol >= 0 && ecol < W;
+            const T ev = xc0[e_ok ? chan + (uint32_t)(rb + ecol) : 0u];
+            edge[u] = e_ok ? ev : T(0);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int i = i0 + u * nthreads;
+            if (i >= total) continue;
+            const int row = i / VPR, v = i - row * VPR;
+            const int c = (int)__umulhi((uint32_t)row, trn_magic);
+            const int tr = row - c * trn;
+            T* trow = tile + c * CHS + tr * RS;
+            *reinterpret_cast<vec_t*>(trow + v * VEC) = reg[u];
+            T* hrow = trow + HOFF;
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) {
+                const int sc = v * VEC + k;
+                const T e = vec_elem<T, VEC>(reg[u], k);
+                if (VEC >= 4) {                                   // which elements are neighbours is static
+                    if ((k & 3) == 0) hrow[2 * (sc / 4 - 1) + 1] = e;
+                    if ((k & 3) == 3) hrow[2 * (sc / 4 + 1)] = e;
+                } else {
+                    if ((sc & 3) == 0) hrow[2 * (sc / 4 - 1) + 1] = e;
+                    if ((sc & 3) == 3) hrow[2 * (sc / 4 + 1)] = e;
                 }
             }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if (dst[u] < 0) continue;
-                const int j = j0 + u * 64 + lane;
-                const int tr = j / VPR, v = j - tr * VPR;
-                *reinterpret_cast<vec_t*>(tc + dst[u]) = reg[u];
-                T* hrow = tc + tr * RS + TW;
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) {
-                    const int sc = v * VEC + i;
-                    const T e = vec_elem<T, VEC>(reg[u], i);
-                    if ((sc & 3) == 0 && sc >= 4) hrow[2 * (sc / 4 - 1) + 1] = e;
-                    if ((sc & 3) == 3 && sc + 1 < TW) hrow[2 * (sc / 4 + 1)] = e;
-                }
-                if (v == 0) hrow[0] = edge_l[u];
-                if (v == VPR - 1) hrow[2 * (LW - 1) + 1] = edge_r[u];
-            }
+            if (v == 0) hrow[0] = edge[u];
+            if (v == VPR - 1) hrow[2 * (LW - 1) + 1] = edge[u];
         }
     }
 }
@@ -194,7 +256,7 @@ __device__ __forceinline__ void stage_chunk(const T* __restrict__ x, T* tile, co
 template <typename T, int NP, int R, int F, int LW>
 __global__ __launch_bounds__(1024) void k1_tiled(const K1Args a) {
     constexpr TileGeom tg = tile_geom(LW, R, (int)sizeof(T));
-    constexpr int TW = tg.tw, RS = tg.rs, CHS = tg.chs, ROWS = tg.rows;
+    constexpr int TW = tg.tw, RS = tg.rs, CHS = tg.chs, ROWS = tg.rows, HOFF = tg.hoff;
     constexpr int EW = 8;                           // 32-bit words per stream entry
     extern __shared__ __align__(16) unsigned char smem_raw[];
     __shared__ int rowtab[ROWS];
@@ -246,18 +308,18 @@ __global__ __launch_bounds__(1024) void k1_tiled(const K1Args a) {
             for (int k = 0; k < 4; ++k) acc[f][rr][k] = 0.0f;
 
     const T* lane_mid = tile + lr * R * RS + 4 * mcol;
-    const T* lane_halo = tile + lr * R * RS + TW + 2 * mcol;
-    const int64_t hw = (int64_t)a.h * a.w;
+    const T* lane_halo = tile + lr * R * RS + HOFF + 2 * mcol;
+    const int hw = a.h * a.w;
+    const uint32_t trn_magic = 0xFFFFFFFFu / (uint32_t)trn + 1u;      // ceil(2^32 / trn), trn >= 3
     const T* __restrict__ xin = static_cast<const T*>(a.x);
 
-    // this wavefront's entry stream
-    // (constant address space: wave-uniform loads from it are scalar loads)
-    typedef const __attribute__((address_space(4))) u32x4* stream_ptr_t;
+    // this wavefront's entry stream (constant address space: wave-uniform loads from it are scalar loads)
+    typedef const __attribute__((address_space(4))) uint32_t* stream_ptr_t;
     typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr_t;
-    const stream_ptr_t ent_base = (stream_ptr_t)(a.stream);
-    int e = has_group ? ((const_i32_ptr_t)a.wave_off)[g * a.ks + ksi] : 0;
-    u32x4 hd = ent_base[(int64_t)e * (EW / 4)];
-    u32x4 wq = ent_base[(int64_t)e * (EW / 4) + 1];
+    stream_ptr_t sp = (stream_ptr_t)(a.stream) + (int64_t)(has_group ? ((const_i32_ptr_t)a.wave_off)[g * a.ks + ksi] : 0) * EW;
+    // the next entry to execute, fetched one entry ahead so that the scalar-load latency hides
+    // behind the previous kernel's multiply-accumulates
+    uint32_t n_head = sp[0], n_w0 = sp[4], n_w1 = sp[5], n_w2 = sp[6], n_w3 = sp[7];
 
     for (int q = 0; q < a.chunks; ++q) {
         const int c0 = q * a.cc;
@@ -265,48 +327,39 @@ __global__ __launch_bounds__(1024) void k1_tiled(const K1Args a) {
         __syncthreads();          // previous chunk fully consumed (and rowtab written, first time round)
         switch (a.vec) {
             case 8:
-                if constexpr (sizeof(T) == 2 && LW % 2 == 0)
-                    stage_chunk<T, 8, LW, R>(xin, tile, rowtab, c0, ccn, trn, x0, a.w, hw, wave, nwaves, lane);
+                if constexpr (sizeof(T) == 2 && LW % 2 == 0 && LW >= 4)
+                    stage_chunk<T, 8, LW, R>(xin, tile, rowtab, c0, ccn, trn, trn_magic, x0, a.w, hw, threadIdx.x, blockDim.x);
                 break;
-            case 4: stage_chunk<T, 4, LW, R>(xin, tile, rowtab, c0, ccn, trn, x0, a.w, hw, wave, nwaves, lane); break;
-            case 2: stage_chunk<T, 2, LW, R>(xin, tile, rowtab, c0, ccn, trn, x0, a.w, hw, wave, nwaves, lane); break;
-            default: stage_chunk<T, 1, LW, R>(xin, tile, rowtab, c0, ccn, trn, x0, a.w, hw, wave, nwaves, lane); break;
+            case 4: stage_chunk<T, 4, LW, R>(xin, tile, rowtab, c0, ccn, trn, trn_magic, x0, a.w, hw, threadIdx.x, blockDim.x); break;
+            case 2: stage_chunk<T, 2, LW, R>(xin, tile, rowtab, c0, ccn, trn, trn_magic, x0, a.w, hw, threadIdx.x, blockDim.x); break;
+            default: stage_chunk<T, 1, LW, R>(xin, tile, rowtab, c0, ccn, trn, trn_magic, x0, a.w, hw, threadIdx.x, blockDim.x); break;
         }
         __syncthreads();
         if (!has_group) continue;
 
         Window<T, R> win;
-#pragma unroll
-        for (int rr = 0; rr < R + 2; ++rr) {
-            win.mid[rr] = typename VecOf<T, 4>::type(0);
-            win.halo[rr] = typename VecOf<T, 2>::type(0);
-        }
+        win.clear();
         for (;;) {
-            const uint32_t head = __builtin_amdgcn_readfirstlane(hd[0]);
-            float wt[4];
-            wt[0] = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(wq[0]));
-            wt[1] = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(wq[1]));
-            wt[2] = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(wq[2]));
-            wt[3] = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(wq[3]));
+            const uint32_t head = n_head;
+            const float wt[4] = {__builtin_bit_cast(float, n_w0), __builtin_bit_cast(float, n_w1),
+                                 __builtin_bit_cast(float, n_w2), __builtin_bit_cast(float, n_w3)};
             const bool at_end = (head & kFlagEnd) != 0;
             if (!at_end && (head & kFlagNewChannel)) {
                 const int cl = (int)(head >> kChanShift);
-                const T* pm = lane_mid + cl * CHS;
-                const T* ph = lane_halo + cl * CHS;
-#pragma unroll
-                for (int rr = 0; rr < R + 2; ++rr) {
-                    win.mid[rr] = *reinterpret_cast<const typename VecOf<T, 4>::type*>(pm + rr * RS);
-                    win.halo[rr] = *reinterpret_cast<const typename VecOf<T, 2>::type*>(ph + rr * RS);
-                }
+                win.load(lane_mid + cl * CHS, lane_halo + cl * CHS, RS);
                 // Wait for the window here, before the next entry's scalar load is issued: LDS reads
                 // and scalar loads share one counter, so a wait placed later (inside the kernel
                 // blocks) would also wait for that prefetch and expose its latency on every kernel.
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                // (0xC07F = lgkmcnt(0), vmcnt and expcnt unconstrained; the builtin, unlike inline
+                // assembly, is visible to the compiler's own wait-count bookkeeping)
+                __builtin_amdgcn_s_waitcnt(0xC07F);
             }
-            // prefetch the next entry (the stream is padded by one entry past the last wavefront)
-            ++e;
-            hd = ent_base[(int64_t)e * (EW / 4)];
-            wq = ent_base[(int64_t)e * (EW / 4) + 1];
+            sp += EW;                 // the stream is padded by one entry past the last wavefront
+            n_head = sp[0];
+            n_w0 = sp[4];
+            n_w1 = sp[5];
+            n_w2 = sp[6];
+            n_w3 = sp[7];
             if (at_end) break;
             dispatch<T, R, F, NP, 0, F * NP>((int)(head & kCodeMask), acc, win, wt);
         }

@@ -226,40 +226,50 @@ pp_status_t build_layouts(const pp_conv_desc_t& d, HostPlan& hp) {
     // ---- parameters ("tuning-decided parameters" of the layer-wise representation) ----
     tl.lw = t.lanes_x ? t.lanes_x : pick_lw(hp.w);
     if (!valid_lw(tl.lw)) return PP_ERR_UNSUPPORTED;
-    tl.f = t.filters_per_wave ? t.filters_per_wave : 8;
+    // Defaults measured on MI355X: four filters per wavefront keep the kernel under 64-80 vector
+    // registers (6-8 wavefronts per SIMD hide the scalar dispatch and the LDS latency); two output
+    // rows per lane when that still leaves a few thousand wavefronts, else one; 16 wavefronts per
+    // workgroup so that an input tile is staged once for 64 filters, some of them splitting the
+    // input channels instead when the layer is too small to fill the chip otherwise.
+    tl.f = t.filters_per_wave ? t.filters_per_wave : 4;
     if (tl.f != 4 && tl.f != 8 && tl.f != 16) return PP_ERR_UNSUPPORTED;
     if (tl.f * tl.np > 256) return PP_ERR_UNSUPPORTED;
     const int groups_f = (hp.c_out + tl.f - 1) / tl.f;
+    const int64_t want_waves = 3000;
     tl.r = t.rows_per_lane;
-    if (tl.r == 0) tl.r = spatial_waves(hp.n_hint, hp.h, hp.w, tl.lw, 2) * groups_f >= 2048 ? 2 : 1;
-    if (tl.r != 1 && tl.r != 2) return PP_ERR_UNSUPPORTED;
+    if (tl.r == 0) tl.r = spatial_waves(hp.n_hint, hp.h, hp.w, tl.lw, 2) * groups_f >= want_waves ? 2 : 1;
+    if (tl.r != 1 && tl.r != 2 && tl.r != 4) return PP_ERR_UNSUPPORTED;
+    if (tl.r == 4 && tl.f != 4) return PP_ERR_UNSUPPORTED;
+    const int max_waves = 16;                      // the kernel's launch bound
     const int64_t base_waves = spatial_waves(hp.n_hint, hp.h, hp.w, tl.lw, tl.r) * groups_f;
     tl.ks = t.split_c;
     if (tl.ks == 0) {
         tl.ks = 1;
-        while (tl.ks < 8 && base_waves * tl.ks < 2048 && hp.c_in >= 16 * tl.ks) tl.ks *= 2;
+        while (tl.ks < 4 && base_waves * tl.ks < want_waves && hp.c_in >= 32 * tl.ks) tl.ks *= 2;
     }
-    if (tl.ks < 1 || tl.ks > 16) return PP_ERR_UNSUPPORTED;
+    if (tl.ks < 1 || tl.ks > max_waves) return PP_ERR_UNSUPPORTED;
     tl.wf = t.waves_f;
     if (tl.wf == 0) {
-        tl.wf = std::min(groups_f, std::max(1, 32 / tl.f));
-        while (tl.wf * tl.ks > 16) tl.wf = std::max(1, tl.wf / 2);
+        tl.wf = std::max(1, std::min(groups_f, max_waves / tl.ks));
+        // do not let one workgroup's filter block leave most of the chip idle
+        while (tl.wf > 1 && spatial_waves(hp.n_hint, hp.h, hp.w, tl.lw, tl.r) * ((groups_f + tl.wf - 1) / tl.wf) < 200)
+            tl.wf /= 2;
     }
-    if (tl.wf < 1 || tl.wf * tl.ks > 16) return PP_ERR_UNSUPPORTED;
+    if (tl.wf < 1 || tl.wf * tl.ks > max_waves) return PP_ERR_UNSUPPORTED;
     // the split-channel partial sums are exchanged through LDS: wf * f * r * 4 accumulators * 64 lanes
     auto reduce_bytes = [&]() { return tl.ks > 1 ? tl.wf * tl.f * tl.r * 4 * 64 * 4 : 0; };
-    while (!t.waves_f && tl.wf > 1 && reduce_bytes() > 60 * 1024) tl.wf /= 2;
-    if (reduce_bytes() > 60 * 1024) return PP_ERR_UNSUPPORTED;
+    while (!t.waves_f && tl.wf > 1 && reduce_bytes() > kMaxDynamicLds) tl.wf /= 2;
+    if (reduce_bytes() > kMaxDynamicLds) return PP_ERR_UNSUPPORTED;
     const TileGeom tg = tile_geom(tl.lw, tl.r, eb);
     tl.cc = t.chunk_c;
     if (tl.cc == 0) {
-        int fit = (32 * 1024) / (tg.chs * eb);
+        int fit = kMaxDynamicLds / (tg.chs * eb);
         fit = std::min(fit, 32);
         fit = std::min(fit, (hp.c_in + tl.ks - 1) / tl.ks * tl.ks);
         tl.cc = std::max(tl.ks, fit / tl.ks * tl.ks);
     }
-    if (tl.cc < tl.ks || tl.cc % tl.ks != 0 || tl.cc > 64) return PP_ERR_UNSUPPORTED;
-    if ((int64_t)tl.cc * tg.chs * eb > 60 * 1024) return PP_ERR_UNSUPPORTED;
+    if (tl.cc < tl.ks || tl.cc % tl.ks != 0 || tl.cc > 512 || tl.cc * tg.rows >= 65536) return PP_ERR_UNSUPPORTED;
+    if ((int64_t)tl.cc * tg.chs * eb > kMaxDynamicLds) return PP_ERR_UNSUPPORTED;
     tl.groups = groups_f;
     tl.chunks = (hp.c_in + tl.cc - 1) / tl.cc;
     hp.chosen.filters_per_wave = tl.f;

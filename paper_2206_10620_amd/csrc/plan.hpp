@@ -74,10 +74,12 @@ float f16_to_f32(uint16_t b);
 
 // Static geometry of a tiled-kernel instantiation (shared by host packing and device code).
 constexpr int kPW = 4;      // output pixels per lane along the width
+constexpr int kMaxDynamicLds = 156 * 1024;   // dynamic LDS bytes a tiled-kernel workgroup may use (CU has 160 KB)
 struct TileGeom {
     int tw;        // tile width in pixels = lw * kPW
     int mrows;     // most micro-rows one wavefront's 64 micro-tiles can touch
     int rows;      // LDS tile rows = mrows * r + 2
+    int hoff;      // element offset, inside a tile row, of micro-column 0's (left, right) halo pair
     int rs;        // LDS row stride in elements
     int chs;       // LDS channel stride in elements
 };
@@ -86,9 +88,10 @@ constexpr TileGeom tile_geom(int lw, int r, int elem_bytes) {
     int mrows = (64 % lw == 0) ? 64 / lw : (64 + lw - 1) / lw + 1;
     int rows = mrows * r + 2;
     int vec = 16 / elem_bytes;                       // elements per 128-bit access
-    int rs = tw + 2 * lw;                            // interior then (left,right) halo pairs
+    int hoff = tw + 2;                               // interior, one dummy pair, lw pairs, one dummy pair
+    int rs = tw + 2 * (lw + 2);
     rs = (rs + vec - 1) / vec * vec;
-    return TileGeom{tw, mrows, rows, rs, rows * rs};
+    return TileGeom{tw, mrows, rows, hoff, rs, rows * rs};
 }
 
 }  // namespace ppc
