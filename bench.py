@@ -90,7 +90,10 @@ def main():
     ap.add_argument("--workload", default="cfg2_vgg_mid")
     ap.add_argument("--all", action="store_true", help="also time the other benchmark layers (reported under 'others')")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-baseline leg and the parity check")
-    ap.add_argument("--tuning", default="", help="f,r,wf,ks,cc overrides for the timed workload (0 = automatic)")
+    ap.add_argument("--copy-ref-mib", type=int, default=0,
+                    help="also launch one plain device copy of this many MiB (a reference dispatch for scaling "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
+    ap.add_argument("--tuning", default="", help="f,r,wf,ks,cc[,pipeline] overrides for the timed workload (0 = automatic)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this library runs on ONE GPU (no collectives, no sharding); run with --gpus 1")
@@ -101,11 +104,20 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
 
+    if args.copy_ref_mib > 0:
+        src = torch.ones(args.copy_ref_mib * (1 << 20) // 4, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                         # one elementwise copy kernel: reads and writes copy_ref_mib MiB
+        torch.cuda.synchronize()
+        del src, dst
+
     table = workloads()
     lay = table[args.workload]()
     tuning = None
     if args.tuning:
-        f, r, wf, ks, cc = (int(v) for v in args.tuning.split(","))
+        vals = [int(v) for v in args.tuning.split(",")] + [0]
+        f, r, wf, ks, cc, pl = vals[:6]
         tuning = pp.Tuning(variant=2, filters_per_wave=f, rows_per_lane=r, waves_f=wf, split_c=ks, chunk_c=cc)
     t = time_layer(lay, args.steps, args.warmup, tuning)
     s = summarize(lay, t)

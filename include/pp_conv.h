@@ -64,7 +64,7 @@ enum {
 typedef struct {
     int32_t variant;        /* 0 auto; 1 generic kernel (any pattern table); 2 tiled pattern-specialised kernel */
     int32_t filters_per_wave; /* F: output filters whose accumulators one wavefront holds (4, 8 or 16) */
-    int32_t rows_per_lane;  /* R: output rows per lane (1 or 2); a lane owns R x 4 adjacent output pixels */
+    int32_t rows_per_lane;  /* R: output rows per lane (1, 2, or 4 with F = 4); a lane owns R x 4 adjacent output pixels */
     int32_t lanes_x;        /* LW: lanes across the width of a tile (2, 4, 7, 8, 14 or 16) */
     int32_t waves_f;        /* WF: wavefronts per workgroup that share one input tile, each on its own F filters */
     int32_t split_c;        /* KS: wavefronts per workgroup that split the input channels of a chunk */

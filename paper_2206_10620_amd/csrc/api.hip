@@ -281,9 +281,14 @@ pp_status_t pp_conv_run(const pp_conv_plan_t* plan, const void* x_dev, void* y_d
     a.vec = staging_vec(hp.w, tg.tw, eb);
     a.relu = relu;
     const int nfb = (tl.groups + tl.wf - 1) / tl.wf;
-    const int64_t blocks = (int64_t)a.strips * a.wg_per_strip * nfb;
-    if (blocks >= ((int64_t)1 << 31)) return PP_ERR_SHAPE;
-    const int lds = k1_lds_bytes(tl.lw, tl.r, tl.f, tl.wf, tl.ks, tl.cc, eb);
+    const int64_t items = (int64_t)a.strips * a.wg_per_strip * nfb;
+    if (items >= ((int64_t)1 << 30)) return PP_ERR_SHAPE;
+    a.nfb = nfb;
+    a.work_items = (int)items;
+    a.blocks_per_xcd = (int)((items + 7) / 8);
+    const int64_t blocks = (int64_t)a.blocks_per_xcd * 8;
+    a.desc_offset = k1_desc_offset(tl.lw, tl.r, tl.f, tl.wf, tl.ks, tl.cc, eb);
+    const int lds = k1_lds_bytes(tl.lw, tl.r, tl.f, tl.wf, tl.ks, tl.cc, eb, a.vec);
     plan->launch(a, (int)blocks, 64 * tl.wf * tl.ks, lds, stream);
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_DEVICE;
 }

@@ -258,18 +258,18 @@ pp_status_t build_layouts(const pp_conv_desc_t& d, HostPlan& hp) {
     if (tl.wf < 1 || tl.wf * tl.ks > max_waves) return PP_ERR_UNSUPPORTED;
     // the split-channel partial sums are exchanged through LDS: wf * f * r * 4 accumulators * 64 lanes
     auto reduce_bytes = [&]() { return tl.ks > 1 ? tl.wf * tl.f * tl.r * 4 * 64 * 4 : 0; };
-    while (!t.waves_f && tl.wf > 1 && reduce_bytes() > kMaxDynamicLds) tl.wf /= 2;
-    if (reduce_bytes() > kMaxDynamicLds) return PP_ERR_UNSUPPORTED;
+    while (!t.waves_f && tl.wf > 1 && reduce_bytes() > kMaxDynamicLds - kStageDescBytesMax) tl.wf /= 2;
+    if (reduce_bytes() > kMaxDynamicLds - kStageDescBytesMax) return PP_ERR_UNSUPPORTED;
     const TileGeom tg = tile_geom(tl.lw, tl.r, eb);
     tl.cc = t.chunk_c;
     if (tl.cc == 0) {
-        int fit = kMaxDynamicLds / (tg.chs * eb);
+        int fit = (kMaxDynamicLds - kStageDescBytesMax) / (tg.chs * eb);
         fit = std::min(fit, 32);
         fit = std::min(fit, (hp.c_in + tl.ks - 1) / tl.ks * tl.ks);
         tl.cc = std::max(tl.ks, fit / tl.ks * tl.ks);
     }
     if (tl.cc < tl.ks || tl.cc % tl.ks != 0 || tl.cc > 512 || tl.cc * tg.rows >= 65536) return PP_ERR_UNSUPPORTED;
-    if ((int64_t)tl.cc * tg.chs * eb > kMaxDynamicLds) return PP_ERR_UNSUPPORTED;
+    if ((int64_t)tl.cc * tg.chs * eb > kMaxDynamicLds - kStageDescBytesMax) return PP_ERR_UNSUPPORTED;
     tl.groups = groups_f;
     tl.chunks = (hp.c_in + tl.cc - 1) / tl.cc;
     hp.chosen.filters_per_wave = tl.f;

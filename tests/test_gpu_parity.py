@@ -66,14 +66,19 @@ TUNINGS = [dict(filters_per_wave=4, rows_per_lane=1, lanes_x=2), dict(filters_pe
            dict(filters_per_wave=8, rows_per_lane=2, lanes_x=16, waves_f=2, split_c=4, chunk_c=8),
            dict(filters_per_wave=4, rows_per_lane=1, lanes_x=8, waves_f=1, split_c=8, chunk_c=16),
            dict(filters_per_wave=8, rows_per_lane=2, lanes_x=7, waves_f=3, split_c=2, chunk_c=6),
-           dict(filters_per_wave=8, rows_per_lane=1, lanes_x=14, waves_f=16, split_c=1, chunk_c=1)]
+           dict(filters_per_wave=8, rows_per_lane=1, lanes_x=14, waves_f=16, split_c=1, chunk_c=1),
+           dict(filters_per_wave=4, rows_per_lane=4, lanes_x=16, waves_f=4, split_c=2, chunk_c=4),
+           dict(filters_per_wave=4, rows_per_lane=4, lanes_x=7, waves_f=2, split_c=1, chunk_c=5),
+           dict(filters_per_wave=4, rows_per_lane=2, lanes_x=14, waves_f=4, split_c=2, chunk_c=4),
+           dict(filters_per_wave=4, rows_per_lane=1, lanes_x=16, waves_f=8, split_c=1, chunk_c=3),
+           dict(filters_per_wave=4, rows_per_lane=2, lanes_x=2, waves_f=2, split_c=4, chunk_c=8)]
 
 
 @pytest.mark.parametrize("tune", TUNINGS)
 @pytest.mark.parametrize("dtype", ["f32", "f16"])
 def test_every_tile_geometry(tune, dtype):
     say(f"tuning {tune} {dtype}")
-    for (n, c_in, c_out, h, w) in [(2, 21, 37, 19, 45), (3, 16, 16, 8, 8)]:
+    for (n, c_in, c_out, h, w) in [(2, 21, 37, 19, 45), (3, 16, 16, 8, 8), (2, 9, 12, 11, 48)]:
         lay = synth.random_pruned_layer("tune", n, c_in, c_out, h, w, dtype, synth.PSET16, 0.5, 0.3, seed=7)
         rep, _ = check_layer(lay, tuning=T(variant=2, **tune), label=f"tune{tune}")
         for k, v in tune.items():
