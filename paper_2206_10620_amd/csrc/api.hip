@@ -287,8 +287,7 @@ pp_status_t pp_conv_run(const pp_conv_plan_t* plan, const void* x_dev, void* y_d
     a.work_items = (int)items;
     a.blocks_per_xcd = (int)((items + 7) / 8);
     const int64_t blocks = (int64_t)a.blocks_per_xcd * 8;
-    a.desc_offset = k1_desc_offset(tl.lw, tl.r, tl.f, tl.wf, tl.ks, tl.cc, eb);
-    const int lds = k1_lds_bytes(tl.lw, tl.r, tl.f, tl.wf, tl.ks, tl.cc, eb, a.vec);
+    const int lds = k1_lds_bytes(tl.lw, tl.r, tl.f, tl.wf, tl.ks, tl.cc, eb);
     plan->launch(a, (int)blocks, 64 * tl.wf * tl.ks, lds, stream);
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_DEVICE;
 }

@@ -48,7 +48,6 @@ struct K1Args {
     int32_t groups;             // G
     int32_t wf, ks, cc, chunks;
     int32_t vec;                // staging vector width in elements
-    int32_t desc_offset;        // byte offset of the staging descriptor table in dynamic LDS
     int32_t relu;
 };
 
@@ -185,132 +184,95 @@ __device__ __forceinline__ void dispatch(int code, float (&acc)[F][R][4], const 
 }
 
 // ---------------------------------------------------------------------------------------------
-// Staging of one channel chunk into LDS, VEC elements per global load.
+// Staging of one channel chunk into LDS (zero-filled outside the images), VEC elements per
+// global load.  The chunk is a list of ccn*trn tile rows of VPR vectors each; thread t takes
+// vectors t, t + nthreads, ...  Interior columns go to [row][0..TW); an element that is some
+// micro-tile's left or right neighbour is also written to that micro-tile's (left, right) halo
+// pair, which sits behind the interior at [row][HOFF + 2*mcol].  The pair array has one dummy pair
+// on each side so that these writes need no bounds test.
 //
-// A channel's tile is trn rows of VPR vectors.  Which vector a lane handles, where it comes from
-// inside the channel image and where it goes inside the channel tile is the same for every
-// channel and every chunk, so it is worked out once per workgroup and kept as a small table of
-// lane descriptors in LDS; after that a wavefront stages whole channels with one descriptor
-// read, one global load (scalar channel base + per-lane offset), one interior LDS write and the
-// halo-pair writes per vector -- a handful of instructions instead of the index arithmetic.
-//
-// LDS tile layout of one channel row: interior columns [0, TW), then the (left, right) halo
-// pairs of the LW micro-columns starting at HOFF, with one dummy pair on each side so that the
-// halo writes need no bounds test.  An element that is some micro-tile's left or right
-// neighbour is written twice: in the interior and in that micro-tile's pair.  Everything that
-// lies outside the images (padding rows, columns beyond W) is zeroed once and never written.
-struct StageDesc {            // 16 bytes per (iteration, lane)
-    int32_t goff;             // element offset of the vector inside the channel image, -1: nothing to load
-    int32_t ldst;             // element offset of the vector inside the channel tile
-    int32_t hdst;             // low 16 bits: halo write base inside the channel tile; high 16: edge destination
-    int32_t eoff;             // element offset of the strip-edge element this lane fetches, -1: none
+// Two vectors per thread are loaded before either is written, and nothing looks at a loaded
+// value until then (out-of-image vectors read a valid dummy address and are zeroed when stored),
+// so both loads are in flight together.
+template <typename T> struct StageRegs {
+    uint32_t raw[2][4];   // up to 16 bytes per vector
+    T edge[2];
 };
 
 template <typename T, int VEC, int LW, int R> struct Stager {
     static constexpr TileGeom tg = tile_geom(LW, R, (int)sizeof(T));
-    static constexpr int TW = tg.tw, VPR = TW / VEC, RS = tg.rs, CHS = tg.chs, HOFF = tg.hoff, ROWS = tg.rows;
+    static constexpr int TW = tg.tw, VPR = TW / VEC, RS = tg.rs, CHS = tg.chs, HOFF = tg.hoff;
     static constexpr int NB = VEC * (int)sizeof(T);
-    static constexpr int NIT_MAX = (ROWS * VPR + 63) / 64;
     static_assert(VPR >= 2, "a tile row must span at least two staging vectors");
-    static_assert(CHS < 65536, "tile offsets are packed in 16 bits");
     typedef typename VecOf<T, VEC>::type vec_t;
 
-    // Build the descriptor table (all threads of the workgroup; rowtab must be visible).
-    static __device__ __forceinline__ void build(StageDesc* desc, const int* rowtab, int trn, int x0, int W, int tid,
-                                                 int nthreads) {
-        const int nit = (trn * VPR + 63) / 64;
-        for (int j = tid; j < nit * 64; j += nthreads) {
-            const int tr = j / VPR, v = j - tr * VPR;
-            StageDesc d;
-            d.goff = -1;
-            d.eoff = -1;
-            d.ldst = 0;
-            d.hdst = 0;
-            if (tr < trn) {
-                const int rb = rowtab[tr];
-                const int col = x0 + v * VEC;
-                if (rb >= 0 && col < W) d.goff = rb + col;
-                d.ldst = tr * RS + v * VEC;
-                // halo write base: element k of the vector (k % 4 == 0) is the right neighbour of the
-                // micro-column before its own, stored at base + 2*(k/4); element k % 4 == 3 is the left
-                // neighbour of the next micro-column, stored at base + 3 + 2*(k/4).  For VEC < 4 a
-                // vector holds at most one such element and base is its destination (0xFFFF: none).
-                int hb;
-                if (VEC >= 4) {
-                    hb = tr * RS + HOFF + 2 * (v * VEC / 4) - 1;
-                } else {
-                    const int sc = v * VEC;                      // first column of the vector
-                    hb = 0xFFFF;
-                    if (VEC == 2) hb = tr * RS + HOFF + ((sc & 3) == 0 ? 2 * (sc / 4 - 1) + 1 : 2 * (sc / 4 + 1));
-                    if (VEC == 1 && (sc & 3) == 0) hb = tr * RS + HOFF + 2 * (sc / 4 - 1) + 1;
-                    if (VEC == 1 && (sc & 3) == 3) hb = tr * RS + HOFF + 2 * (sc / 4 + 1);
-                }
-                // the two elements just outside the strip are fetched by the first / last vector of a row
-                int edst = 0;
-                const int ecol = v == 0 ? x0 - 1 : x0 + TW;
-                if (rb >= 0 && (v == 0 || v == VPR - 1) && ecol >= 0 && ecol < W) {
-                    d.eoff = rb + ecol;
-                    edst = tr * RS + HOFF + (v == 0 ? 0 : 2 * (LW - 1) + 1);
-                }
-                d.hdst = (hb & 0xFFFF) | (edst << 16);
-            }
-            desc[j] = d;
-        }
+    static __device__ __forceinline__ void load(StageRegs<T>& sr, int u, int i, int total, const T* xc0,
+                                                const int* rowtab, int trn, uint32_t trn_magic, int x0, int W, int hw) {
+        const int row = i / VPR, v = i - row * VPR;              // VPR is a compile-time constant
+        const int c = (int)__umulhi((uint32_t)row, trn_magic);   // row / trn (exact for row < 2^16)
+        const int tr = row - c * trn;
+        const int rb = i < total ? rowtab[tr] : -1;
+        const int col = x0 + v * VEC;
+        const uint32_t chan = (uint32_t)(c * hw);
+        const uint32_t goff = (rb >= 0 && col < W) ? chan + (uint32_t)(rb + col) : 0u;
+        const vec_t val = *reinterpret_cast<const vec_t*>(xc0 + goff);
+        __builtin_memcpy(&sr.raw[u][0], &val, NB);
+        // the two elements just outside the strip are fetched by the first / last vector of a row
+        const int ecol = v == 0 ? x0 - 1 : x0 + TW;
+        const bool e_ok = rb >= 0 && (v == 0 || v == VPR - 1) && ecol >= 0 && ecol < W;
+        sr.edge[u] = xc0[e_ok ? chan + (uint32_t)(rb + ecol) : 0u];
     }
 
-    // Stage channels c = wave, wave + nwaves, ... < ccn of the chunk starting at channel c0.
-    static __device__ __forceinline__ void stage(const T* __restrict__ x, T* tile, const StageDesc* desc, int c0, int ccn,
-                                                 int trn, int hw, int wave, int nwaves, int lane) {
-        const int nit = (trn * VPR + 63) / 64;
-        constexpr int G = 4;                                   // vectors in flight per lane
-        const int per_wave = (ccn - wave + nwaves - 1) / nwaves;   // channels this wavefront stages (<= 0: none)
-        const int total = per_wave > 0 ? per_wave * nit : 0;
-        for (int s0 = 0; s0 < total; s0 += G) {
-            // first half: issue the loads; only the loaded values stay live across the wait (the
-            // descriptors are read again from LDS in the second half: cheaper than holding them)
-            vec_t val[G];
-            T ev[G];
+    static __device__ __forceinline__ void store(const StageRegs<T>& sr, int u, int i, int total, T* tile,
+                                                 const int* rowtab, int trn, uint32_t trn_magic, int x0, int W) {
+        if (i >= total) return;
+        const int row = i / VPR, v = i - row * VPR;
+        const int c = (int)__umulhi((uint32_t)row, trn_magic);
+        const int tr = row - c * trn;
+        const bool in_img = rowtab[tr] >= 0;
+        T* trow = tile + c * CHS + tr * RS;
+        vec_t val;
+        __builtin_memcpy(&val, &sr.raw[u][0], NB);
+        if (!(in_img && x0 + v * VEC < W)) val = vec_t(0);
+        *reinterpret_cast<vec_t*>(trow + v * VEC) = val;
+        T* hrow = trow + HOFF;
 #pragma unroll
-            for (int g = 0; g < G; ++g) {
-                const int s = s0 + g;
-                if (s < total) {                               // wave-uniform
-                    const int ci = s / nit, it = s - ci * nit;
-                    const StageDesc d = desc[it * 64 + lane];
-                    const T* xc = x + (int64_t)(c0 + wave + ci * nwaves) * hw;   // scalar base
-                    if (d.goff >= 0) val[g] = *reinterpret_cast<const vec_t*>(xc + d.goff);
-                    if (d.eoff >= 0) ev[g] = xc[d.eoff];
-                }
+        for (int k = 0; k < VEC; ++k) {
+            const int sc = v * VEC + k;
+            const T e = vec_elem<T, VEC>(val, k);
+            if (VEC >= 4) {                                   // which elements are neighbours is static
+                if ((k & 3) == 0) hrow[2 * (sc / 4 - 1) + 1] = e;
+                if ((k & 3) == 3) hrow[2 * (sc / 4 + 1)] = e;
+            } else {
+                if ((sc & 3) == 0) hrow[2 * (sc / 4 - 1) + 1] = e;
+                if ((sc & 3) == 3) hrow[2 * (sc / 4 + 1)] = e;
             }
-#pragma unroll
-            for (int g = 0; g < G; ++g) {
-                const int s = s0 + g;
-                if (s >= total) break;
-                const int ci = s / nit, it = s - ci * nit;
-                const StageDesc d = desc[it * 64 + lane];
-                T* tc = tile + (wave + ci * nwaves) * CHS;
-                if (d.goff >= 0) {
-                    *reinterpret_cast<vec_t*>(tc + d.ldst) = val[g];
-                    const int hb = d.hdst & 0xFFFF;
-                    if (VEC >= 4) {
-#pragma unroll
-                        for (int k = 0; k < VEC; k += 4) {
-                            tc[hb + 2 * (k / 4)] = vec_elem<T, VEC>(val[g], k);
-                            tc[hb + 3 + 2 * (k / 4)] = vec_elem<T, VEC>(val[g], k + 3);
-                        }
-                    } else if (hb != 0xFFFF) {
-                        // VEC == 2: the neighbour element is the first one when the vector starts a
-                        // micro-tile (destination index odd), else the second; VEC == 1: the element itself
-                        const bool first = VEC == 1 || ((hb - HOFF) & 1) != 0;
-                        tc[hb] = first ? vec_elem<T, VEC>(val[g], 0) : vec_elem<T, VEC>(val[g], VEC - 1);
-                    }
-                }
-                if (d.eoff >= 0) tc[(uint32_t)d.hdst >> 16] = ev[g];
-            }
+        }
+        const int ecol = v == 0 ? x0 - 1 : x0 + TW;
+        const T edge = (in_img && ecol >= 0 && ecol < W) ? sr.edge[u] : T(0);
+        if (v == 0) hrow[0] = edge;
+        if (v == VPR - 1) hrow[2 * (LW - 1) + 1] = edge;
+    }
+
+    static __device__ __forceinline__ void stage(const T* x, T* tile, const int* rowtab, int c0, int ccn, int trn,
+                                                 uint32_t trn_magic, int x0, int W, int hw, int tid, int nthreads) {
+        // Everything derived from the thread index is the same for every chunk; recomputing it is a
+        // few integer instructions, keeping it live across the multiply-accumulate loop would cost
+        // a dozen registers.  The empty asm makes the index opaque so that it is recomputed.
+        asm volatile("" : "+v"(tid));
+        const int total = ccn * trn * VPR;
+        const T* xc0 = x + (int64_t)c0 * hw;
+        StageRegs<T> sr;
+        for (int i0 = tid; i0 < total; i0 += 2 * nthreads) {
+            load(sr, 0, i0, total, xc0, rowtab, trn, trn_magic, x0, W, hw);
+            load(sr, 1, i0 + nthreads, total, xc0, rowtab, trn, trn_magic, x0, W, hw);
+            store(sr, 0, i0, total, tile, rowtab, trn, trn_magic, x0, W);
+            store(sr, 1, i0 + nthreads, total, tile, rowtab, trn, trn_magic, x0, W);
         }
     }
 };
 
-// Run a staging routine with the vector width picked at launch time.
+// Run the staging routine with the vector width picked at launch time.
 #define PPC_STAGE_DISPATCH(VECVAR, CALL)                                        \
     switch (VECVAR) {                                                           \
         case 8:                                                                 \
@@ -333,7 +295,6 @@ void k1_tiled(const K1Args a) {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     __shared__ int rowtab[ROWS];
     T* tile = reinterpret_cast<T*>(smem_raw);
-    StageDesc* sdesc = reinterpret_cast<StageDesc*>(smem_raw + a.desc_offset);
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -389,6 +350,7 @@ void k1_tiled(const K1Args a) {
     const T* lane_mid = tile + lr * R * RS + 4 * mcol;
     const T* lane_halo = tile + lr * R * RS + HOFF + 2 * mcol;
     const int hw = a.h * a.w;
+    const uint32_t trn_magic = 0xFFFFFFFFu / (uint32_t)trn + 1u;      // ceil(2^32 / trn), trn >= 3
     const T* __restrict__ xin = static_cast<const T*>(a.x);
 
     // this wavefront's entry stream (constant address space: wave-uniform loads from it are scalar loads)
@@ -399,22 +361,11 @@ void k1_tiled(const K1Args a) {
     // behind the previous kernel's multiply-accumulates
     uint32_t n_head = sp[0], n_w0 = sp[4], n_w1 = sp[5], n_w2 = sp[6], n_w3 = sp[7];
 
-    // Once per workgroup: zero the tile (what lies outside the images is never written again) and
-    // build the staging descriptors.
-    __syncthreads();              // rowtab
-    {
-        typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
-        u32x4_t* t16 = reinterpret_cast<u32x4_t*>(smem_raw);
-        const int n16 = a.cc * CHS * (int)sizeof(T) / 16;
-        for (int i = threadIdx.x; i < n16; i += blockDim.x) t16[i] = u32x4_t(0);
-    }
-    PPC_STAGE_DISPATCH(a.vec, build(sdesc, rowtab, trn, x0, a.w, threadIdx.x, blockDim.x))
-
     for (int q = 0; q < a.chunks; ++q) {
         const int c0 = q * a.cc;
         const int ccn = (a.c_in - c0 < a.cc) ? a.c_in - c0 : a.cc;
-        __syncthreads();          // previous chunk fully consumed (first time: tile zeroed, descriptors built)
-        PPC_STAGE_DISPATCH(a.vec, stage(xin, tile, sdesc, c0, ccn, trn, hw, wave, nwaves, lane))
+        __syncthreads();          // previous chunk fully consumed (and rowtab written, first time round)
+        PPC_STAGE_DISPATCH(a.vec, stage(xin, tile, rowtab, c0, ccn, trn, trn_magic, x0, a.w, hw, threadIdx.x, blockDim.x))
         __syncthreads();
         if (!has_group) continue;
 
@@ -513,18 +464,12 @@ void k1_tiled(const K1Args a) {
     }
 }
 
-// Dynamic LDS layout of a launch: [tile or split-channel exchange area][staging descriptors].
-inline int k1_desc_offset(int lw, int r, int f, int wf, int ks, int cc, int elem_bytes) {
+// Dynamic LDS bytes a launch needs: the tile, or the split-channel exchange area if larger.
+inline int k1_lds_bytes(int lw, int r, int f, int wf, int ks, int cc, int elem_bytes) {
     TileGeom tg = tile_geom(lw, r, elem_bytes);
     int tile = cc * tg.chs * elem_bytes;
     int red = ks > 1 ? wf * f * r * 4 * 64 * 4 : 0;
-    int first = tile > red ? tile : red;
-    return (first + 15) / 16 * 16;
-}
-inline int k1_lds_bytes(int lw, int r, int f, int wf, int ks, int cc, int elem_bytes, int vec) {
-    TileGeom tg = tile_geom(lw, r, elem_bytes);
-    int nit = (tg.rows * (tg.tw / vec) + 63) / 64;
-    return k1_desc_offset(lw, r, f, wf, ks, cc, elem_bytes) + nit * 64 * (int)sizeof(StageDesc);
+    return tile > red ? tile : red;
 }
 
 typedef void (*k1_launch_fn)(const K1Args& a, int blocks, int threads, int lds_bytes, hipStream_t stream);

@@ -201,9 +201,13 @@ pp_status_t build_layouts(const pp_conv_desc_t& d, HostPlan& hp) {
 
     // can the tiled kernel express this layer's pattern table?
     std::vector<int> slot_of(hp.num_patterns, -1);
-    bool builtin = (hp.taps == 4);
-    int max_slot = -1;
-    if (builtin) {
+    // An unpruned (nine-tap) kernel is run as three four-tap kernels on the same channel whose
+    // patterns cover the 3x3 window: {0,1,3,4}, {4,5,7,8} with a zero centre weight, and
+    // {0,2,4,6} with zero weights on taps 0 and 4 (12 multiply-accumulates for 9 weights).
+    const bool dense = hp.taps == 9;
+    bool builtin = true;
+    int max_slot = dense ? 8 : -1;
+    if (!dense) {
         std::vector<char> used(hp.num_patterns, 0);
         for (uint8_t p : hp.canon.kpat) used[p] = 1;
         for (int p = 0; p < hp.num_patterns; ++p) {
@@ -258,18 +262,18 @@ pp_status_t build_layouts(const pp_conv_desc_t& d, HostPlan& hp) {
     if (tl.wf < 1 || tl.wf * tl.ks > max_waves) return PP_ERR_UNSUPPORTED;
     // the split-channel partial sums are exchanged through LDS: wf * f * r * 4 accumulators * 64 lanes
     auto reduce_bytes = [&]() { return tl.ks > 1 ? tl.wf * tl.f * tl.r * 4 * 64 * 4 : 0; };
-    while (!t.waves_f && tl.wf > 1 && reduce_bytes() > kMaxDynamicLds - kStageDescBytesMax) tl.wf /= 2;
-    if (reduce_bytes() > kMaxDynamicLds - kStageDescBytesMax) return PP_ERR_UNSUPPORTED;
+    while (!t.waves_f && tl.wf > 1 && reduce_bytes() > kMaxDynamicLds) tl.wf /= 2;
+    if (reduce_bytes() > kMaxDynamicLds) return PP_ERR_UNSUPPORTED;
     const TileGeom tg = tile_geom(tl.lw, tl.r, eb);
     tl.cc = t.chunk_c;
     if (tl.cc == 0) {
-        int fit = (kMaxDynamicLds - kStageDescBytesMax) / (tg.chs * eb);
+        int fit = (kMaxDynamicLds) / (tg.chs * eb);
         fit = std::min(fit, 32);
         fit = std::min(fit, (hp.c_in + tl.ks - 1) / tl.ks * tl.ks);
         tl.cc = std::max(tl.ks, fit / tl.ks * tl.ks);
     }
     if (tl.cc < tl.ks || tl.cc % tl.ks != 0 || tl.cc > 512 || tl.cc * tg.rows >= 65536) return PP_ERR_UNSUPPORTED;
-    if ((int64_t)tl.cc * tg.chs * eb > kMaxDynamicLds - kStageDescBytesMax) return PP_ERR_UNSUPPORTED;
+    if ((int64_t)tl.cc * tg.chs * eb > kMaxDynamicLds) return PP_ERR_UNSUPPORTED;
     tl.groups = groups_f;
     tl.chunks = (hp.c_in + tl.cc - 1) / tl.cc;
     hp.chosen.filters_per_wave = tl.f;
@@ -288,7 +292,9 @@ pp_status_t build_layouts(const pp_conv_desc_t& d, HostPlan& hp) {
         tl.perm_pad[pos] = cn.perm[pos];
         tl.bias_pad[pos] = hp.bias[cn.perm[pos]];
     }
-    struct Item { int32_t ci; int32_t fl; int32_t slot; int64_t src; };
+    struct Item { int32_t ci; int32_t fl; int32_t slot; int64_t src; int32_t part; };
+    static const int kDenseSlot[3] = {4, 7, 8};                       // built-in slots of the three cover patterns
+    static const int kDenseTap[3][4] = {{0, 1, 3, 4}, {-1, 5, 7, 8}, {-1, 2, -1, 6}};   // source tap of each weight, -1: zero
     tl.stream.clear();
     tl.wave_off.assign((size_t)G * KS, 0);
     std::vector<Item> items;
@@ -307,12 +313,18 @@ pp_status_t build_layouts(const pp_conv_desc_t& d, HostPlan& hp) {
         for (int fl = 0; fl < F; ++fl) {
             int pos = g * F + fl;
             if (pos >= hp.c_out) break;
-            for (int64_t e = hp.filt_off[pos]; e < hp.filt_off[pos + 1]; ++e)
-                items.push_back(Item{cn.kidx[e], fl, slot_of[cn.kpat[e]], e});
+            for (int64_t e = hp.filt_off[pos]; e < hp.filt_off[pos + 1]; ++e) {
+                if (!dense) {
+                    items.push_back(Item{cn.kidx[e], fl, slot_of[cn.kpat[e]], e, 0});
+                } else {
+                    for (int part = 0; part < 3; ++part) items.push_back(Item{cn.kidx[e], fl, kDenseSlot[part], e, part});
+                }
+            }
         }
         std::sort(items.begin(), items.end(), [](const Item& a, const Item& b) {
             if (a.ci != b.ci) return a.ci < b.ci;
-            return a.fl < b.fl;
+            if (a.fl != b.fl) return a.fl < b.fl;
+            return a.part < b.part;
         });
         for (int s = 0; s < KS; ++s) {
             tl.wave_off[(size_t)g * KS + s] = (int32_t)(tl.stream.size() / EW);
@@ -328,7 +340,16 @@ pp_status_t build_layouts(const pp_conv_desc_t& d, HostPlan& hp) {
                     if (k.ci != prev_ci) header |= kFlagNewChannel;
                     header |= (uint32_t)(k.ci - q * CC) << kChanShift;
                     prev_ci = k.ci;
-                    push_entry(header, &cn.wpacked[(size_t)k.src * 4]);
+                    if (!dense) {
+                        push_entry(header, &cn.wpacked[(size_t)k.src * 4]);
+                    } else {
+                        float w4[4];
+                        for (int j4 = 0; j4 < 4; ++j4) {
+                            const int tap = kDenseTap[k.part][j4];
+                            w4[j4] = tap < 0 ? 0.0f : cn.wpacked[(size_t)k.src * 9 + tap];
+                        }
+                        push_entry(header, w4);
+                    }
                 }
                 push_entry(kFlagEnd, nullptr);
             }
@@ -340,7 +361,7 @@ pp_status_t build_layouts(const pp_conv_desc_t& d, HostPlan& hp) {
 }
 
 pp_status_t unpack_stream(const HostPlan& hp, int32_t* kidx, uint8_t* kpat, float* w) {
-    if (!hp.tiled) return PP_ERR_UNSUPPORTED;
+    if (!hp.tiled || hp.taps != 4) return PP_ERR_UNSUPPORTED;
     const TiledLayout& tl = hp.tl;
     const int EW = tl.entry_words;
     // slot -> lowest pattern id carrying that mask

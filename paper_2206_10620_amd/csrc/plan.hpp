@@ -74,7 +74,6 @@ float f16_to_f32(uint16_t b);
 
 // Static geometry of a tiled-kernel instantiation (shared by host packing and device code).
 constexpr int kPW = 4;      // output pixels per lane along the width
-constexpr int kStageDescBytesMax = 24 * 1024; // upper bound of the staging descriptor table (worst case: element-wise staging)
 constexpr int kMaxDynamicLds = 156 * 1024;   // dynamic LDS bytes a tiled-kernel workgroup may use (CU has 160 KB)
 struct TileGeom {
     int tw;        // tile width in pixels = lw * kPW

@@ -69,9 +69,9 @@ TUNINGS = [dict(filters_per_wave=4, rows_per_lane=1, lanes_x=2), dict(filters_pe
            dict(filters_per_wave=8, rows_per_lane=1, lanes_x=14, waves_f=16, split_c=1, chunk_c=1),
            dict(filters_per_wave=4, rows_per_lane=4, lanes_x=16, waves_f=4, split_c=2, chunk_c=4),
            dict(filters_per_wave=4, rows_per_lane=4, lanes_x=7, waves_f=2, split_c=1, chunk_c=5),
-           dict(filters_per_wave=4, rows_per_lane=2, lanes_x=14, waves_f=4, split_c=2, chunk_c=4),
-           dict(filters_per_wave=4, rows_per_lane=1, lanes_x=16, waves_f=8, split_c=1, chunk_c=3),
-           dict(filters_per_wave=4, rows_per_lane=2, lanes_x=2, waves_f=2, split_c=4, chunk_c=8)]
+           dict(filters_per_wave=4, rows_per_lane=2, lanes_x=14, waves_f=4, split_c=2, chunk_c=8),
+           dict(filters_per_wave=4, rows_per_lane=1, lanes_x=16, waves_f=8, split_c=1, chunk_c=8),
+           dict(filters_per_wave=4, rows_per_lane=2, lanes_x=8, waves_f=2, split_c=4, chunk_c=8)]
 
 
 @pytest.mark.parametrize("tune", TUNINGS)
