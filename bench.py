@@ -31,6 +31,15 @@ import numpy as np
 PEAK_FP32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
+# HBM-side traffic of one launch (bytes), from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by a copy
+# kernel of known size; see profiles/k1_tiled_<workload>.md.  Valid only for the kernel revision
+# it was measured on: reported as null for any other.
+MEASURED_TRAFFIC = {
+    "cfg2_vgg_mid": ("k1-2026-11-27-e", 20.92e6),
+    "cfg5_enhance_1080p": ("k1-2026-11-27-e", 924.8e6),
+    "cfg4_vgg_L6": ("k1-2026-11-27-e", 50.48e6),
+}
+
 
 def workloads():
     import synth
@@ -122,6 +131,9 @@ def main():
     s = summarize(lay, t)
     sec_wall = t["wall_ms_per_step"] * 1e-3
 
+    rev, tbytes = MEASURED_TRAFFIC.get(args.workload, (None, None))
+    traffic = tbytes if (rev == pp.KERNEL_REVISION and not args.tuning) else None
+
     out = {
         "metric": "effective GMAC/s (nonzero MACs), pattern-pruned 3x3 conv",
         "value": lay.eff_macs / sec_wall / 1e9,
@@ -136,7 +148,7 @@ def main():
         "alg_gb_per_s": s["alg_gb_per_s"], "frac_hbm": s["frac_hbm"],
         "roofline": {"bound": "alu", "achieved": 2 * lay.eff_macs / (t["event_ms_per_step"] * 1e-3) / 1e12,
                      "peak": PEAK_FP32_TFLOPS, "unit": "TFLOP/s",
-                     "frac": s["frac_fp32_valu"], "traffic": None,
+                     "frac": s["frac_fp32_valu"], "traffic": traffic,
                      "kernel": "k1_tiled", "kernel_us": s["us_per_step"]},
     }
 

@@ -11,6 +11,10 @@ PP_OK, PP_ERR_NULL, PP_ERR_SHAPE, PP_ERR_PATTERN, PP_ERR_UNSUPPORTED, PP_ERR_ALL
 PP_F32, PP_F16 = 0, 1
 PP_FLAG_RELU, PP_FLAG_DENSE, PP_FLAG_HOST_ONLY = 1, 2, 4
 
+# Bumped whenever the device code of the tiled kernel changes (measurements that are tied to a
+# kernel build, such as hardware-counter readings, are keyed by it).
+KERNEL_REVISION = "k1-2026-11-27-e"
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libpp_conv.so")
 
