@@ -69,6 +69,12 @@ typedef struct {
     int32_t waves_f;        /* WF: wavefronts per workgroup that share one input tile, each on its own F filters */
     int32_t split_c;        /* KS: wavefronts per workgroup that split the input channels of a chunk */
     int32_t chunk_c;        /* CC: input channels staged in LDS at a time (multiple of split_c) */
+    int32_t staging;        /* how input tiles reach LDS: 1 through registers, one buffer; 2..8 direct global-to-LDS
+                               loads into a ring of that many buffers of chunk_c channels (needs rows that start on
+                               4-byte boundaries: any fp32 width, even fp16 widths) */
+    int32_t balance;        /* 1: filters and channels take wavefront slots and chunk places in reordered / natural
+                               order; 2: they are dealt so that the wavefronts of a workgroup do about equal work
+                               between two barriers (the default whenever a workgroup has several wavefronts) */
 } pp_conv_tuning_t;
 
 /* Layer description (section 2.1.1 for the sparsity, section 2.3.1 for what the layer-wise

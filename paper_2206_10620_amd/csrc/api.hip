@@ -11,25 +11,25 @@
 
 namespace ppc {
 
-k1_launch_fn k1_lookup_f32_p8_r1(int f, int lw);
-k1_launch_fn k1_lookup_f32_p8_r2(int f, int lw);
-k1_launch_fn k1_lookup_f32_p8_r4(int f, int lw);
-k1_launch_fn k1_lookup_f32_p16_r1(int f, int lw);
-k1_launch_fn k1_lookup_f32_p16_r2(int f, int lw);
-k1_launch_fn k1_lookup_f32_p16_r4(int f, int lw);
-k1_launch_fn k1_lookup_f16_p8_r1(int f, int lw);
-k1_launch_fn k1_lookup_f16_p8_r2(int f, int lw);
-k1_launch_fn k1_lookup_f16_p8_r4(int f, int lw);
-k1_launch_fn k1_lookup_f16_p16_r1(int f, int lw);
-k1_launch_fn k1_lookup_f16_p16_r2(int f, int lw);
-k1_launch_fn k1_lookup_f16_p16_r4(int f, int lw);
+k1_launch_fn k1_lookup_f32_p8_r1(int f, int lw, bool direct);
+k1_launch_fn k1_lookup_f32_p8_r2(int f, int lw, bool direct);
+k1_launch_fn k1_lookup_f32_p8_r4(int f, int lw, bool direct);
+k1_launch_fn k1_lookup_f32_p16_r1(int f, int lw, bool direct);
+k1_launch_fn k1_lookup_f32_p16_r2(int f, int lw, bool direct);
+k1_launch_fn k1_lookup_f32_p16_r4(int f, int lw, bool direct);
+k1_launch_fn k1_lookup_f16_p8_r1(int f, int lw, bool direct);
+k1_launch_fn k1_lookup_f16_p8_r2(int f, int lw, bool direct);
+k1_launch_fn k1_lookup_f16_p8_r4(int f, int lw, bool direct);
+k1_launch_fn k1_lookup_f16_p16_r1(int f, int lw, bool direct);
+k1_launch_fn k1_lookup_f16_p16_r2(int f, int lw, bool direct);
+k1_launch_fn k1_lookup_f16_p16_r4(int f, int lw, bool direct);
 
-k1_launch_fn k1_lookup(int dtype, int np, int r, int f, int lw) {
+k1_launch_fn k1_lookup(int dtype, int np, int r, int f, int lw, bool direct) {
 #define PPC_PICK(DT, NP)                                   \
     switch (r) {                                           \
-        case 1: return k1_lookup_##DT##_p##NP##_r1(f, lw); \
-        case 2: return k1_lookup_##DT##_p##NP##_r2(f, lw); \
-        case 4: return k1_lookup_##DT##_p##NP##_r4(f, lw); \
+        case 1: return k1_lookup_##DT##_p##NP##_r1(f, lw, direct); \
+        case 2: return k1_lookup_##DT##_p##NP##_r2(f, lw, direct); \
+        case 4: return k1_lookup_##DT##_p##NP##_r4(f, lw, direct); \
         default: return nullptr;                           \
     }
     if (dtype == PP_F32) {
@@ -115,6 +115,7 @@ struct pp_conv_plan {
     uint32_t* d_stream = nullptr;
     int32_t* d_wave_off = nullptr;
     int32_t* d_perm_pad = nullptr;
+    int32_t* d_chan_map = nullptr;
     float* d_bias_pad = nullptr;
     k1_launch_fn launch = nullptr;
     // generic kernel
@@ -141,7 +142,7 @@ bool upload(T** dst, const void* src, size_t bytes) {
 }
 
 void free_device(pp_conv_plan_t* p) {
-    void* bufs[] = {p->d_stream, p->d_wave_off, p->d_perm_pad, p->d_bias_pad, p->d_filt_off, p->d_kidx,
+    void* bufs[] = {p->d_stream, p->d_wave_off, p->d_chan_map, p->d_perm_pad, p->d_bias_pad, p->d_filt_off, p->d_kidx,
                     p->d_kpat,   p->d_w,        p->d_tap,      p->d_perm,     p->d_bias};
     for (void* b : bufs)
         if (b) (void)hipFree(b);
@@ -189,7 +190,7 @@ pp_status_t pp_conv_plan(const pp_conv_desc_t* desc, pp_conv_plan_t** out_plan) 
     }
     HostPlan& hp = p->hp;
     if (hp.tiled) {
-        p->launch = k1_lookup(hp.dtype, hp.tl.np, hp.tl.r, hp.tl.f, hp.tl.lw);
+        p->launch = k1_lookup(hp.dtype, hp.tl.np, hp.tl.r, hp.tl.f, hp.tl.lw, hp.tl.mode != 0);
         if (!p->launch) {
             delete p;
             return PP_ERR_UNSUPPORTED;
@@ -208,6 +209,7 @@ pp_status_t pp_conv_plan(const pp_conv_desc_t* desc, pp_conv_plan_t** out_plan) 
         ok = ok && upload(&p->d_stream, tl.stream.data(), tl.stream.size() * 4);
         ok = ok && upload(&p->d_wave_off, tl.wave_off.data(), tl.wave_off.size() * 4);
         ok = ok && upload(&p->d_perm_pad, tl.perm_pad.data(), tl.perm_pad.size() * 4);
+        ok = ok && upload(&p->d_chan_map, tl.chan_map.data(), tl.chan_map.size() * 4);
         ok = ok && upload(&p->d_bias_pad, tl.bias_pad.data(), tl.bias_pad.size() * 4);
     } else {
         const Canonical& cn = hp.canon;
@@ -264,6 +266,7 @@ pp_status_t pp_conv_run(const pp_conv_plan_t* plan, const void* x_dev, void* y_d
     a.wave_off = plan->d_wave_off;
     a.bias_pad = plan->d_bias_pad;
     a.perm_pad = plan->d_perm_pad;
+    a.chan_map = plan->d_chan_map;
     a.n = n;
     a.c_in = hp.c_in;
     a.c_out = hp.c_out;
@@ -279,6 +282,9 @@ pp_status_t pp_conv_run(const pp_conv_plan_t* plan, const void* x_dev, void* y_d
     a.cc = tl.cc;
     a.chunks = tl.chunks;
     a.vec = staging_vec(hp.w, tg.tw, eb);
+    a.mode = tl.mode;
+    a.nbuf = tl.nbuf;
+    a.table_offset = k1_lds_table_offset(tl.lw, tl.r, tl.cc, eb, tl.nbuf);
     a.relu = relu;
     const int nfb = (tl.groups + tl.wf - 1) / tl.wf;
     const int64_t items = (int64_t)a.strips * a.wg_per_strip * nfb;
@@ -287,7 +293,7 @@ pp_status_t pp_conv_run(const pp_conv_plan_t* plan, const void* x_dev, void* y_d
     a.work_items = (int)items;
     a.blocks_per_xcd = (int)((items + 7) / 8);
     const int64_t blocks = (int64_t)a.blocks_per_xcd * 8;
-    const int lds = k1_lds_bytes(tl.lw, tl.r, tl.f, tl.wf, tl.ks, tl.cc, eb);
+    const int lds = (int)k1_lds_layout_bytes(tl.lw, tl.r, tl.f, tl.wf, tl.ks, tl.cc, eb, tl.mode, tl.nbuf);
     plan->launch(a, (int)blocks, 64 * tl.wf * tl.ks, lds, stream);
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_DEVICE;
 }

@@ -11,8 +11,13 @@
 //     "input tiling"): WF of them work on different filter groups, KS of them split the input
 //     channels of each chunk and are summed through LDS at the end in a fixed order.
 //
+// Input tiles reach LDS without passing through registers where the shape allows it: gfx950's
+// direct global-to-LDS loads write 64 consecutive 16-byte (or 4-byte) slots per wavefront
+// instruction, asynchronously, so the tile of the next channel chunk is in flight into a second
+// buffer while the current chunk is consumed, at no cost in registers.
+//
 // Per input channel a lane reads its (R+2) x 6 input window from LDS once, with one 128-bit
-// (fp32) or 64-bit (fp16) read for the four interior columns and one read for the packed
+// (fp32) or 64-bit (fp16) read for the four interior columns and one 64-bit read for the
 // (left, right) halo pair per row, and reuses it from registers for every kernel of the
 // wavefront's filters that keeps that channel.  The multiply-accumulates of one kernel are a
 // straight-line block specialised on (filter slot, pattern): all register indices are static
@@ -36,6 +41,7 @@ struct K1Args {
     const uint32_t* stream;     // weight-stream entries
     const int32_t* wave_off;    // [G*KS] first entry per (group, split)
     const float* bias_pad;      // [G*F]
+    const int32_t* chan_map;    // [filter blocks][chunks*cc] input channel at each place of each chunk
     const int32_t* perm_pad;    // [G*F] original filter index or -1
     int32_t n, c_in, c_out, h, w;
     int32_t vh;                 // virtual output rows: n*(h+1)-1
@@ -47,7 +53,10 @@ struct K1Args {
     int32_t blocks_per_xcd;     // ceil(work_items / 8); the grid has 8 * blocks_per_xcd blocks
     int32_t groups;             // G
     int32_t wf, ks, cc, chunks;
-    int32_t vec;                // staging vector width in elements
+    int32_t vec;                // register staging: vector width in elements
+    int32_t mode;               // 0: staging through registers; 1: direct-to-LDS loads, 16-byte slots; 2: 4-byte slots
+    int32_t nbuf;               // direct modes: tile buffers in the ring (2..8)
+    int32_t table_offset;       // direct modes: byte offset of the slot tables in dynamic LDS (after the tile buffers; multiple of 16)
     int32_t relu;
 };
 
@@ -72,7 +81,9 @@ template <typename T, int N> __device__ __forceinline__ T vec_elem(const typenam
 }
 
 // A lane's input window for one channel: rows 0..R+1, columns -1..4, and the multiply-accumulate
-// of one of its elements with a wave-uniform weight.
+// of one of its elements with a wave-uniform weight.  LDS holds, per tile row, the interior
+// columns and, separately, one (left, right) pair of 32-bit words per micro-column: for fp32 the
+// two neighbour elements themselves, for fp16 the words (x[-2], x[-1]) and (x[4], x[5]).
 template <typename T, int R> struct Window;
 
 template <int R> struct Window<float, R> {
@@ -85,11 +96,11 @@ template <int R> struct Window<float, R> {
             halo[rr] = f32x2(0);
         }
     }
-    __device__ __forceinline__ void load(const float* pm, const float* ph, int rs) {
+    __device__ __forceinline__ void load(const float* pm, const float* ph, int rs, int hrs) {
 #pragma unroll
         for (int rr = 0; rr < R + 2; ++rr) {
             mid[rr] = *reinterpret_cast<const f32x4*>(pm + rr * rs);
-            halo[rr] = *reinterpret_cast<const f32x2*>(ph + rr * rs);
+            halo[rr] = *reinterpret_cast<const f32x2*>(ph + rr * hrs);
         }
     }
     template <int ROW, int COL> __device__ __forceinline__ void fma(float& acc, float w) const {
@@ -104,25 +115,27 @@ template <int R> struct Window<float, R> {
 // register, fp32 accumulator).  Written as inline assembly because the compiler otherwise
 // unpacks halves that are used several times with extra conversion instructions.
 template <int R> struct Window<_Float16, R> {
-    uint32_t mid[R + 2][2];   // columns (0,1), (2,3)
-    uint32_t halo[R + 2];     // (column -1, column 4)
+    uint32_t mid[R + 2][2];    // columns (0,1), (2,3)
+    uint32_t halo[R + 2][2];   // (column -2, column -1), (column 4, column 5)
     __device__ __forceinline__ void clear() {
 #pragma unroll
-        for (int rr = 0; rr < R + 2; ++rr) mid[rr][0] = mid[rr][1] = halo[rr] = 0u;
+        for (int rr = 0; rr < R + 2; ++rr) mid[rr][0] = mid[rr][1] = halo[rr][0] = halo[rr][1] = 0u;
     }
-    __device__ __forceinline__ void load(const _Float16* pm, const _Float16* ph, int rs) {
+    __device__ __forceinline__ void load(const _Float16* pm, const _Float16* ph, int rs, int hrs) {
         typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 #pragma unroll
         for (int rr = 0; rr < R + 2; ++rr) {
             const u32x2 m = *reinterpret_cast<const u32x2*>(pm + rr * rs);
+            const u32x2 h = *reinterpret_cast<const u32x2*>(ph + rr * hrs);
             mid[rr][0] = m[0];
             mid[rr][1] = m[1];
-            halo[rr] = *reinterpret_cast<const uint32_t*>(ph + rr * rs);
+            halo[rr][0] = h[0];
+            halo[rr][1] = h[1];
         }
     }
     template <int ROW, int COL> __device__ __forceinline__ void fma(float& acc, float w) const {
-        constexpr bool hi = (COL < 0) ? false : (COL > 3) ? true : (COL & 1) != 0;
-        const uint32_t src = (COL < 0 || COL > 3) ? halo[ROW] : mid[ROW][(COL < 0 ? 0 : COL) >> 1];
+        constexpr bool hi = (COL < 0) ? true : (COL > 3) ? false : (COL & 1) != 0;
+        const uint32_t src = (COL < 0) ? halo[ROW][0] : (COL > 3) ? halo[ROW][1] : mid[ROW][(COL < 0 ? 0 : COL) >> 1];
         if constexpr (hi)
             asm("v_fma_mix_f32 %0, %1, %2, %0 op_sel:[0,1,0] op_sel_hi:[0,1,0]" : "+v"(acc) : "s"(w), "v"(src));
         else
@@ -184,15 +197,14 @@ __device__ __forceinline__ void dispatch(int code, float (&acc)[F][R][4], const 
 }
 
 // ---------------------------------------------------------------------------------------------
-// Staging of one channel chunk into LDS (zero-filled outside the images), VEC elements per
-// global load.  The chunk is a list of ccn*trn tile rows of VPR vectors each; thread t takes
-// vectors t, t + nthreads, ...  Interior columns go to [row][0..TW); an element that is some
-// micro-tile's left or right neighbour is also written to that micro-tile's (left, right) halo
-// pair, which sits behind the interior at [row][HOFF + 2*mcol].  The pair array has one dummy pair
-// on each side so that these writes need no bounds test.
+// LDS tile of one channel: [rows][TW] interior elements, then [rows][LW] halo pairs of two 32-bit
+// words each.  Everything outside the images (padding rows, columns beyond W, the pairs of
+// neighbours that do not exist) is zero: the staging code never writes those places and the
+// buffers are zeroed once per workgroup.
 //
-// Two vectors per thread are loaded before either is written, and nothing looks at a loaded
-// value until then (out-of-image vectors read a valid dummy address and are zeroed when stored),
+// (1) Staging through registers, VEC elements per global load, for shapes whose rows are not
+// aligned for the direct path.  Thread t takes vectors t, t + nthreads, ... of the chunk; two
+// vectors are loaded before either is written and nothing looks at a loaded value until then,
 // so both loads are in flight together.
 template <typename T> struct StageRegs {
     uint32_t raw[2][4];   // up to 16 bytes per vector
@@ -201,19 +213,24 @@ template <typename T> struct StageRegs {
 
 template <typename T, int VEC, int LW, int R> struct Stager {
     static constexpr TileGeom tg = tile_geom(LW, R, (int)sizeof(T));
-    static constexpr int TW = tg.tw, VPR = TW / VEC, RS = tg.rs, CHS = tg.chs, HOFF = tg.hoff;
+    static constexpr int TW = tg.tw, VPR = TW / VEC, CHS = tg.chs, HOFF = tg.hoff, HRS = tg.hrs;
+    static constexpr int HP = HRS / LW;                      // elements per halo pair (2 for fp32, 4 for fp16)
     static constexpr int NB = VEC * (int)sizeof(T);
     static_assert(VPR >= 2, "a tile row must span at least two staging vectors");
     typedef typename VecOf<T, VEC>::type vec_t;
 
+    // element index, inside a halo pair, of the left / right neighbour
+    static constexpr int kLeft = HP == 2 ? 0 : 1, kRight = HP == 2 ? 1 : 2;
+
     static __device__ __forceinline__ void load(StageRegs<T>& sr, int u, int i, int total, const T* xc0,
-                                                const int* rowtab, int trn, uint32_t trn_magic, int x0, int W, int hw) {
+                                                const int32_t* __restrict__ cmap, const int* rowtab, int trn,
+                                                uint32_t trn_magic, int x0, int W, int hw) {
         const int row = i / VPR, v = i - row * VPR;              // VPR is a compile-time constant
         const int c = (int)__umulhi((uint32_t)row, trn_magic);   // row / trn (exact for row < 2^16)
         const int tr = row - c * trn;
         const int rb = i < total ? rowtab[tr] : -1;
         const int col = x0 + v * VEC;
-        const uint32_t chan = (uint32_t)(c * hw);
+        const uint32_t chan = (uint32_t)((i < total ? cmap[c] : 0) * hw);   // the channel staged at place c of the chunk
         const uint32_t goff = (rb >= 0 && col < W) ? chan + (uint32_t)(rb + col) : 0u;
         const vec_t val = *reinterpret_cast<const vec_t*>(xc0 + goff);
         __builtin_memcpy(&sr.raw[u][0], &val, NB);
@@ -230,49 +247,43 @@ template <typename T, int VEC, int LW, int R> struct Stager {
         const int c = (int)__umulhi((uint32_t)row, trn_magic);
         const int tr = row - c * trn;
         const bool in_img = rowtab[tr] >= 0;
-        T* trow = tile + c * CHS + tr * RS;
+        T* tc = tile + c * CHS;
         vec_t val;
         __builtin_memcpy(&val, &sr.raw[u][0], NB);
         if (!(in_img && x0 + v * VEC < W)) val = vec_t(0);
-        *reinterpret_cast<vec_t*>(trow + v * VEC) = val;
-        T* hrow = trow + HOFF;
+        *reinterpret_cast<vec_t*>(tc + tr * TW + v * VEC) = val;
+        T* hrow = tc + HOFF + tr * HRS;
 #pragma unroll
         for (int k = 0; k < VEC; ++k) {
-            const int sc = v * VEC + k;
+            const int sc = v * VEC + k;                                       // column inside the strip
             const T e = vec_elem<T, VEC>(val, k);
-            if (VEC >= 4) {                                   // which elements are neighbours is static
-                if ((k & 3) == 0) hrow[2 * (sc / 4 - 1) + 1] = e;
-                if ((k & 3) == 3) hrow[2 * (sc / 4 + 1)] = e;
-            } else {
-                if ((sc & 3) == 0) hrow[2 * (sc / 4 - 1) + 1] = e;
-                if ((sc & 3) == 3) hrow[2 * (sc / 4 + 1)] = e;
-            }
+            if ((sc & 3) == 0 && sc >= 4) hrow[(sc / 4 - 1) * HP + kRight] = e;     // right neighbour of the micro-column before
+            if ((sc & 3) == 3 && sc + 1 < TW) hrow[(sc / 4 + 1) * HP + kLeft] = e;  // left neighbour of the next one
         }
         const int ecol = v == 0 ? x0 - 1 : x0 + TW;
         const T edge = (in_img && ecol >= 0 && ecol < W) ? sr.edge[u] : T(0);
-        if (v == 0) hrow[0] = edge;
-        if (v == VPR - 1) hrow[2 * (LW - 1) + 1] = edge;
+        if (v == 0) hrow[kLeft] = edge;
+        if (v == VPR - 1) hrow[(LW - 1) * HP + kRight] = edge;
     }
 
-    static __device__ __forceinline__ void stage(const T* x, T* tile, const int* rowtab, int c0, int ccn, int trn,
+    static __device__ __forceinline__ void stage(const T* x, const int32_t* cmap, T* tile, const int* rowtab, int ccn, int trn,
                                                  uint32_t trn_magic, int x0, int W, int hw, int tid, int nthreads) {
         // Everything derived from the thread index is the same for every chunk; recomputing it is a
         // few integer instructions, keeping it live across the multiply-accumulate loop would cost
         // a dozen registers.  The empty asm makes the index opaque so that it is recomputed.
         asm volatile("" : "+v"(tid));
         const int total = ccn * trn * VPR;
-        const T* xc0 = x + (int64_t)c0 * hw;
+        const T* xc0 = x;
         StageRegs<T> sr;
         for (int i0 = tid; i0 < total; i0 += 2 * nthreads) {
-            load(sr, 0, i0, total, xc0, rowtab, trn, trn_magic, x0, W, hw);
-            load(sr, 1, i0 + nthreads, total, xc0, rowtab, trn, trn_magic, x0, W, hw);
+            load(sr, 0, i0, total, xc0, cmap, rowtab, trn, trn_magic, x0, W, hw);
+            load(sr, 1, i0 + nthreads, total, xc0, cmap, rowtab, trn, trn_magic, x0, W, hw);
             store(sr, 0, i0, total, tile, rowtab, trn, trn_magic, x0, W);
             store(sr, 1, i0 + nthreads, total, tile, rowtab, trn, trn_magic, x0, W);
         }
     }
 };
 
-// Run the staging routine with the vector width picked at launch time.
 #define PPC_STAGE_DISPATCH(VECVAR, CALL)                                        \
     switch (VECVAR) {                                                           \
         case 8:                                                                 \
@@ -283,14 +294,169 @@ template <typename T, int VEC, int LW, int R> struct Stager {
         default: Stager<T, 1, LW, R>::CALL; break;                              \
     }
 
+// (2) Direct staging.  One wavefront instruction moves 64 slots of SLOT bytes from per-lane
+// global addresses to 64 consecutive slots of LDS, asynchronously (counted by vmcnt).  The
+// interior of a channel tile is ROWS*TW*sizeof(T)/SLOT slots, its halo area ROWS*LW*2 four-byte
+// slots: NI + NH instructions per channel.  Which global element a lane fetches for instruction
+// `it` of that sequence is the same for every channel and chunk, so it is tabulated once per
+// workgroup as a byte offset from the channel's first element in use; kNoSlot marks a lane that
+// must not write (outside the images, or past the end of its area).  Such places are never
+// written at all: the buffers are zeroed once, before the first load, and stay zero there.
+//
+// Buffers form a ring of NB; the loads of up to NB-1 chunks are in flight while one chunk is
+// consumed.  Loads of one wavefront complete in order, so "chunk q has landed" is "at most as
+// many loads outstanding as this wavefront has issued for later chunks" -- which needs the exact
+// number of load instructions per chunk: an instruction without a single valid lane is skipped by
+// a wave-uniform test, and every other one is issued unconditionally.
+template <typename T, int SLOT, int LW, int R> struct DirectStager {
+    static constexpr TileGeom tg = tile_geom(LW, R, (int)sizeof(T));
+    static constexpr int TW = tg.tw, CHS = tg.chs, HOFF = tg.hoff, HRS = tg.hrs, ROWS = tg.rows;
+    static constexpr int ES = SLOT / (int)sizeof(T);                  // elements per interior slot
+    static constexpr int SPR = TW / ES;                               // interior slots per tile row
+    static constexpr bool kUsable = TW % ES == 0;                     // (fp16, LW = 7 has 56-byte rows: 4-byte slots only)
+    static constexpr int HE = 4 / (int)sizeof(T);                     // elements per halo slot (one 32-bit word)
+    static constexpr int NI = (ROWS * SPR + 63) / 64, NH = (ROWS * LW * 2 + 63) / 64, NPER = NI + NH;
+    static constexpr uint32_t kNoSlot = 0xFFFFFFFFu;
+
+    // How the NPER instructions of each of a chunk's channels are dealt to the wavefronts:
+    // wavefront w issues instruction w % NPER (and, with fewer wavefronts than instructions,
+    // every nwaves-th one after it) for the channels phase, phase + nphase, ...
+    struct Deal {
+        int it0, phase, nphase;
+        int valid_its;      // how many of this wavefront's instructions have a valid lane
+    };
+
+    static __device__ __forceinline__ void build(uint32_t* table, const int* rowtab, int rb0, int trn, int x0, int W,
+                                                 int tid, int nthreads) {
+        for (int j = tid; j < NI * 64; j += nthreads) {
+            const int tr = j / SPR, v = j - tr * SPR;
+            uint32_t off = kNoSlot;
+            if (tr < trn) {
+                const int rb = rowtab[tr];
+                const int col = x0 + v * ES;
+                if (rb >= 0 && col < W) off = (uint32_t)(rb - rb0 + col) * (uint32_t)sizeof(T);
+            }
+            table[j] = off;
+        }
+        uint32_t* htab = table + NI * 64;
+        for (int j = tid; j < NH * 64; j += nthreads) {
+            const int tr = j / (2 * LW), rem = j - tr * (2 * LW);
+            const int mc = rem >> 1, side = rem & 1;
+            uint32_t off = kNoSlot;
+            if (tr < trn) {
+                const int rb = rowtab[tr];
+                // the word that holds the neighbour: fp32 the element itself; fp16 the aligned pair
+                // (x[-2], x[-1]) on the left, (x[4], x[5]) on the right
+                const int need = x0 + 4 * mc + (side ? 4 : -1);            // column of the neighbour element
+                const int first = side ? need : need - (HE - 1);           // first column of the word
+                if (rb >= 0 && need >= 0 && need < W) off = (uint32_t)(rb - rb0 + first) * (uint32_t)sizeof(T);
+            }
+            htab[j] = off;
+        }
+    }
+
+    static __device__ __forceinline__ void deal(Deal& d, const uint32_t* table, int wave, int nwaves, int lane) {
+        d.nphase = nwaves / NPER > 0 ? nwaves / NPER : 1;
+        d.it0 = wave % NPER;
+        d.phase = wave / NPER;
+        d.valid_its = 0;
+        if (d.phase >= d.nphase) {
+            d.it0 = NPER;          // spare wavefront: issues nothing
+            return;
+        }
+        for (int it = d.it0; it < NPER; it += nwaves)
+            if (__builtin_amdgcn_ballot_w64(table[it * 64 + lane] != kNoSlot) != 0) ++d.valid_its;
+    }
+    // load instructions this wavefront issues for a chunk of ccn channels
+    static __device__ __forceinline__ int loads_per_chunk(const Deal& d, int ccn) {
+        const int nch = ccn > d.phase ? (ccn - d.phase + d.nphase - 1) / d.nphase : 0;
+        return nch * d.valid_its;
+    }
+
+    static __device__ __forceinline__ void run_setup(const uint32_t* table, int wave, int nwaves, int lane, int cc,
+                                                     int ccn_last, int& it0, int& phase, int& nphase, int& valid,
+                                                     int& loads_full, int& loads_last) {
+        Deal d;
+        deal(d, table, wave, nwaves, lane);
+        it0 = d.it0;
+        phase = d.phase;
+        nphase = d.nphase;
+        valid = d.valid_its;
+        loads_full = loads_per_chunk(d, cc);
+        loads_last = loads_per_chunk(d, ccn_last);
+    }
+
+    // One direct load: lanes with a slot fetch SLOT bytes at base + off into LDS at lds_dst + lane*SLOT.
+    // Inline assembly rather than the compiler builtin on purpose: the compiler cannot tell which
+    // later LDS reads an in-flight direct load may alias and would wait for all of them before the
+    // first read of another buffer, which is exactly the overlap this path exists for.
+    template <int BYTES>
+    static __device__ __forceinline__ void dma(uint32_t off, const void* base, uint32_t lds_dst) {
+        if constexpr (BYTES == 16)
+            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(lds_dst) : "memory");
+        else
+            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(off), "s"(base), "s"(lds_dst) : "memory");
+    }
+
+    // Start the loads of channels [c0, c0+ccn) into the buffer at LDS byte address lds_buf.
+    // xrow0: the first element in use of channel 0 (image base + first valid tile row).
+    // cmap: the channels of this chunk, by place (wave-uniform reads from constant memory).
+    static __device__ __forceinline__ void issue(const Deal& d, const T* __restrict__ xrow0, uint32_t lds_buf,
+                                                 const uint32_t* table, const __attribute__((address_space(4))) int32_t* cmap,
+                                                 int ccn, int hw, int nwaves, int lane) {
+        for (int it = d.it0; it < NPER; it += nwaves) {               // wave-uniform; one pass unless NPER > nwaves
+            const uint32_t off = table[it * 64 + lane];
+            const bool ok = off != kNoSlot;
+            if (__builtin_amdgcn_ballot_w64(ok) == 0) continue;
+            const uint32_t lds_it = lds_buf + (uint32_t)(it < NI ? it * 64 * SLOT : HOFF * (int)sizeof(T) + (it - NI) * 64 * 4);
+            for (int c = d.phase; c < ccn; c += d.nphase) {
+                const T* xc = xrow0 + (int64_t)cmap[c] * hw;
+                const uint32_t dst = lds_it + (uint32_t)(c * CHS * (int)sizeof(T));
+                if (ok) {
+                    if (it < NI) dma<SLOT>(off, xc, dst);
+                    else dma<4>(off, xc, dst);
+                }
+            }
+        }
+    }
+};
+
+#define PPC_DIRECT_DISPATCH(MODEVAR, CALL)                                      \
+    if (MODEVAR == 1) {                                                         \
+        typedef DirectStager<T, 16, LW, R> ST;                                  \
+        if constexpr (ST::kUsable) { ST::CALL; }                                \
+    } else {                                                                    \
+        typedef DirectStager<T, 4, LW, R> ST;                                   \
+        ST::CALL;                                                               \
+    }
+
+// Wait until at most n of this wavefront's vector-memory operations are outstanding (the count is
+// an immediate of the instruction; the hardware counter has 6 bits).
+__device__ __forceinline__ void wait_vmcnt_at_most(int n) {
+#define PPC_W(N) case N: asm volatile("s_waitcnt vmcnt(" #N ")" ::: "memory"); break;
+    switch (n) {
+        PPC_W(0) PPC_W(1) PPC_W(2) PPC_W(3) PPC_W(4) PPC_W(5) PPC_W(6) PPC_W(7)
+        PPC_W(8) PPC_W(9) PPC_W(10) PPC_W(11) PPC_W(12) PPC_W(13) PPC_W(14) PPC_W(15)
+        PPC_W(16) PPC_W(17) PPC_W(18) PPC_W(19) PPC_W(20) PPC_W(21) PPC_W(22) PPC_W(23)
+        PPC_W(24) PPC_W(25) PPC_W(26) PPC_W(27) PPC_W(28) PPC_W(29) PPC_W(30) PPC_W(31)
+        PPC_W(32) PPC_W(33) PPC_W(34) PPC_W(35) PPC_W(36) PPC_W(37) PPC_W(38) PPC_W(39)
+        PPC_W(40) PPC_W(41) PPC_W(42) PPC_W(43) PPC_W(44) PPC_W(45) PPC_W(46) PPC_W(47)
+        PPC_W(48) PPC_W(49) PPC_W(50) PPC_W(51) PPC_W(52) PPC_W(53) PPC_W(54) PPC_W(55)
+        PPC_W(56) PPC_W(57) PPC_W(58) PPC_W(59) PPC_W(60) PPC_W(61) PPC_W(62)
+        default: break;     // 63 or more: the counter cannot exceed that, nothing to wait for
+    }
+#undef PPC_W
+}
+
 // Variants with at most 32 accumulators per lane are asked to fit 64 vector registers, i.e. 8
 // resident wavefronts per SIMD: two 16-wavefront workgroups per CU, which is what hides the scalar
 // dispatch and LDS latency of one behind the multiply-accumulates of the other.
-template <typename T, int NP, int R, int F, int LW>
+template <typename T, int NP, int R, int F, int LW, bool DIRECT>
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(F * R * 4 <= 32 ? 8 : 4)))
 void k1_tiled(const K1Args a) {
     constexpr TileGeom tg = tile_geom(LW, R, (int)sizeof(T));
-    constexpr int TW = tg.tw, RS = tg.rs, CHS = tg.chs, ROWS = tg.rows, HOFF = tg.hoff;
+    constexpr int TW = tg.tw, RS = tg.rs, CHS = tg.chs, ROWS = tg.rows, HOFF = tg.hoff, HRS = tg.hrs;
+    constexpr int HP = HRS / LW;                    // elements per halo pair
     constexpr int EW = 8;                           // 32-bit words per stream entry
     extern __shared__ __align__(16) unsigned char smem_raw[];
     __shared__ int rowtab[ROWS];
@@ -348,10 +514,11 @@ void k1_tiled(const K1Args a) {
             for (int k = 0; k < 4; ++k) acc[f][rr][k] = 0.0f;
 
     const T* lane_mid = tile + lr * R * RS + 4 * mcol;
-    const T* lane_halo = tile + lr * R * RS + HOFF + 2 * mcol;
+    const T* lane_halo = tile + HOFF + lr * R * HRS + HP * mcol;
     const int hw = a.h * a.w;
     const uint32_t trn_magic = 0xFFFFFFFFu / (uint32_t)trn + 1u;      // ceil(2^32 / trn), trn >= 3
     const T* __restrict__ xin = static_cast<const T*>(a.x);
+    const int32_t* __restrict__ cmap = a.chan_map + (int64_t)fb * a.chunks * a.cc;   // this filter block's channel order
 
     // this wavefront's entry stream (constant address space: wave-uniform loads from it are scalar loads)
     typedef const __attribute__((address_space(4))) uint32_t* stream_ptr_t;
@@ -361,12 +528,69 @@ void k1_tiled(const K1Args a) {
     // behind the previous kernel's multiply-accumulates
     uint32_t n_head = sp[0], n_w0 = sp[4], n_w1 = sp[5], n_w2 = sp[6], n_w3 = sp[7];
 
+    // Direct staging: ring of a.nbuf buffers of a.cc channels each; the loads of the next
+    // a.nbuf - 1 chunks are in flight while a chunk is consumed.
+    typedef __attribute__((address_space(3))) unsigned char* lds_byte_ptr;
+    const uint32_t lds_tile = (uint32_t)(uintptr_t)(lds_byte_ptr)smem_raw;   // LDS byte address of buffer 0
+    const int buf_elems = a.cc * CHS;
+    const uint32_t* table = reinterpret_cast<const uint32_t*>(smem_raw + a.table_offset);
+    const T* xrow0 = xin;
+    int d_it0 = 0, d_phase = 0, d_nphase = 1, d_valid = 0, loads_full = 0, loads_last = 0;
+#define PPC_DEAL(ST) typename ST::Deal{d_it0, d_phase, d_nphase, d_valid}
+    const int ahead = a.nbuf - 1;
+    if constexpr (DIRECT) {
+        // zero every buffer once: places without a slot are never written afterwards
+        for (int i = threadIdx.x * 16; i < a.table_offset; i += blockDim.x * 16)
+            *reinterpret_cast<f32x4*>(smem_raw + i) = f32x4(0);
+        __syncthreads();          // rowtab written, buffers zeroed
+        int rb0 = rowtab[0];
+        if (rb0 < 0) rb0 = rowtab[1];
+        if (rb0 < 0) rb0 = rowtab[2];          // two consecutive virtual rows are never both outside the images
+        if (rb0 < 0) rb0 = 0;
+        rb0 = __builtin_amdgcn_readfirstlane(rb0);
+        xrow0 = xin + rb0;
+        PPC_DIRECT_DISPATCH(a.mode, build(reinterpret_cast<uint32_t*>(smem_raw + a.table_offset), rowtab, rb0, trn, x0, a.w,
+                                          threadIdx.x, blockDim.x))
+        __syncthreads();
+        const int ccn_last = a.c_in - (a.chunks - 1) * a.cc;
+        PPC_DIRECT_DISPATCH(a.mode, run_setup(table, wave, nwaves, lane, a.cc, ccn_last, d_it0, d_phase, d_nphase,
+                                                               d_valid, loads_full, loads_last))
+        for (int q = 0; q < ahead && q < a.chunks; ++q) {
+            const int ccn = (a.c_in - q * a.cc < a.cc) ? a.c_in - q * a.cc : a.cc;
+            PPC_DIRECT_DISPATCH(a.mode, issue(PPC_DEAL(ST), xrow0, lds_tile + (uint32_t)(q * buf_elems * (int)sizeof(T)), table,
+                                              (const_i32_ptr_t)cmap + q * a.cc, ccn, hw, nwaves, lane))
+        }
+    }
+
+    int ring = 0;                 // buffer that holds chunk q
     for (int q = 0; q < a.chunks; ++q) {
         const int c0 = q * a.cc;
         const int ccn = (a.c_in - c0 < a.cc) ? a.c_in - c0 : a.cc;
-        __syncthreads();          // previous chunk fully consumed (and rowtab written, first time round)
-        PPC_STAGE_DISPATCH(a.vec, stage(xin, tile, rowtab, c0, ccn, trn, trn_magic, x0, a.w, hw, threadIdx.x, blockDim.x))
-        __syncthreads();
+        int boff = 0;             // element offset of the buffer this chunk is read from
+        if constexpr (DIRECT) {
+            // chunk q has landed once no more loads are outstanding than were issued for the chunks
+            // after it (q+1 .. q+ahead-1, as far as they exist; all but the last chunk are full)
+            int later = a.chunks - 1 - q;
+            if (later > ahead - 1) later = ahead - 1;
+            int allowed = later * loads_full;
+            if (later > 0 && q + later == a.chunks - 1) allowed += loads_last - loads_full;
+            wait_vmcnt_at_most(allowed);
+            __syncthreads();      // everyone's loads of chunk q have landed; everyone is done with chunk q-1
+            boff = ring * buf_elems;
+            const int qn = q + ahead;            // goes into the buffer chunk q-1 was read from
+            if (qn < a.chunks) {
+                const int cn0 = qn * a.cc;
+                const int ccn1 = (a.c_in - cn0 < a.cc) ? a.c_in - cn0 : a.cc;
+                const int slot = ring == 0 ? ahead : ring - 1;
+                PPC_DIRECT_DISPATCH(a.mode, issue(PPC_DEAL(ST), xrow0, lds_tile + (uint32_t)(slot * buf_elems * (int)sizeof(T)), table,
+                                                  (const_i32_ptr_t)cmap + cn0, ccn1, hw, nwaves, lane))
+            }
+            ring = ring + 1 == a.nbuf ? 0 : ring + 1;
+        } else {
+            __syncthreads();      // previous chunk fully consumed (and rowtab written, first time round)
+            PPC_STAGE_DISPATCH(a.vec, stage(xin, cmap + c0, tile, rowtab, ccn, trn, trn_magic, x0, a.w, hw, threadIdx.x, blockDim.x))
+            __syncthreads();
+        }
         if (!has_group) continue;
 
         Window<T, R> win;
@@ -377,8 +601,8 @@ void k1_tiled(const K1Args a) {
                                  __builtin_bit_cast(float, n_w2), __builtin_bit_cast(float, n_w3)};
             const bool at_end = (head & kFlagEnd) != 0;
             if (!at_end && (head & kFlagNewChannel)) {
-                const int cl = (int)(head >> kChanShift);
-                win.load(lane_mid + cl * CHS, lane_halo + cl * CHS, RS);
+                const int cl = (int)(head >> kChanShift) * CHS + boff;
+                win.load(lane_mid + cl, lane_halo + cl, RS, HRS);
                 // Wait for the window here, before the next entry's scalar load is issued: LDS reads
                 // and scalar loads share one counter, so a wait placed later (inside the kernel
                 // blocks) would also wait for that prefetch and expose its latency on every kernel.
@@ -464,16 +688,8 @@ void k1_tiled(const K1Args a) {
     }
 }
 
-// Dynamic LDS bytes a launch needs: the tile, or the split-channel exchange area if larger.
-inline int k1_lds_bytes(int lw, int r, int f, int wf, int ks, int cc, int elem_bytes) {
-    TileGeom tg = tile_geom(lw, r, elem_bytes);
-    int tile = cc * tg.chs * elem_bytes;
-    int red = ks > 1 ? wf * f * r * 4 * 64 * 4 : 0;
-    return tile > red ? tile : red;
-}
-
 typedef void (*k1_launch_fn)(const K1Args& a, int blocks, int threads, int lds_bytes, hipStream_t stream);
-// Look up the instantiation for (dtype, np, r, f, lw); nullptr if that combination is not built.
-k1_launch_fn k1_lookup(int dtype, int np, int r, int f, int lw);
+// Look up the instantiation for (dtype, np, r, f, lw, staging path); nullptr if that combination is not built.
+k1_launch_fn k1_lookup(int dtype, int np, int r, int f, int lw, bool direct);
 
 }  // namespace ppc

@@ -265,15 +265,59 @@ pp_status_t build_layouts(const pp_conv_desc_t& d, HostPlan& hp) {
     while (!t.waves_f && tl.wf > 1 && reduce_bytes() > kMaxDynamicLds) tl.wf /= 2;
     if (reduce_bytes() > kMaxDynamicLds) return PP_ERR_UNSUPPORTED;
     const TileGeom tg = tile_geom(tl.lw, tl.r, eb);
-    tl.cc = t.chunk_c;
-    if (tl.cc == 0) {
-        int fit = (kMaxDynamicLds) / (tg.chs * eb);
-        fit = std::min(fit, 32);
-        fit = std::min(fit, (hp.c_in + tl.ks - 1) / tl.ks * tl.ks);
-        tl.cc = std::max(tl.ks, fit / tl.ks * tl.ks);
+    // How input tiles reach LDS: direct global-to-LDS loads in 16-byte slots when every image row
+    // and every strip starts on a 16-byte boundary, in 4-byte slots when they start on a 4-byte
+    // boundary, through registers otherwise (fp16 rows of odd width).  The direct path addresses a
+    // channel's rows with 32-bit byte offsets from the first row of the tile.
+    if (t.staging < 0 || t.staging > 8) return PP_ERR_UNSUPPORTED;
+    tl.mode = 0;
+    if (t.staging != 1 && ((int64_t)hp.c_in * hp.h * hp.w + (int64_t)tg.rows * hp.w) * eb < ((int64_t)1 << 31)) {
+        if (hp.w % (16 / eb) == 0 && (tg.tw * eb) % 16 == 0) tl.mode = 1;
+        else if (eb == 4 || hp.w % 2 == 0) tl.mode = 2;
     }
+    if (t.staging >= 2 && tl.mode == 0) return PP_ERR_UNSUPPORTED;
+    const int nw = tl.wf * tl.ks;
+    const int64_t spatial_wgs = spatial_waves(hp.n_hint, hp.h, hp.w, tl.lw, tl.r);
+    const int64_t total_wgs = spatial_wgs * ((groups_f + tl.wf - 1) / tl.wf);
+    // LDS one workgroup may take: all of it when there is at most about one workgroup per CU anyway,
+    // else a share that lets as many workgroups be resident as the wavefront slots allow (8 per SIMD
+    // for the small-accumulator variants, else 4)
+    const int wg_per_cu = total_wgs <= 320 ? 1 : std::max(1, ((tl.f * tl.r * 4 <= 32) ? 32 : 16) / nw);
+    const int64_t budget = std::min<int64_t>(kMaxDynamicLds, 160 * 1024 / wg_per_cu - 1024);
+    const int64_t chan_bytes = (int64_t)tg.chs * eb;
+    const int cap = std::min(32, (hp.c_in + tl.ks - 1) / tl.ks * tl.ks);
+    tl.cc = t.chunk_c;
+    tl.nbuf = tl.mode ? (t.staging >= 2 ? t.staging : 0) : 1;
+    auto lds_bytes = [&](int cc, int nbuf) { return k1_lds_layout_bytes(tl.lw, tl.r, tl.f, tl.wf, tl.ks, cc, eb, tl.mode, nbuf); };
+    if (tl.mode == 0) {
+        if (tl.cc == 0) {
+            int cc = tl.ks;
+            while (cc + tl.ks <= cap && lds_bytes(cc + tl.ks, 1) <= budget) cc += tl.ks;
+            tl.cc = cc;
+        }
+    } else {
+        // channels of LDS available to the ring
+        auto fit = [&](int64_t bytes) { return (int)std::max<int64_t>(0, (bytes - k1_lds_table_bytes(tl.lw, tl.r, eb, tl.mode)) / chan_bytes); };
+        if (tl.cc == 0 && tl.nbuf == 0) {
+            // Measured: what a chunk costs besides its multiply-accumulates (barrier, stream
+            // bookkeeping, issuing loads) outweighs what deeper prefetch gains, so two large buffers.
+            int ct = fit(budget);
+            if (ct < 2 * std::max(tl.ks, 4)) ct = fit(kMaxDynamicLds);       // a ring too small to be worth a second workgroup
+            tl.nbuf = 2;
+            tl.cc = std::max(tl.ks, std::min(cap, ct / tl.nbuf) / tl.ks * tl.ks);
+        } else if (tl.cc == 0) {
+            int ct = fit(budget);
+            if (ct < tl.nbuf * tl.ks) ct = fit(kMaxDynamicLds);
+            tl.cc = std::max(tl.ks, std::min(cap, ct / tl.nbuf) / tl.ks * tl.ks);
+        } else if (tl.nbuf == 0) {
+            tl.nbuf = std::max(2, std::min(4, fit(budget) / tl.cc));
+        }
+        const int chunks = (hp.c_in + tl.cc - 1) / tl.cc;
+        if (t.staging < 2) tl.nbuf = std::max(2, std::min(tl.nbuf, chunks));   // no more buffers than chunks
+    }
+    if (tl.nbuf < 1 || tl.nbuf > 8) return PP_ERR_UNSUPPORTED;
+    if (lds_bytes(std::max(tl.cc, 1), tl.nbuf) > kMaxDynamicLds) return PP_ERR_UNSUPPORTED;
     if (tl.cc < tl.ks || tl.cc % tl.ks != 0 || tl.cc > 512 || tl.cc * tg.rows >= 65536) return PP_ERR_UNSUPPORTED;
-    if ((int64_t)tl.cc * tg.chs * eb > kMaxDynamicLds) return PP_ERR_UNSUPPORTED;
     tl.groups = groups_f;
     tl.chunks = (hp.c_in + tl.cc - 1) / tl.cc;
     hp.chosen.filters_per_wave = tl.f;
@@ -282,22 +326,108 @@ pp_status_t build_layouts(const pp_conv_desc_t& d, HostPlan& hp) {
     hp.chosen.waves_f = tl.wf;
     hp.chosen.split_c = tl.ks;
     hp.chosen.chunk_c = tl.cc;
+    hp.chosen.staging = tl.mode ? tl.nbuf : 1;
 
-    // ---- weight stream: one sequence of entries per (filter group, channel split) wavefront ----
+    // ---- device layout: which filter sits in which wavefront slot, which channel in which chunk ----
+    // The wavefronts of a workgroup meet at a barrier once per channel chunk, so what a chunk costs
+    // is what its busiest wavefront does in it.  Two static choices even that out; neither changes
+    // the reordered layer-wise representation reported by pp_conv_plan_query:
+    //  (1) inside a filter block (the wf*f consecutive filters of the new order that one workgroup
+    //      computes) filters are dealt to the wf groups heaviest first, each to the group with the
+    //      least kernels so far that still has a free slot;
+    //  (2) per filter block the input channels are put into chunks (and, with split_c > 1, into the
+    //      channel ranges of the splits) greedily, each time taking the channel that keeps the
+    //      per-group cost of the range closest to an even share.
     const Canonical& cn = hp.canon;
     const int G = tl.groups, F = tl.f, KS = tl.ks, CC = tl.cc, Q = tl.chunks, CS = CC / KS, EW = tl.entry_words;
+    const int WF = tl.wf, NFB = (G + WF - 1) / WF, C = hp.c_in;
+    if (t.balance < 0 || t.balance > 2) return PP_ERR_UNSUPPORTED;
+    const bool balance = t.balance != 1 && WF * KS > 1;
+    hp.chosen.balance = balance ? 2 : 1;
+    tl.slot_pos.assign((size_t)G * F, -1);
+    tl.chan_map.assign((size_t)NFB * Q * CC, -1);
+    const int per_kernel = dense ? 3 : 1;
+    std::vector<float> cost;
+    std::vector<double> load, share, sums;
+    std::vector<int> room, left;
+    for (int fb = 0; fb < NFB; ++fb) {
+        const int g0 = fb * WF, ng = std::min(WF, G - g0);
+        const int pos0 = g0 * F, pos1 = std::min(hp.c_out, (g0 + ng) * F);
+        int32_t* cmap = &tl.chan_map[(size_t)fb * Q * CC];
+        if (!balance) {
+            for (int pos = pos0; pos < pos1; ++pos) tl.slot_pos[pos] = pos;
+            for (int ci = 0; ci < C; ++ci) cmap[ci] = ci;
+            continue;
+        }
+        // (1) filters come in descending kernel count already
+        load.assign(ng, 0.0);
+        room.assign(ng, F);
+        for (int pos = pos0; pos < pos1; ++pos) {
+            int best = -1;
+            for (int g = 0; g < ng; ++g)
+                if (room[g] > 0 && (best < 0 || load[g] < load[best])) best = g;
+            tl.slot_pos[(size_t)(g0 + best) * F + (F - room[best])] = pos;
+            load[best] += cn.kcount[pos];
+            --room[best];
+        }
+        // cost of channel ci to group g: its kernels there, plus half a kernel for loading the window
+        cost.assign((size_t)ng * C, 0.0f);
+        for (int g = 0; g < ng; ++g)
+            for (int fl = 0; fl < F; ++fl) {
+                const int pos = tl.slot_pos[(size_t)(g0 + g) * F + fl];
+                if (pos < 0) continue;
+                for (int64_t e = hp.filt_off[pos]; e < hp.filt_off[pos + 1]; ++e) cost[(size_t)g * C + cn.kidx[e]] += (float)per_kernel;
+            }
+        share.assign(ng, 0.0);
+        for (int g = 0; g < ng; ++g)
+            for (int ci = 0; ci < C; ++ci) {
+                float& v = cost[(size_t)g * C + ci];
+                if (v > 0.0f) v += 0.5f;
+                share[g] += v / C;                   // the group's cost per channel if spread evenly
+            }
+        // (2) fill the ranges in order; candidates are looked for among the first kScan channels left
+        const int kScan = 512;
+        left.resize(C);
+        for (int ci = 0; ci < C; ++ci) left[ci] = ci;
+        sums.assign(ng, 0.0);
+        for (int p = 0; p < C; ++p) {
+            const int k = p % CS;                    // channels already in this range
+            if (k == 0) std::fill(sums.begin(), sums.end(), 0.0);
+            const int ncand = std::min<int>(kScan, (int)left.size());
+            int best = 0;
+            double best_score = 0.0;
+            for (int j = 0; j < ncand; ++j) {
+                const int ci = left[j];
+                double score = -1e30;
+                for (int g = 0; g < ng; ++g) score = std::max(score, sums[g] + cost[(size_t)g * C + ci] - share[g] * (k + 1));
+                if (j == 0 || score < best_score) {
+                    best = j;
+                    best_score = score;
+                }
+            }
+            const int ci = left[best];
+            left.erase(left.begin() + best);
+            for (int g = 0; g < ng; ++g) sums[g] += cost[(size_t)g * C + ci];
+            cmap[p] = ci;
+        }
+    }
     tl.perm_pad.assign((size_t)G * F, -1);
     tl.bias_pad.assign((size_t)G * F, 0.0f);
-    for (int pos = 0; pos < hp.c_out; ++pos) {
-        tl.perm_pad[pos] = cn.perm[pos];
-        tl.bias_pad[pos] = hp.bias[cn.perm[pos]];
+    for (size_t sl = 0; sl < tl.slot_pos.size(); ++sl) {
+        const int pos = tl.slot_pos[sl];
+        if (pos < 0) continue;
+        tl.perm_pad[sl] = cn.perm[pos];
+        tl.bias_pad[sl] = hp.bias[cn.perm[pos]];
     }
+
+    // ---- weight stream: one sequence of entries per (filter group, channel split) wavefront ----
     struct Item { int32_t ci; int32_t fl; int32_t slot; int64_t src; int32_t part; };
     static const int kDenseSlot[3] = {4, 7, 8};                       // built-in slots of the three cover patterns
     static const int kDenseTap[3][4] = {{0, 1, 3, 4}, {-1, 5, 7, 8}, {-1, 2, -1, 6}};   // source tap of each weight, -1: zero
     tl.stream.clear();
     tl.wave_off.assign((size_t)G * KS, 0);
     std::vector<Item> items;
+    std::vector<size_t> first(C + 1);
     auto push_entry = [&](uint32_t header, const float* w4) {
         size_t at = tl.stream.size();
         tl.stream.resize(at + EW, 0u);
@@ -309,10 +439,11 @@ pp_status_t build_layouts(const pp_conv_desc_t& d, HostPlan& hp) {
         std::memcpy(&tl.stream[at + 4], wv, 16);
     };
     for (int g = 0; g < G; ++g) {
+        const int32_t* cmap = &tl.chan_map[(size_t)(g / WF) * Q * CC];
         items.clear();
         for (int fl = 0; fl < F; ++fl) {
-            int pos = g * F + fl;
-            if (pos >= hp.c_out) break;
+            const int pos = tl.slot_pos[(size_t)g * F + fl];
+            if (pos < 0) continue;
             for (int64_t e = hp.filt_off[pos]; e < hp.filt_off[pos + 1]; ++e) {
                 if (!dense) {
                     items.push_back(Item{cn.kidx[e], fl, slot_of[cn.kpat[e]], e, 0});
@@ -326,29 +457,31 @@ pp_status_t build_layouts(const pp_conv_desc_t& d, HostPlan& hp) {
             if (a.fl != b.fl) return a.fl < b.fl;
             return a.part < b.part;
         });
+        // first[ci] .. first[ci+1]: the group's kernels on channel ci
+        std::fill(first.begin(), first.end(), (size_t)0);
+        for (const Item& k : items) ++first[k.ci + 1];
+        for (int ci = 0; ci < C; ++ci) first[ci + 1] += first[ci];
         for (int s = 0; s < KS; ++s) {
             tl.wave_off[(size_t)g * KS + s] = (int32_t)(tl.stream.size() / EW);
-            size_t it = 0;
             for (int q = 0; q < Q; ++q) {
-                const int lo = q * CC + s * CS, hi = lo + CS;      // this wavefront's channels of chunk q
-                while (it < items.size() && items[it].ci < lo) ++it;
-                size_t j = it;
-                int prev_ci = -1;
-                for (; j < items.size() && items[j].ci < hi; ++j) {
-                    const Item& k = items[j];
-                    uint32_t header = (uint32_t)(k.fl * tl.np + k.slot);
-                    if (k.ci != prev_ci) header |= kFlagNewChannel;
-                    header |= (uint32_t)(k.ci - q * CC) << kChanShift;
-                    prev_ci = k.ci;
-                    if (!dense) {
-                        push_entry(header, &cn.wpacked[(size_t)k.src * 4]);
-                    } else {
-                        float w4[4];
-                        for (int j4 = 0; j4 < 4; ++j4) {
-                            const int tap = kDenseTap[k.part][j4];
-                            w4[j4] = tap < 0 ? 0.0f : cn.wpacked[(size_t)k.src * 9 + tap];
+                for (int cl = s * CS; cl < (s + 1) * CS; ++cl) {    // this wavefront's channels of chunk q, by place in the chunk
+                    const int ci = cmap[q * CC + cl];
+                    if (ci < 0) continue;
+                    for (size_t j = first[ci]; j < first[ci + 1]; ++j) {
+                        const Item& k = items[j];
+                        uint32_t header = (uint32_t)(k.fl * tl.np + k.slot);
+                        if (j == first[ci]) header |= kFlagNewChannel;
+                        header |= (uint32_t)cl << kChanShift;
+                        if (!dense) {
+                            push_entry(header, &cn.wpacked[(size_t)k.src * 4]);
+                        } else {
+                            float w4[4];
+                            for (int j4 = 0; j4 < 4; ++j4) {
+                                const int tap = kDenseTap[k.part][j4];
+                                w4[j4] = tap < 0 ? 0.0f : cn.wpacked[(size_t)k.src * 9 + tap];
+                            }
+                            push_entry(header, w4);
                         }
-                        push_entry(header, w4);
                     }
                 }
                 push_entry(kFlagEnd, nullptr);
@@ -383,10 +516,11 @@ pp_status_t unpack_stream(const HostPlan& hp, int32_t* kidx, uint8_t* kpat, floa
                         ++e;
                         break;
                     }
-                    if (ent[0] & kFlagNewChannel) ci = q * tl.cc + (int)(ent[0] >> kChanShift);
+                    if (ent[0] & kFlagNewChannel)
+                        ci = tl.chan_map[((size_t)(g / tl.wf) * tl.chunks + q) * tl.cc + (int)(ent[0] >> kChanShift)];
                     int code = (int)(ent[0] & kCodeMask);
-                    int pos = g * tl.f + code / tl.np;
-                    if (pos >= hp.c_out || ci < 0) return PP_ERR_UNSUPPORTED;
+                    int pos = tl.slot_pos[(size_t)g * tl.f + code / tl.np];
+                    if (pos < 0 || ci < 0) return PP_ERR_UNSUPPORTED;
                     Rec r;
                     r.pat = pid_of[code % tl.np];
                     r.ci = ci;

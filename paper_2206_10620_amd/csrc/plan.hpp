@@ -34,11 +34,15 @@ struct Canonical {          // tuning-independent result of the reorder
 struct TiledLayout {        // geometry of the tiled kernel for one plan
     int np = 0;             // pattern slots compiled in (8 or 16)
     int f = 0, r = 0, lw = 0, wf = 0, ks = 0, cc = 0;
+    int mode = 0;           // input staging: 0 through registers, 1 direct loads in 16-byte slots, 2 in 4-byte slots
+    int nbuf = 1;           // tile buffers in LDS: 1, or the ring size of direct staging (2..8)
     int groups = 0;         // G = ceil(c_out / f)
     int chunks = 0;         // Q = ceil(c_in / cc)
     int entry_words = 8;    // 32-bit words per entry: header, 3 reserved, 4 fp32 weights
     std::vector<uint32_t> stream;      // entries
     std::vector<int32_t> wave_off;     // [G*ks] first entry of each (group, split) wavefront stream
+    std::vector<int32_t> slot_pos;     // [G*f] position in the reordered filter list of the filter in each slot, -1 for padding
+    std::vector<int32_t> chan_map;     // [filter blocks][chunks*cc] input channel staged at each place of each chunk, -1 for padding
     std::vector<int32_t> perm_pad;     // [G*f] original filter index by slot, -1 for padding
     std::vector<float> bias_pad;       // [G*f]
 };
@@ -79,19 +83,39 @@ struct TileGeom {
     int tw;        // tile width in pixels = lw * kPW
     int mrows;     // most micro-rows one wavefront's 64 micro-tiles can touch
     int rows;      // LDS tile rows = mrows * r + 2
-    int hoff;      // element offset, inside a tile row, of micro-column 0's (left, right) halo pair
-    int rs;        // LDS row stride in elements
-    int chs;       // LDS channel stride in elements
+    int rs;        // interior row stride in elements (= tw: rows are contiguous)
+    int hoff;      // element offset, inside a channel, of the halo area
+    int hrs;       // halo row stride in elements: lw pairs of two 32-bit words
+    int chs;       // LDS channel stride in elements (multiple of 16 bytes)
 };
 constexpr TileGeom tile_geom(int lw, int r, int elem_bytes) {
     int tw = lw * kPW;
     int mrows = (64 % lw == 0) ? 64 / lw : (64 + lw - 1) / lw + 1;
     int rows = mrows * r + 2;
     int vec = 16 / elem_bytes;                       // elements per 128-bit access
-    int hoff = tw + 2;                               // interior, one dummy pair, lw pairs, one dummy pair
-    int rs = tw + 2 * (lw + 2);
-    rs = (rs + vec - 1) / vec * vec;
-    return TileGeom{tw, mrows, rows, hoff, rs, rows * rs};
+    int hoff = (rows * tw + vec - 1) / vec * vec;
+    int hrs = lw * 2 * (4 / elem_bytes);
+    int chs = (hoff + rows * hrs + vec - 1) / vec * vec;
+    return TileGeom{tw, mrows, rows, tw, hoff, hrs, chs};
+}
+
+// Dynamic LDS of a tiled-kernel launch: nbuf tile buffers of cc channels (one for register
+// staging, a ring of 2..8 for direct staging) followed, for direct staging, by the slot tables;
+// the split-channel exchange area reuses the start of it.
+constexpr int k1_lds_table_offset(int lw, int r, int cc, int elem_bytes, int nbuf) {
+    return nbuf * cc * tile_geom(lw, r, elem_bytes).chs * elem_bytes;
+}
+constexpr int64_t k1_lds_table_bytes(int lw, int r, int elem_bytes, int mode) {
+    if (!mode) return 0;
+    TileGeom tg = tile_geom(lw, r, elem_bytes);
+    int slot = mode == 1 ? 16 : 4;
+    int ni = (tg.rows * (tg.tw * elem_bytes / slot) + 63) / 64, nh = (tg.rows * lw * 2 + 63) / 64;
+    return (int64_t)(ni + nh) * 64 * 4;
+}
+constexpr int64_t k1_lds_layout_bytes(int lw, int r, int f, int wf, int ks, int cc, int elem_bytes, int mode, int nbuf) {
+    int64_t total = (int64_t)nbuf * cc * tile_geom(lw, r, elem_bytes).chs * elem_bytes + k1_lds_table_bytes(lw, r, elem_bytes, mode);
+    int64_t red = ks > 1 ? (int64_t)wf * f * r * 4 * 64 * 4 : 0;
+    return total > red ? total : red;
 }
 
 }  // namespace ppc

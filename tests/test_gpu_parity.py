@@ -69,7 +69,8 @@ TUNINGS = [dict(filters_per_wave=4, rows_per_lane=1, lanes_x=2), dict(filters_pe
            dict(filters_per_wave=8, rows_per_lane=1, lanes_x=14, waves_f=16, split_c=1, chunk_c=1),
            dict(filters_per_wave=4, rows_per_lane=4, lanes_x=16, waves_f=4, split_c=2, chunk_c=4),
            dict(filters_per_wave=4, rows_per_lane=4, lanes_x=7, waves_f=2, split_c=1, chunk_c=5),
-           dict(filters_per_wave=4, rows_per_lane=2, lanes_x=14, waves_f=4, split_c=2, chunk_c=8),
+           dict(filters_per_wave=4, rows_per_lane=2, lanes_x=14, waves_f=4, split_c=2, chunk_c=8, balance=1),
+           dict(filters_per_wave=4, rows_per_lane=2, lanes_x=14, waves_f=4, split_c=2, chunk_c=8, balance=2),
            dict(filters_per_wave=4, rows_per_lane=1, lanes_x=16, waves_f=8, split_c=1, chunk_c=8),
            dict(filters_per_wave=4, rows_per_lane=2, lanes_x=8, waves_f=2, split_c=4, chunk_c=8)]
 
@@ -84,6 +85,40 @@ def test_every_tile_geometry(tune, dtype):
         for k, v in tune.items():
             assert rep["chosen"][k] == v
     say(f"  E={rep['E']:.2e}")
+
+
+# How input tiles reach LDS: 1 = through registers, k >= 2 = direct loads into a ring of k buffers.
+# Shapes: rows on 16-byte boundaries (16-byte slots), on 4-byte boundaries only (4-byte slots), and
+# c_in / chunk_c combinations with fewer chunks than buffers, exactly as many, and many more; a
+# one-wavefront workgroup (more load instructions per channel than wavefronts) and a 16-wavefront one.
+STAGINGS = [(1, dict(filters_per_wave=4, rows_per_lane=2, lanes_x=8, waves_f=4, split_c=2, chunk_c=4)),
+            (2, dict(filters_per_wave=4, rows_per_lane=2, lanes_x=8, waves_f=4, split_c=2, chunk_c=4)),
+            (1, dict(filters_per_wave=4, rows_per_lane=2, lanes_x=8, waves_f=4, split_c=2, chunk_c=4, balance=1)),
+            (2, dict(filters_per_wave=4, rows_per_lane=2, lanes_x=8, waves_f=4, split_c=2, chunk_c=4, balance=1)),
+            (3, dict(filters_per_wave=4, rows_per_lane=1, lanes_x=14, waves_f=1, split_c=1, chunk_c=3)),
+            (4, dict(filters_per_wave=8, rows_per_lane=2, lanes_x=16, waves_f=8, split_c=2, chunk_c=2)),
+            (8, dict(filters_per_wave=4, rows_per_lane=4, lanes_x=4, waves_f=2, split_c=1, chunk_c=1)),
+            (3, dict(filters_per_wave=16, rows_per_lane=1, lanes_x=7, waves_f=2, split_c=1, chunk_c=5)),
+            (5, dict(filters_per_wave=4, rows_per_lane=2, lanes_x=2, waves_f=16, split_c=1, chunk_c=7))]
+
+
+@pytest.mark.parametrize("staging,tune", STAGINGS)
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_staging_paths(staging, tune, dtype):
+    say(f"staging {staging} {tune} {dtype}")
+    for (n, c_in, c_out, h, w) in [(2, 23, 40, 19, 48), (3, 7, 16, 9, 8), (2, 36, 12, 33, 50), (1, 5, 9, 6, 122)]:
+        lay = synth.random_pruned_layer("stg", n, c_in, c_out, h, w, dtype, synth.PSET16, 0.5, 0.3, seed=11)
+        rep, _ = check_layer(lay, tuning=T(variant=2, staging=staging, **tune), label=f"stg{staging}{tune}")
+        assert rep["chosen"]["staging"] == staging
+        assert rep["chosen"]["chunk_c"] == tune["chunk_c"]
+    say(f"  E={rep['E']:.2e}")
+
+
+def test_staging_default_is_direct_when_rows_are_aligned():
+    for dtype, w, want_direct in [("f32", 45, True), ("f16", 45, False), ("f16", 46, True), ("f32", 48, True)]:
+        lay = synth.random_pruned_layer("stgdef", 2, 40, 24, 17, w, dtype, synth.PSET8, 0.5, 0.3, seed=5)
+        rep, _ = check_layer(lay, label=f"stgdef-{dtype}-{w}")
+        assert (rep["chosen"]["staging"] >= 2) == want_direct, rep["chosen"]
 
 
 def test_degenerate_sparsity():
@@ -136,9 +171,15 @@ def test_filter_reordering_invariance_and_determinism():
     lay2.pattern_id, lay2.conn_mask, lay2.weights, lay2.bias = lay.pattern_id[rows], lay.conn_mask[rows], lay.weights[rows], lay.bias[perm]
     y3, _ = run_layer(lay2, x)
     assert np.array_equal(y3, y1[:, perm])                     # same per-filter summation order: bit-identical
-    # waves per workgroup and filters per wave do not change any output's summation order either
+    # With channels in natural order, waves per workgroup and filters per wave do not change any
+    # output's summation order either; the load-balanced channel order depends on which filters share
+    # a workgroup, so there results agree to rounding only.
+    y5, _ = run_layer(lay, x, tuning=T(variant=2, filters_per_wave=4, waves_f=6, balance=1))
+    y6, _ = run_layer(lay, x, tuning=T(variant=2, filters_per_wave=4, waves_f=3, balance=1))
+    assert np.array_equal(y5, y6)
     y4, _ = run_layer(lay, x, tuning=T(variant=2, filters_per_wave=4, waves_f=3))
-    assert np.array_equal(y4, y1)
+    assert not np.array_equal(y4, y6)                          # (the orders do differ)
+    assert np.max(np.abs(y4 - y6)) <= 1e-5 * max(1.0, float(np.max(np.abs(y6))))
 
 
 def test_maxpool():

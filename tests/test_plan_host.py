@@ -116,6 +116,34 @@ def test_error_paths():
     assert pp.pp_status_string(pp.PP_ERR_PATTERN) == "bad pattern mask or id"
 
 
+def test_staging_choice_and_limits():
+    """Input staging: direct loads need rows that start on 4-byte boundaries; the ring must fit in LDS."""
+    def chosen(lay, **tune):
+        plan = pp.plan_from_layer(lay, host_only=True, tuning=pp.Tuning(variant=2, **tune) if tune else None)
+        ch = plan.query()["chosen"]
+        plan.close()
+        return ch
+
+    def lay(dtype, w, c_in=40):
+        return synth.random_pruned_layer("stg", 2, c_in, 24, 17, w, dtype, synth.PSET8, 0.5, 0.3, seed=5)
+
+    assert chosen(lay("f32", 45))["staging"] >= 2          # any fp32 width
+    assert chosen(lay("f16", 46))["staging"] >= 2          # even fp16 width
+    assert chosen(lay("f16", 45))["staging"] == 1          # odd fp16 width: through registers
+    assert chosen(lay("f32", 48), staging=1)["staging"] == 1
+    ch = chosen(lay("f32", 48), staging=5, chunk_c=4)
+    assert ch["staging"] == 5 and ch["chunk_c"] == 4
+    # an automatic ring never has more buffers than there are chunks to put in them
+    ch = chosen(lay("f32", 48, c_in=6), chunk_c=4)
+    assert ch["staging"] == 2
+    with pytest.raises(pp.PPError):
+        chosen(lay("f16", 45), staging=2)                   # direct loads impossible
+    with pytest.raises(pp.PPError):
+        chosen(lay("f32", 48), staging=9)
+    with pytest.raises(pp.PPError):
+        chosen(lay("f32", 48), staging=8, chunk_c=32, lanes_x=16, rows_per_lane=4)   # ring larger than LDS
+
+
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "pp_conv.h")).read()
     names = set(re.findall(r"\b(pp_[a-z0-9_]+)\s*\(", header))
