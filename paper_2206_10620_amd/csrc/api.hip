@@ -264,6 +264,7 @@ pp_status_t pp_conv_run(const pp_conv_plan_t* plan, const void* x_dev, void* y_d
     a.y = y_dev;
     a.stream = plan->d_stream;
     a.wave_off = plan->d_wave_off;
+    a.idle_off = tl.idle_off;
     a.bias_pad = plan->d_bias_pad;
     a.perm_pad = plan->d_perm_pad;
     a.chan_map = plan->d_chan_map;

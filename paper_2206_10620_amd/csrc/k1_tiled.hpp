@@ -40,6 +40,7 @@ struct K1Args {
     void* y;
     const uint32_t* stream;     // weight-stream entries
     const int32_t* wave_off;    // [G*KS] first entry per (group, split)
+    int32_t idle_off;           // first entry of a run of end-of-chunk entries, for wavefronts without a filter group
     const float* bias_pad;      // [G*F]
     const int32_t* chan_map;    // [filter blocks][chunks*cc] input channel at each place of each chunk
     const int32_t* perm_pad;    // [G*F] original filter index or -1
@@ -86,6 +87,12 @@ template <typename T, int N> __device__ __forceinline__ T vec_elem(const typenam
 // two neighbour elements themselves, for fp16 the words (x[-2], x[-1]) and (x[4], x[5]).
 template <typename T, int R> struct Window;
 
+// The four weights of a kernel as they sit in scalar registers: fp32 values, or for fp16 storage
+// two words of two binary16 values each (w0 | w1 << 16, w2 | w3 << 16).
+template <typename T> struct Weights;
+template <> struct Weights<float> { float w[4]; };
+template <> struct Weights<_Float16> { uint32_t pair[2]; };
+
 template <int R> struct Window<float, R> {
     f32x4 mid[R + 2];    // columns 0..3
     f32x2 halo[R + 2];   // (column -1, column 4)
@@ -103,7 +110,8 @@ template <int R> struct Window<float, R> {
             halo[rr] = *reinterpret_cast<const f32x2*>(ph + rr * hrs);
         }
     }
-    template <int ROW, int COL> __device__ __forceinline__ void fma(float& acc, float w) const {
+    template <int ROW, int COL, int J> __device__ __forceinline__ void fma(float& acc, const Weights<float>& wt) const {
+        const float w = wt.w[J];
         if constexpr (COL < 0) acc = __builtin_fmaf(w, halo[ROW][0], acc);
         else if constexpr (COL > 3) acc = __builtin_fmaf(w, halo[ROW][1], acc);
         else acc = __builtin_fmaf(w, mid[ROW][COL], acc);
@@ -111,9 +119,10 @@ template <int R> struct Window<float, R> {
 };
 
 // fp16 storage: the window stays packed, two halves per register, and every multiply-accumulate
-// is one v_fma_mix_f32 (fp16 input selected from the low or high half, fp32 weight from a scalar
-// register, fp32 accumulator).  Written as inline assembly because the compiler otherwise
-// unpacks halves that are used several times with extra conversion instructions.
+// is one v_fma_mix_f32: fp16 weight from the low or high half of a scalar register, fp16 input
+// from the low or high half of a vector register, both widened exactly, fp32 accumulator.  Written
+// as inline assembly because the compiler otherwise unpacks halves that are used several times
+// with extra conversion instructions.
 template <int R> struct Window<_Float16, R> {
     uint32_t mid[R + 2][2];    // columns (0,1), (2,3)
     uint32_t halo[R + 2][2];   // (column -2, column -1), (column 4, column 5)
@@ -133,32 +142,38 @@ template <int R> struct Window<_Float16, R> {
             halo[rr][1] = h[1];
         }
     }
-    template <int ROW, int COL> __device__ __forceinline__ void fma(float& acc, float w) const {
+    template <int ROW, int COL, int J> __device__ __forceinline__ void fma(float& acc, const Weights<_Float16>& wt) const {
         constexpr bool hi = (COL < 0) ? true : (COL > 3) ? false : (COL & 1) != 0;
         const uint32_t src = (COL < 0) ? halo[ROW][0] : (COL > 3) ? halo[ROW][1] : mid[ROW][(COL < 0 ? 0 : COL) >> 1];
-        if constexpr (hi)
-            asm("v_fma_mix_f32 %0, %1, %2, %0 op_sel:[0,1,0] op_sel_hi:[0,1,0]" : "+v"(acc) : "s"(w), "v"(src));
+        const uint32_t w = wt.pair[J >> 1];
+        // op_sel_hi = 1: the operand is fp16; op_sel: which half of it
+        if constexpr (hi && (J & 1))
+            asm("v_fma_mix_f32 %0, %1, %2, %0 op_sel:[1,1,0] op_sel_hi:[1,1,0]" : "+v"(acc) : "s"(w), "v"(src));
+        else if constexpr (hi)
+            asm("v_fma_mix_f32 %0, %1, %2, %0 op_sel:[0,1,0] op_sel_hi:[1,1,0]" : "+v"(acc) : "s"(w), "v"(src));
+        else if constexpr (J & 1)
+            asm("v_fma_mix_f32 %0, %1, %2, %0 op_sel:[1,0,0] op_sel_hi:[1,1,0]" : "+v"(acc) : "s"(w), "v"(src));
         else
-            asm("v_fma_mix_f32 %0, %1, %2, %0 op_sel_hi:[0,1,0]" : "+v"(acc) : "s"(w), "v"(src));
+            asm("v_fma_mix_f32 %0, %1, %2, %0 op_sel_hi:[1,1,0]" : "+v"(acc) : "s"(w), "v"(src));
     }
 };
 
 // ---------------------------------------------------------------------------------------------
 // Multiply-accumulate block of one kept kernel: filter slot FS, pattern slot PS (4 taps).
-template <typename T, int R, int F, int FS, int RR, int TAP>
-__device__ __forceinline__ void mac_row(float (&acc)[F][R][4], const Window<T, R>& win, float wj) {
+template <typename T, int R, int F, int FS, int RR, int TAP, int J>
+__device__ __forceinline__ void mac_row(float (&acc)[F][R][4], const Window<T, R>& win, const Weights<T>& wt) {
     constexpr int dr = TAP / 3, dc = TAP % 3 - 1;
-    win.template fma<RR + dr, 0 + dc>(acc[FS][RR][0], wj);
-    win.template fma<RR + dr, 1 + dc>(acc[FS][RR][1], wj);
-    win.template fma<RR + dr, 2 + dc>(acc[FS][RR][2], wj);
-    win.template fma<RR + dr, 3 + dc>(acc[FS][RR][3], wj);
+    win.template fma<RR + dr, 0 + dc, J>(acc[FS][RR][0], wt);
+    win.template fma<RR + dr, 1 + dc, J>(acc[FS][RR][1], wt);
+    win.template fma<RR + dr, 2 + dc, J>(acc[FS][RR][2], wt);
+    win.template fma<RR + dr, 3 + dc, J>(acc[FS][RR][3], wt);
 }
 
-template <typename T, int R, int F, int FS, int TAP, int RR = 0>
-__device__ __forceinline__ void mac_tap(float (&acc)[F][R][4], const Window<T, R>& win, float wj) {
+template <typename T, int R, int F, int FS, int TAP, int J, int RR = 0>
+__device__ __forceinline__ void mac_tap(float (&acc)[F][R][4], const Window<T, R>& win, const Weights<T>& wt) {
     if constexpr (RR < R) {
-        mac_row<T, R, F, FS, RR, TAP>(acc, win, wj);
-        mac_tap<T, R, F, FS, TAP, RR + 1>(acc, win, wj);
+        mac_row<T, R, F, FS, RR, TAP, J>(acc, win, wt);
+        mac_tap<T, R, F, FS, TAP, J, RR + 1>(acc, win, wt);
     }
 }
 
@@ -172,29 +187,54 @@ constexpr int nth_tap(uint32_t mask, int j) {
 }
 
 template <typename T, int R, int F, int FS, int PS>
-__device__ __forceinline__ void mac_kernel(float (&acc)[F][R][4], const Window<T, R>& win, const float (&wt)[4]) {
+__device__ __forceinline__ void mac_kernel(float (&acc)[F][R][4], const Window<T, R>& win, const Weights<T>& wt) {
     constexpr uint32_t mask = kBuiltinMasks[PS];
-    mac_tap<T, R, F, FS, nth_tap(mask, 0)>(acc, win, wt[0]);
-    mac_tap<T, R, F, FS, nth_tap(mask, 1)>(acc, win, wt[1]);
-    mac_tap<T, R, F, FS, nth_tap(mask, 2)>(acc, win, wt[2]);
-    mac_tap<T, R, F, FS, nth_tap(mask, 3)>(acc, win, wt[3]);
+    mac_tap<T, R, F, FS, nth_tap(mask, 0), 0>(acc, win, wt);
+    mac_tap<T, R, F, FS, nth_tap(mask, 1), 1>(acc, win, wt);
+    mac_tap<T, R, F, FS, nth_tap(mask, 2), 2>(acc, win, wt);
+    mac_tap<T, R, F, FS, nth_tap(mask, 3), 3>(acc, win, wt);
 }
 
 // Wave-uniform dispatch on code = filter slot * NP + pattern slot: a balanced tree of scalar
-// compares down to the specialised block.
-template <typename T, int R, int F, int NP, int LO, int HI>
-__device__ __forceinline__ void dispatch(int code, float (&acc)[F][R][4], const Window<T, R>& win, const float (&wt)[4]) {
+// compares down to the specialised block.  COPY tells the two copies of the tree apart (the
+// stream walker is unrolled twice).
+template <typename T, int R, int F, int NP, int COPY, int LO, int HI>
+__device__ __forceinline__ void dispatch(int code, float (&acc)[F][R][4], const Window<T, R>& win, const Weights<T>& wt) {
     if constexpr (HI - LO == 1) {
         mac_kernel<T, R, F, LO / NP, LO % NP>(acc, win, wt);
         // A distinct marker per block: without it the optimiser merges the tails of blocks that
         // differ only in their accumulator registers and pays for it with register copies.
-        asm volatile("; kernel block %0" ::"n"(LO));
+        asm volatile("; kernel block %0 copy %1" ::"n"(LO), "n"(COPY));
     } else {
         constexpr int MID = (LO + HI) / 2;
-        if (code < MID) dispatch<T, R, F, NP, LO, MID>(code, acc, win, wt);
-        else dispatch<T, R, F, NP, MID, HI>(code, acc, win, wt);
+        if (code < MID) dispatch<T, R, F, NP, COPY, LO, MID>(code, acc, win, wt);
+        else dispatch<T, R, F, NP, COPY, MID, HI>(code, acc, win, wt);
     }
 }
+
+// One stream entry in scalar registers, fetched with a single scalar load.
+//   fp32: 8 words {header, -, -, -, w0, w1, w2, w3};   fp16: 4 words {header, w0|w1<<16, w2|w3<<16, -}
+template <typename T> struct Entry;
+template <> struct Entry<float> {
+    static constexpr int kWords = 8;
+    typedef uint32_t vec_t __attribute__((ext_vector_type(8)));
+    vec_t v;
+    __device__ __forceinline__ uint32_t head() const { return v[0]; }
+    __device__ __forceinline__ Weights<float> weights() const {
+        // (element values are copied out first: a bit cast applied to a vector element expression
+        // directly reads the wrong element with this compiler)
+        const uint32_t u0 = v[4], u1 = v[5], u2 = v[6], u3 = v[7];
+        return Weights<float>{{__builtin_bit_cast(float, u0), __builtin_bit_cast(float, u1), __builtin_bit_cast(float, u2),
+                               __builtin_bit_cast(float, u3)}};
+    }
+};
+template <> struct Entry<_Float16> {
+    static constexpr int kWords = 4;
+    typedef uint32_t vec_t __attribute__((ext_vector_type(4)));
+    vec_t v;
+    __device__ __forceinline__ uint32_t head() const { return v[0]; }
+    __device__ __forceinline__ Weights<_Float16> weights() const { return Weights<_Float16>{{v[1], v[2]}}; }
+};
 
 // ---------------------------------------------------------------------------------------------
 // LDS tile of one channel: [rows][TW] interior elements, then [rows][LW] halo pairs of two 32-bit
@@ -450,14 +490,14 @@ __device__ __forceinline__ void wait_vmcnt_at_most(int n) {
 
 // Variants with at most 32 accumulators per lane are asked to fit 64 vector registers, i.e. 8
 // resident wavefronts per SIMD: two 16-wavefront workgroups per CU, which is what hides the scalar
-// dispatch and LDS latency of one behind the multiply-accumulates of the other.
+// dispatch and LDS latency of one behind the multiply-accumulates of the other.  (Staging through
+// registers needs the registers itself and is left at 4.)
 template <typename T, int NP, int R, int F, int LW, bool DIRECT>
-__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(F * R * 4 <= 32 ? 8 : 4)))
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(DIRECT && F * R * 4 <= 32 ? 8 : 4)))
 void k1_tiled(const K1Args a) {
     constexpr TileGeom tg = tile_geom(LW, R, (int)sizeof(T));
     constexpr int TW = tg.tw, RS = tg.rs, CHS = tg.chs, ROWS = tg.rows, HOFF = tg.hoff, HRS = tg.hrs;
     constexpr int HP = HRS / LW;                    // elements per halo pair
-    constexpr int EW = 8;                           // 32-bit words per stream entry
     extern __shared__ __align__(16) unsigned char smem_raw[];
     __shared__ int rowtab[ROWS];
     T* tile = reinterpret_cast<T*>(smem_raw);
@@ -520,13 +560,11 @@ void k1_tiled(const K1Args a) {
     const T* __restrict__ xin = static_cast<const T*>(a.x);
     const int32_t* __restrict__ cmap = a.chan_map + (int64_t)fb * a.chunks * a.cc;   // this filter block's channel order
 
-    // this wavefront's entry stream (constant address space: wave-uniform loads from it are scalar loads)
-    typedef const __attribute__((address_space(4))) uint32_t* stream_ptr_t;
+    // This wavefront's entry stream (constant address space: wave-uniform loads from it are scalar
+    // loads).  Wavefronts beyond the last filter group walk a stream of end-of-chunk entries only.
+    typedef const __attribute__((address_space(4))) typename Entry<T>::vec_t* stream_ptr_t;
     typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr_t;
-    stream_ptr_t sp = (stream_ptr_t)(a.stream) + (int64_t)(has_group ? ((const_i32_ptr_t)a.wave_off)[g * a.ks + ksi] : 0) * EW;
-    // the next entry to execute, fetched one entry ahead so that the scalar-load latency hides
-    // behind the previous kernel's multiply-accumulates
-    uint32_t n_head = sp[0], n_w0 = sp[4], n_w1 = sp[5], n_w2 = sp[6], n_w3 = sp[7];
+    stream_ptr_t sp = (stream_ptr_t)(a.stream) + (has_group ? ((const_i32_ptr_t)a.wave_off)[g * a.ks + ksi] : a.idle_off);
 
     // Direct staging: ring of a.nbuf buffers of a.cc channels each; the loads of the next
     // a.nbuf - 1 chunks are in flight while a chunk is consumed.
@@ -562,11 +600,10 @@ void k1_tiled(const K1Args a) {
         }
     }
 
+    // Make chunk q readable: returns the element offset of the buffer that holds it.
     int ring = 0;                 // buffer that holds chunk q
-    for (int q = 0; q < a.chunks; ++q) {
-        const int c0 = q * a.cc;
-        const int ccn = (a.c_in - c0 < a.cc) ? a.c_in - c0 : a.cc;
-        int boff = 0;             // element offset of the buffer this chunk is read from
+    auto begin_chunk = [&](int q) -> int {
+        int boff = 0;
         if constexpr (DIRECT) {
             // chunk q has landed once no more loads are outstanding than were issued for the chunks
             // after it (q+1 .. q+ahead-1, as far as they exist; all but the last chunk are full)
@@ -587,39 +624,52 @@ void k1_tiled(const K1Args a) {
             }
             ring = ring + 1 == a.nbuf ? 0 : ring + 1;
         } else {
+            const int c0 = q * a.cc;
+            const int ccn = (a.c_in - c0 < a.cc) ? a.c_in - c0 : a.cc;
             __syncthreads();      // previous chunk fully consumed (and rowtab written, first time round)
             PPC_STAGE_DISPATCH(a.vec, stage(xin, cmap + c0, tile, rowtab, ccn, trn, trn_magic, x0, a.w, hw, threadIdx.x, blockDim.x))
             __syncthreads();
         }
-        if (!has_group) continue;
+        return boff;
+    };
 
-        Window<T, R> win;
-        win.clear();
-        for (;;) {
-            const uint32_t head = n_head;
-            const float wt[4] = {__builtin_bit_cast(float, n_w0), __builtin_bit_cast(float, n_w1),
-                                 __builtin_bit_cast(float, n_w2), __builtin_bit_cast(float, n_w3)};
-            const bool at_end = (head & kFlagEnd) != 0;
-            if (!at_end && (head & kFlagNewChannel)) {
-                const int cl = (int)(head >> kChanShift) * CHS + boff;
-                win.load(lane_mid + cl, lane_halo + cl, RS, HRS);
-                // Wait for the window here, before the next entry's scalar load is issued: LDS reads
-                // and scalar loads share one counter, so a wait placed later (inside the kernel
-                // blocks) would also wait for that prefetch and expose its latency on every kernel.
-                // (0xC07F = lgkmcnt(0), vmcnt and expcnt unconstrained; the builtin, unlike inline
-                // assembly, is visible to the compiler's own wait-count bookkeeping)
-                __builtin_amdgcn_s_waitcnt(0xC07F);
-            }
-            sp += EW;                 // the stream is padded by one entry past the last wavefront
-            n_head = sp[0];
-            n_w0 = sp[4];
-            n_w1 = sp[5];
-            n_w2 = sp[6];
-            n_w3 = sp[7];
-            if (at_end) break;
-            dispatch<T, R, F, NP, 0, F * NP>((int)(head & kCodeMask), acc, win, wt);
-        }
+    // The stream walker.  Entries are fetched one ahead, so that the scalar-load latency hides behind
+    // the previous kernel's multiply-accumulates, and alternately into two register sets, so that
+    // no entry is ever copied: the loop body exists twice, once per set.  An end-of-chunk entry
+    // switches to the next chunk's tile; the one after the last chunk ends the loop.
+    int q = 0;
+    int boff = begin_chunk(0);
+    Window<T, R> win;
+    win.clear();
+    Entry<T> ea, eb;
+    ea.v = sp[0];
+#define PPC_STEP(CUR, NXT, COPY)                                                                        \
+    {                                                                                                   \
+        const uint32_t head = CUR.head();                                                               \
+        if (head & kFlagNewChannel) {                                                                   \
+            const int cl = (int)(head >> kChanShift) * CHS + boff;                                      \
+            win.load(lane_mid + cl, lane_halo + cl, RS, HRS);                                           \
+            /* Wait for the window here, before the next entry's scalar load is issued: LDS reads and   \
+               scalar loads share one counter, so a wait placed later (inside the kernel blocks) would  \
+               also wait for that prefetch and expose its latency on every kernel.  (0xC07F =           \
+               lgkmcnt(0), vmcnt and expcnt unconstrained; the builtin, unlike inline assembly, is      \
+               visible to the compiler's own wait-count bookkeeping) */                                 \
+            __builtin_amdgcn_s_waitcnt(0xC07F);                                                         \
+        }                                                                                               \
+        ++sp;                     /* the stream is padded by one entry past the last wavefront */       \
+        NXT.v = sp[0];                                                                                  \
+        if (head & kFlagEnd) {                                                                          \
+            if (++q == a.chunks) break;                                                                 \
+            boff = begin_chunk(q);                                                                      \
+        } else {                                                                                        \
+            dispatch<T, R, F, NP, COPY, 0, F * NP>((int)(head & kCodeMask), acc, win, CUR.weights());   \
+        }                                                                                               \
     }
+    for (;;) {
+        PPC_STEP(ea, eb, 0)
+        PPC_STEP(eb, ea, 1)
+    }
+#undef PPC_STEP
 
     // ---- sum the channel splits through LDS, in a fixed order (deterministic) ----
     if (a.ks > 1) {

@@ -225,7 +225,7 @@ pp_status_t build_layouts(const pp_conv_desc_t& d, HostPlan& hp) {
     TiledLayout& tl = hp.tl;
     const int eb = hp.dtype == PP_F16 ? 2 : 4;
     tl.np = max_slot < 8 ? 8 : 16;
-    tl.entry_words = 8;
+    tl.entry_words = hp.dtype == PP_F16 ? 4 : 8;   // header + two words of binary16 pairs, or header + 3 spare + 4 fp32
 
     // ---- parameters ("tuning-decided parameters" of the layer-wise representation) ----
     tl.lw = t.lanes_x ? t.lanes_x : pick_lw(hp.w);
@@ -433,10 +433,14 @@ pp_status_t build_layouts(const pp_conv_desc_t& d, HostPlan& hp) {
         tl.stream.resize(at + EW, 0u);
         tl.stream[at] = header;
         if (!w4) return;
-        float wv[4] = {w4[0], w4[1], w4[2], w4[3]};
-        if (hp.dtype == PP_F16)      // binary16 storage: the stream carries the rounded values, widened
-            for (float& v : wv) v = f16_to_f32(f32_to_f16_rne(v));
-        std::memcpy(&tl.stream[at + 4], wv, 16);
+        if (hp.dtype == PP_F16) {    // binary16 storage: the weights are rounded here, once
+            uint16_t hb[4];
+            for (int j = 0; j < 4; ++j) hb[j] = f32_to_f16_rne(w4[j]);
+            tl.stream[at + 1] = (uint32_t)hb[0] | ((uint32_t)hb[1] << 16);
+            tl.stream[at + 2] = (uint32_t)hb[2] | ((uint32_t)hb[3] << 16);
+        } else {
+            std::memcpy(&tl.stream[at + 4], w4, 16);
+        }
     };
     for (int g = 0; g < G; ++g) {
         const int32_t* cmap = &tl.chan_map[(size_t)(g / WF) * Q * CC];
@@ -488,6 +492,9 @@ pp_status_t build_layouts(const pp_conv_desc_t& d, HostPlan& hp) {
             }
         }
     }
+    // what wavefronts without a filter group walk: one end-of-chunk entry per chunk
+    tl.idle_off = (int32_t)(tl.stream.size() / EW);
+    for (int q = 0; q < Q; ++q) push_entry(kFlagEnd, nullptr);
     push_entry(kFlagEnd, nullptr);     // the walker prefetches one entry ahead
     if (tl.stream.size() / EW >= ((size_t)1 << 31)) return PP_ERR_SHAPE;
     return PP_OK;
@@ -524,7 +531,11 @@ pp_status_t unpack_stream(const HostPlan& hp, int32_t* kidx, uint8_t* kpat, floa
                     Rec r;
                     r.pat = pid_of[code % tl.np];
                     r.ci = ci;
-                    std::memcpy(r.w, &ent[4], 16);
+                    if (hp.dtype == PP_F16) {
+                        for (int j = 0; j < 4; ++j) r.w[j] = f16_to_f32((uint16_t)(ent[1 + j / 2] >> (16 * (j & 1))));
+                    } else {
+                        std::memcpy(r.w, &ent[4], 16);
+                    }
                     per_filter[pos].push_back(r);
                 }
             }
