@@ -72,6 +72,9 @@ typedef struct {
     int32_t staging;        /* how input tiles reach LDS: 1 through registers, one buffer; 2..8 direct global-to-LDS
                                loads into a ring of that many buffers of chunk_c channels (needs rows that start on
                                4-byte boundaries: any fp32 width, even fp16 widths) */
+    int32_t split_wg;       /* SW: workgroups that share one output tile, each on its own contiguous range of channel
+                               chunks (1..64, at most the number of chunks); the last to finish adds the partial
+                               sums up in range order, so results do not depend on who that is */
     int32_t balance;        /* 1: filters and channels take wavefront slots and chunk places in reordered / natural
                                order; 2: they are dealt so that the wavefronts of a workgroup do about equal work
                                between two barriers (the default whenever a workgroup has several wavefronts) */
@@ -107,7 +110,10 @@ pp_status_t pp_conv_plan(const pp_conv_desc_t *desc, pp_conv_plan_t **out_plan);
  *   hip_stream : a hipStream_t (NULL = the default stream)
  * Returns after the launch without synchronising; launch-configuration errors are returned,
  * asynchronous faults are not.  Concurrent runs of one plan on different streams with different
- * y_dev are allowed.  n <= 0 is PP_ERR_SHAPE. */
+ * y_dev are allowed unless the plan splits channels across workgroups (chosen.split_wg > 1 in
+ * pp_conv_plan_query): such a plan owns one partial-sum workspace, sized for n_hint images, and its
+ * runs must not overlap; more than n_hint images are processed n_hint at a time.  n <= 0 is
+ * PP_ERR_SHAPE. */
 pp_status_t pp_conv_run(const pp_conv_plan_t *plan, const void *x_dev, void *y_dev, int32_t n, void *hip_stream);
 
 /* Free the plan's host and device memory.  NULL is a no-op returning PP_OK.  The caller must

@@ -116,6 +116,8 @@ struct pp_conv_plan {
     int32_t* d_wave_off = nullptr;
     int32_t* d_perm_pad = nullptr;
     int32_t* d_chan_map = nullptr;
+    float* d_ws = nullptr;             // partial sums of a plan that splits channels across workgroups
+    int32_t* d_counters = nullptr;     // arrivals per output tile (zero between launches)
     float* d_bias_pad = nullptr;
     k1_launch_fn launch = nullptr;
     // generic kernel
@@ -142,7 +144,7 @@ bool upload(T** dst, const void* src, size_t bytes) {
 }
 
 void free_device(pp_conv_plan_t* p) {
-    void* bufs[] = {p->d_stream, p->d_wave_off, p->d_chan_map, p->d_perm_pad, p->d_bias_pad, p->d_filt_off, p->d_kidx,
+    void* bufs[] = {p->d_stream, p->d_wave_off, p->d_chan_map, p->d_ws, p->d_counters, p->d_perm_pad, p->d_bias_pad, p->d_filt_off, p->d_kidx,
                     p->d_kpat,   p->d_w,        p->d_tap,      p->d_perm,     p->d_bias};
     for (void* b : bufs)
         if (b) (void)hipFree(b);
@@ -210,6 +212,17 @@ pp_status_t pp_conv_plan(const pp_conv_desc_t* desc, pp_conv_plan_t** out_plan) 
         ok = ok && upload(&p->d_wave_off, tl.wave_off.data(), tl.wave_off.size() * 4);
         ok = ok && upload(&p->d_perm_pad, tl.perm_pad.data(), tl.perm_pad.size() * 4);
         ok = ok && upload(&p->d_chan_map, tl.chan_map.data(), tl.chan_map.size() * 4);
+        if (tl.sw > 1) {
+            // workspace and arrival counters for batches of up to n_hint images
+            const int nh = std::max(1, hp.n_hint), eb = hp.dtype == PP_F16 ? 2 : 4;
+            const TileGeom tg = tile_geom(tl.lw, tl.r, eb);
+            const int64_t mrows = ((int64_t)nh * (hp.h + 1) - 1 + tl.r - 1) / tl.r;
+            const int64_t tiles = ((hp.w + tg.tw - 1) / tg.tw) * ((mrows * tl.lw + 63) / 64) * ((tl.groups + tl.wf - 1) / tl.wf);
+            const int64_t ws_bytes = (int64_t)tl.sw * nh * hp.c_out * hp.h * hp.w * 4;
+            ok = ok && hipMalloc(reinterpret_cast<void**>(&p->d_ws), (size_t)ws_bytes) == hipSuccess;
+            ok = ok && hipMalloc(reinterpret_cast<void**>(&p->d_counters), (size_t)tiles * 4) == hipSuccess;
+            ok = ok && hipMemset(p->d_counters, 0, (size_t)tiles * 4) == hipSuccess;
+        }
         ok = ok && upload(&p->d_bias_pad, tl.bias_pad.data(), tl.bias_pad.size() * 4);
     } else {
         const Canonical& cn = hp.canon;
@@ -235,27 +248,10 @@ pp_status_t pp_conv_plan(const pp_conv_desc_t* desc, pp_conv_plan_t** out_plan) 
     return PP_OK;
 }
 
-pp_status_t pp_conv_run(const pp_conv_plan_t* plan, const void* x_dev, void* y_dev, int32_t n, void* hip_stream) {
-    if (!plan || !x_dev || !y_dev) return PP_ERR_NULL;
-    if (!plan->on_device) return PP_ERR_UNSUPPORTED;
+// One launch of the tiled kernel on n images.
+static pp_status_t launch_tiled(const pp_conv_plan_t* plan, const void* x_dev, void* y_dev, int32_t n, hipStream_t stream) {
     const HostPlan& hp = plan->hp;
-    if (n <= 0) return PP_ERR_SHAPE;
-    const int64_t hw = (int64_t)hp.h * hp.w;
-    if ((int64_t)n * hp.c_in * hw >= ((int64_t)1 << 31) || (int64_t)n * hp.c_out * hw >= ((int64_t)1 << 31) ||
-        (int64_t)n * (hp.h + 1) >= ((int64_t)1 << 30))
-        return PP_ERR_SHAPE;
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const int relu = (hp.flags & PP_FLAG_RELU) ? 1 : 0;
-    if (!hp.tiled) {
-        K0Args a{x_dev, y_dev, plan->d_filt_off, plan->d_kidx, plan->d_kpat, plan->d_w, plan->d_tap, plan->d_perm,
-                 plan->d_bias, n, hp.c_in, hp.c_out, hp.h, hp.w, hp.taps, relu};
-        const int64_t blocks = ((int64_t)n * hw + 255) / 256;
-        if (blocks >= ((int64_t)1 << 31)) return PP_ERR_SHAPE;
-        dim3 grid((unsigned)blocks, (unsigned)hp.c_out);
-        if (hp.dtype == PP_F16) hipLaunchKernelGGL(k0_generic<_Float16>, grid, dim3(256), 0, stream, a);
-        else hipLaunchKernelGGL(k0_generic<float>, grid, dim3(256), 0, stream, a);
-        return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_DEVICE;
-    }
     const TiledLayout& tl = hp.tl;
     const int eb = hp.dtype == PP_F16 ? 2 : 4;
     const TileGeom tg = tile_geom(tl.lw, tl.r, eb);
@@ -288,8 +284,12 @@ pp_status_t pp_conv_run(const pp_conv_plan_t* plan, const void* x_dev, void* y_d
     a.table_offset = k1_lds_table_offset(tl.lw, tl.r, tl.cc, eb, tl.nbuf);
     a.relu = relu;
     const int nfb = (tl.groups + tl.wf - 1) / tl.wf;
-    const int64_t items = (int64_t)a.strips * a.wg_per_strip * nfb;
+    const int64_t items = (int64_t)a.strips * a.wg_per_strip * nfb * tl.sw;
     if (items >= ((int64_t)1 << 30)) return PP_ERR_SHAPE;
+    a.split_wg = tl.sw;
+    a.out_elems = (int32_t)((int64_t)n * hp.c_out * hp.h * hp.w);
+    a.ws = plan->d_ws;
+    a.counters = plan->d_counters;
     a.nfb = nfb;
     a.work_items = (int)items;
     a.blocks_per_xcd = (int)((items + 7) / 8);
@@ -297,6 +297,41 @@ pp_status_t pp_conv_run(const pp_conv_plan_t* plan, const void* x_dev, void* y_d
     const int lds = (int)k1_lds_layout_bytes(tl.lw, tl.r, tl.f, tl.wf, tl.ks, tl.cc, eb, tl.mode, tl.nbuf);
     plan->launch(a, (int)blocks, 64 * tl.wf * tl.ks, lds, stream);
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_DEVICE;
+}
+
+pp_status_t pp_conv_run(const pp_conv_plan_t* plan, const void* x_dev, void* y_dev, int32_t n, void* hip_stream) {
+    if (!plan || !x_dev || !y_dev) return PP_ERR_NULL;
+    if (!plan->on_device) return PP_ERR_UNSUPPORTED;
+    const HostPlan& hp = plan->hp;
+    if (n <= 0) return PP_ERR_SHAPE;
+    const int64_t hw = (int64_t)hp.h * hp.w;
+    if ((int64_t)n * hp.c_in * hw >= ((int64_t)1 << 31) || (int64_t)n * hp.c_out * hw >= ((int64_t)1 << 31) ||
+        (int64_t)n * (hp.h + 1) >= ((int64_t)1 << 30))
+        return PP_ERR_SHAPE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int relu = (hp.flags & PP_FLAG_RELU) ? 1 : 0;
+    if (!hp.tiled) {
+        K0Args a{x_dev, y_dev, plan->d_filt_off, plan->d_kidx, plan->d_kpat, plan->d_w, plan->d_tap, plan->d_perm,
+                 plan->d_bias, n, hp.c_in, hp.c_out, hp.h, hp.w, hp.taps, relu};
+        const int64_t blocks = ((int64_t)n * hw + 255) / 256;
+        if (blocks >= ((int64_t)1 << 31)) return PP_ERR_SHAPE;
+        dim3 grid((unsigned)blocks, (unsigned)hp.c_out);
+        if (hp.dtype == PP_F16) hipLaunchKernelGGL(k0_generic<_Float16>, grid, dim3(256), 0, stream, a);
+        else hipLaunchKernelGGL(k0_generic<float>, grid, dim3(256), 0, stream, a);
+        return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_DEVICE;
+    }
+    // A plan that splits channels across workgroups owns a workspace for n_hint images: larger
+    // batches go through it n_hint images at a time.
+    const TiledLayout& tl = hp.tl;
+    const int eb = hp.dtype == PP_F16 ? 2 : 4;
+    const int step = tl.sw > 1 ? std::max(1, hp.n_hint) : n;
+    for (int n0 = 0; n0 < n; n0 += step) {
+        const int nb = std::min(step, n - n0);
+        const pp_status_t st = launch_tiled(plan, static_cast<const char*>(x_dev) + (int64_t)n0 * hp.c_in * hw * eb,
+                                            static_cast<char*>(y_dev) + (int64_t)n0 * hp.c_out * hw * eb, nb, stream);
+        if (st != PP_OK) return st;
+    }
+    return PP_OK;
 }
 
 pp_status_t pp_conv_destroy(pp_conv_plan_t* plan) {

@@ -59,6 +59,11 @@ struct K1Args {
     int32_t nbuf;               // direct modes: tile buffers in the ring (2..8)
     int32_t table_offset;       // direct modes: byte offset of the slot tables in dynamic LDS (after the tile buffers; multiple of 16)
     int32_t relu;
+    // channel split across workgroups: slice s of split_wg takes chunks [s*chunks/split_wg, (s+1)*chunks/split_wg)
+    int32_t split_wg;
+    int32_t out_elems;          // n*c_out*h*w: elements of one partial-sum plane in ws
+    float* ws;                  // [split_wg][n][c_out][h][w] partial sums (split_wg > 1)
+    int32_t* counters;          // [work_items / split_wg] arrivals per output tile; zero between launches
 };
 
 typedef float f32x2 __attribute__((ext_vector_type(2)));
@@ -66,6 +71,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef const __attribute__((address_space(3))) unsigned char* lds_cbyte_ptr;   // a byte address in LDS
 
 template <typename T, int N> struct VecOf;
 template <> struct VecOf<float, 1> { typedef float type; };
@@ -103,11 +109,12 @@ template <int R> struct Window<float, R> {
             halo[rr] = f32x2(0);
         }
     }
-    __device__ __forceinline__ void load(const float* pm, const float* ph, int rs, int hrs) {
+    // pm, ph: LDS addresses of the lane's first interior element and first halo pair; strides in bytes
+    __device__ __forceinline__ void load(lds_cbyte_ptr pm, lds_cbyte_ptr ph, int rs_bytes, int hrs_bytes) {
 #pragma unroll
         for (int rr = 0; rr < R + 2; ++rr) {
-            mid[rr] = *reinterpret_cast<const f32x4*>(pm + rr * rs);
-            halo[rr] = *reinterpret_cast<const f32x2*>(ph + rr * hrs);
+            mid[rr] = *reinterpret_cast<const __attribute__((address_space(3))) f32x4*>(pm + rr * rs_bytes);
+            halo[rr] = *reinterpret_cast<const __attribute__((address_space(3))) f32x2*>(ph + rr * hrs_bytes);
         }
     }
     template <int ROW, int COL, int J> __device__ __forceinline__ void fma(float& acc, const Weights<float>& wt) const {
@@ -130,12 +137,12 @@ template <int R> struct Window<_Float16, R> {
 #pragma unroll
         for (int rr = 0; rr < R + 2; ++rr) mid[rr][0] = mid[rr][1] = halo[rr][0] = halo[rr][1] = 0u;
     }
-    __device__ __forceinline__ void load(const _Float16* pm, const _Float16* ph, int rs, int hrs) {
+    __device__ __forceinline__ void load(lds_cbyte_ptr pm, lds_cbyte_ptr ph, int rs_bytes, int hrs_bytes) {
         typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 #pragma unroll
         for (int rr = 0; rr < R + 2; ++rr) {
-            const u32x2 m = *reinterpret_cast<const u32x2*>(pm + rr * rs);
-            const u32x2 h = *reinterpret_cast<const u32x2*>(ph + rr * hrs);
+            const u32x2 m = *reinterpret_cast<const __attribute__((address_space(3))) u32x2*>(pm + rr * rs_bytes);
+            const u32x2 h = *reinterpret_cast<const __attribute__((address_space(3))) u32x2*>(ph + rr * hrs_bytes);
             mid[rr][0] = m[0];
             mid[rr][1] = m[1];
             halo[rr][0] = h[0];
@@ -334,6 +341,13 @@ template <typename T, int VEC, int LW, int R> struct Stager {
         default: Stager<T, 1, LW, R>::CALL; break;                              \
     }
 
+// A wave-uniform pointer, in scalar registers whatever the compiler thought of its provenance.
+template <typename P> __device__ __forceinline__ P* uniform_ptr(P* p) {
+    const uint64_t v = (uint64_t)(uintptr_t)p;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return (P*)(uintptr_t)(((uint64_t)hi << 32) | lo);
+}
+
 // (2) Direct staging.  One wavefront instruction moves 64 slots of SLOT bytes from per-lane
 // global addresses to 64 consecutive slots of LDS, asynchronously (counted by vmcnt).  The
 // interior of a channel tile is ROWS*TW*sizeof(T)/SLOT slots, its halo area ROWS*LW*2 four-byte
@@ -443,14 +457,18 @@ template <typename T, int SLOT, int LW, int R> struct DirectStager {
     // cmap: the channels of this chunk, by place (wave-uniform reads from constant memory).
     static __device__ __forceinline__ void issue(const Deal& d, const T* __restrict__ xrow0, uint32_t lds_buf,
                                                  const uint32_t* table, const __attribute__((address_space(4))) int32_t* cmap,
-                                                 int ccn, int hw, int nwaves, int lane) {
+                                                 int ccn, int hw, int nwaves) {
+        // the lane id is worked out here, every time, instead of living in a register across the
+        // multiply-accumulate loop (the empty asm stops the compiler from hoisting it)
+        int lane = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+        asm volatile("" : "+v"(lane));
         for (int it = d.it0; it < NPER; it += nwaves) {               // wave-uniform; one pass unless NPER > nwaves
             const uint32_t off = table[it * 64 + lane];
             const bool ok = off != kNoSlot;
             if (__builtin_amdgcn_ballot_w64(ok) == 0) continue;
             const uint32_t lds_it = lds_buf + (uint32_t)(it < NI ? it * 64 * SLOT : HOFF * (int)sizeof(T) + (it - NI) * 64 * 4);
             for (int c = d.phase; c < ccn; c += d.nphase) {
-                const T* xc = xrow0 + (int64_t)cmap[c] * hw;
+                const T* xc = uniform_ptr(xrow0 + (int64_t)cmap[c] * hw);
                 const uint32_t dst = lds_it + (uint32_t)(c * CHS * (int)sizeof(T));
                 if (ok) {
                     if (it < NI) dma<SLOT>(off, xc, dst);
@@ -509,13 +527,17 @@ void k1_tiled(const K1Args a) {
 
     // Block -> work item.  Consecutive block ids are dealt round-robin to the 8 XCDs, each with
     // its own L2, so block id i is first turned into "slot i/8 of XCD i%8" and every XCD is given a
-    // contiguous range of work items.  Work items are ordered filter block fastest, then strip,
-    // then row band: workgroups that read the same input tile (other filter blocks) or its
-    // edge columns (neighbouring strips) run on the same XCD at about the same time and find
-    // those lines in its L2.
+    // contiguous range of work items.  Work items are ordered channel share fastest, then filter
+    // block, then strip, then row band: workgroups that read the same input tile (other filter
+    // blocks), its edge columns (neighbouring strips) or add up one output tile (other shares) run
+    // on the same XCD at about the same time and find those lines in its L2.
     const int per_xcd = a.blocks_per_xcd;
     int item = (int)(blockIdx.x % 8u) * per_xcd + (int)(blockIdx.x / 8u);
     if (item >= a.work_items) return;            // grid is rounded up to a multiple of 8
+    const int slice = item % a.split_wg;         // which share of the channel chunks
+    item /= a.split_wg;
+    const int tile_id = item;                    // the output tile: (filter block, strip, row band)
+    const int q0 = slice * a.chunks / a.split_wg, q1 = (slice + 1) * a.chunks / a.split_wg;   // (products stay far below 2^31)
     const int fb = item % a.nfb;
     item /= a.nfb;
     const int strip = item % a.strips;
@@ -553,8 +575,12 @@ void k1_tiled(const K1Args a) {
 #pragma unroll
             for (int k = 0; k < 4; ++k) acc[f][rr][k] = 0.0f;
 
-    const T* lane_mid = tile + lr * R * RS + 4 * mcol;
-    const T* lane_halo = tile + HOFF + lr * R * HRS + HP * mcol;
+    // The lane's interior columns start lane_bytes into a channel tile, and its halo pair at
+    // HOFF + that offset * HRS / RS (rows of pairs are HRS long where rows of pixels are RS long, and
+    // a pair takes HP elements where a micro-column takes 4: the same ratio), so one register holds
+    // the lane's place.
+    static_assert(HRS * 4 == RS * HP && (RS % HRS == 0), "halo rows must scale with interior rows");
+    const int lane_bytes = (lr * R * RS + 4 * mcol) * (int)sizeof(T);
     const int hw = a.h * a.w;
     const uint32_t trn_magic = 0xFFFFFFFFu / (uint32_t)trn + 1u;      // ceil(2^32 / trn), trn >= 3
     const T* __restrict__ xin = static_cast<const T*>(a.x);
@@ -564,7 +590,7 @@ void k1_tiled(const K1Args a) {
     // loads).  Wavefronts beyond the last filter group walk a stream of end-of-chunk entries only.
     typedef const __attribute__((address_space(4))) typename Entry<T>::vec_t* stream_ptr_t;
     typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr_t;
-    stream_ptr_t sp = (stream_ptr_t)(a.stream) + (has_group ? ((const_i32_ptr_t)a.wave_off)[g * a.ks + ksi] : a.idle_off);
+    stream_ptr_t sp = (stream_ptr_t)(a.stream) + (has_group ? ((const_i32_ptr_t)a.wave_off)[(g * a.ks + ksi) * a.split_wg + slice] : a.idle_off);
 
     // Direct staging: ring of a.nbuf buffers of a.cc channels each; the loads of the next
     // a.nbuf - 1 chunks are in flight while a chunk is consumed.
@@ -593,34 +619,36 @@ void k1_tiled(const K1Args a) {
         const int ccn_last = a.c_in - (a.chunks - 1) * a.cc;
         PPC_DIRECT_DISPATCH(a.mode, run_setup(table, wave, nwaves, lane, a.cc, ccn_last, d_it0, d_phase, d_nphase,
                                                                d_valid, loads_full, loads_last))
-        for (int q = 0; q < ahead && q < a.chunks; ++q) {
-            const int ccn = (a.c_in - q * a.cc < a.cc) ? a.c_in - q * a.cc : a.cc;
-            PPC_DIRECT_DISPATCH(a.mode, issue(PPC_DEAL(ST), xrow0, lds_tile + (uint32_t)(q * buf_elems * (int)sizeof(T)), table,
-                                              (const_i32_ptr_t)cmap + q * a.cc, ccn, hw, nwaves, lane))
+        if (q1 != a.chunks) loads_last = loads_full;        // only the layer's last chunk can be short
+        for (int k = 0; k < ahead && q0 + k < q1; ++k) {
+            const int c0 = (q0 + k) * a.cc;
+            const int ccn = (a.c_in - c0 < a.cc) ? a.c_in - c0 : a.cc;
+            PPC_DIRECT_DISPATCH(a.mode, issue(PPC_DEAL(ST), xrow0, lds_tile + (uint32_t)(k * buf_elems * (int)sizeof(T)), table,
+                                              (const_i32_ptr_t)cmap + c0, ccn, hw, nwaves))
         }
     }
 
-    // Make chunk q readable: returns the element offset of the buffer that holds it.
+    // Make chunk q readable: returns the LDS address of the buffer that holds it.
     int ring = 0;                 // buffer that holds chunk q
-    auto begin_chunk = [&](int q) -> int {
+    auto begin_chunk = [&](int q) -> lds_cbyte_ptr {
         int boff = 0;
         if constexpr (DIRECT) {
             // chunk q has landed once no more loads are outstanding than were issued for the chunks
             // after it (q+1 .. q+ahead-1, as far as they exist; all but the last chunk are full)
-            int later = a.chunks - 1 - q;
+            int later = q1 - 1 - q;
             if (later > ahead - 1) later = ahead - 1;
             int allowed = later * loads_full;
-            if (later > 0 && q + later == a.chunks - 1) allowed += loads_last - loads_full;
+            if (later > 0 && q + later == q1 - 1) allowed += loads_last - loads_full;
             wait_vmcnt_at_most(allowed);
             __syncthreads();      // everyone's loads of chunk q have landed; everyone is done with chunk q-1
             boff = ring * buf_elems;
             const int qn = q + ahead;            // goes into the buffer chunk q-1 was read from
-            if (qn < a.chunks) {
+            if (qn < q1) {
                 const int cn0 = qn * a.cc;
                 const int ccn1 = (a.c_in - cn0 < a.cc) ? a.c_in - cn0 : a.cc;
                 const int slot = ring == 0 ? ahead : ring - 1;
                 PPC_DIRECT_DISPATCH(a.mode, issue(PPC_DEAL(ST), xrow0, lds_tile + (uint32_t)(slot * buf_elems * (int)sizeof(T)), table,
-                                                  (const_i32_ptr_t)cmap + cn0, ccn1, hw, nwaves, lane))
+                                                  (const_i32_ptr_t)cmap + cn0, ccn1, hw, nwaves))
             }
             ring = ring + 1 == a.nbuf ? 0 : ring + 1;
         } else {
@@ -630,15 +658,16 @@ void k1_tiled(const K1Args a) {
             PPC_STAGE_DISPATCH(a.vec, stage(xin, cmap + c0, tile, rowtab, ccn, trn, trn_magic, x0, a.w, hw, threadIdx.x, blockDim.x))
             __syncthreads();
         }
-        return boff;
+        return (lds_cbyte_ptr)smem_raw + boff * (int)sizeof(T);
     };
 
     // The stream walker.  Entries are fetched one ahead, so that the scalar-load latency hides behind
     // the previous kernel's multiply-accumulates, and alternately into two register sets, so that
     // no entry is ever copied: the loop body exists twice, once per set.  An end-of-chunk entry
-    // switches to the next chunk's tile; the one after the last chunk ends the loop.
-    int q = 0;
-    int boff = begin_chunk(0);
+    // switches to the next chunk's tile; the one after the last chunk of this workgroup's share ends
+    // the loop.
+    int q = q0;
+    lds_cbyte_ptr chunk_base = begin_chunk(q0);
     Window<T, R> win;
     win.clear();
     Entry<T> ea, eb;
@@ -647,8 +676,9 @@ void k1_tiled(const K1Args a) {
     {                                                                                                   \
         const uint32_t head = CUR.head();                                                               \
         if (head & kFlagNewChannel) {                                                                   \
-            const int cl = (int)(head >> kChanShift) * CHS + boff;                                      \
-            win.load(lane_mid + cl, lane_halo + cl, RS, HRS);                                           \
+            const lds_cbyte_ptr pc = chunk_base + (head >> kChanShift) * (uint32_t)(CHS * sizeof(T));   \
+            win.load(pc + lane_bytes, pc + HOFF * (int)sizeof(T) + lane_bytes / (RS / HRS),             \
+                     RS * (int)sizeof(T), HRS * (int)sizeof(T));                                        \
             /* Wait for the window here, before the next entry's scalar load is issued: LDS reads and   \
                scalar loads share one counter, so a wait placed later (inside the kernel blocks) would  \
                also wait for that prefetch and expose its latency on every kernel.  (0xC07F =           \
@@ -659,8 +689,8 @@ void k1_tiled(const K1Args a) {
         ++sp;                     /* the stream is padded by one entry past the last wavefront */       \
         NXT.v = sp[0];                                                                                  \
         if (head & kFlagEnd) {                                                                          \
-            if (++q == a.chunks) break;                                                                 \
-            boff = begin_chunk(q);                                                                      \
+            if (++q == q1) break;                                                                       \
+            chunk_base = begin_chunk(q);                                                                \
         } else {                                                                                        \
             dispatch<T, R, F, NP, COPY, 0, F * NP>((int)(head & kCodeMask), acc, win, CUR.weights());   \
         }                                                                                               \
@@ -671,10 +701,25 @@ void k1_tiled(const K1Args a) {
     }
 #undef PPC_STEP
 
+    // The epilogue reads the kernel arguments again from the argument segment (through a pointer the
+    // compiler cannot see through) instead of keeping a dozen of them in scalar registers across the
+    // loop, where scalar registers are short and every spilled one costs a vector register.
+    typedef const __attribute__((address_space(4))) K1Args* args_ptr_t;
+    args_ptr_t ka = (args_ptr_t)__builtin_amdgcn_kernarg_segment_ptr();
+    asm volatile("" : "+s"(ka));
+
+    // What the lane needs after the loop (its place in the tile) is derived again from the thread
+    // index rather than kept in registers across the loop; the empty asm keeps the compiler from
+    // merging the two computations.
+    int lane_e = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));   // lane id, without the thread index
+    asm volatile("" : "+v"(lane_e));
+    const int m_e = m0 + lane_e;
+    const int mrow_e = m_e / LW, mcol_e = m_e - mrow_e * LW;
+
     // ---- sum the channel splits through LDS, in a fixed order (deterministic) ----
-    if (a.ks > 1) {
+    if (ka->ks > 1) {
         float* red = reinterpret_cast<float*>(smem_raw);      // [wf][F*R*4][64]
-        for (int s = 1; s < a.ks; ++s) {
+        for (int s = 1; s < ka->ks; ++s) {
             __syncthreads();
             if (ksi == s) {
 #pragma unroll
@@ -683,7 +728,7 @@ void k1_tiled(const K1Args a) {
                     for (int rr = 0; rr < R; ++rr)
 #pragma unroll
                         for (int k = 0; k < 4; ++k)
-                            red[((wfi * F + f) * R * 4 + rr * 4 + k) * 64 + lane] = acc[f][rr][k];
+                            red[((wfi * F + f) * R * 4 + rr * 4 + k) * 64 + lane_e] = acc[f][rr][k];
             }
             __syncthreads();
             if (ksi == 0) {
@@ -693,49 +738,108 @@ void k1_tiled(const K1Args a) {
                     for (int rr = 0; rr < R; ++rr)
 #pragma unroll
                         for (int k = 0; k < 4; ++k)
-                            acc[f][rr][k] += red[((wfi * F + f) * R * 4 + rr * 4 + k) * 64 + lane];
+                            acc[f][rr][k] += red[((wfi * F + f) * R * 4 + rr * 4 + k) * 64 + lane_e];
             }
         }
     }
-    if (ksi != 0 || !has_group || mrow >= a.mrows) return;
-
-    // ---- epilogue: bias, ReLU, store at the filter's original index ----
-    T* __restrict__ yout = static_cast<T*>(a.y);
-    const int xcol = x0 + 4 * mcol;
-    if (xcol >= a.w) return;
-    const bool vec_store = (a.w & 3) == 0;
+    // Visit this lane's outputs: fn(f, rr, element offset of the four pixels in an [n][c_out][h][w]
+    // array, original filter index, slot).  Only the wavefronts that hold sums have any.
+    const int xcol = x0 + 4 * mcol_e;
+    const bool owns = ksi == 0 && has_group && mrow_e < ka->mrows && xcol < ka->w;
+    auto for_each_output = [&](auto&& fn) {
+        if (!owns) return;
 #pragma unroll
-    for (int rr = 0; rr < R; ++rr) {
-        const int v = mrow * R + rr;
-        if (v >= a.vh) continue;
-        const int img = v / (a.h + 1), yy = v - img * (a.h + 1);
-        if (yy >= a.h) continue;
+        for (int rr = 0; rr < R; ++rr) {
+            const int v = mrow_e * R + rr;
+            if (v >= ka->vh) continue;
+            const int img = v / (ka->h + 1), yy = v - img * (ka->h + 1);
+            if (yy >= ka->h) continue;
 #pragma unroll
-        for (int f = 0; f < F; ++f) {
-            const int co = a.perm_pad[g * F + f];
-            if (co < 0) continue;
-            const float bz = a.bias_pad[g * F + f];
-            float o[4];
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                o[k] = acc[f][rr][k] + bz;
-                if (a.relu) o[k] = o[k] > 0.0f ? o[k] : 0.0f;
+            for (int f = 0; f < F; ++f) {
+                const int co = ka->perm_pad[g * F + f];
+                if (co < 0) continue;
+                fn(f, rr, (((int64_t)img * ka->c_out + co) * ka->h + yy) * ka->w + xcol, g * F + f);
             }
-            T* dst = yout + (((int64_t)img * a.c_out + co) * a.h + yy) * a.w + xcol;
-            if (vec_store) {
-                typename VecOf<T, 4>::type ov;
-                ov[0] = (T)o[0];
-                ov[1] = (T)o[1];
-                ov[2] = (T)o[2];
-                ov[3] = (T)o[3];
-                *reinterpret_cast<typename VecOf<T, 4>::type*>(dst) = ov;
+        }
+    };
+    const bool vec_store = (ka->w & 3) == 0;
+
+    // ---- channel split across workgroups: publish this share's partial sums; the workgroup that
+    // arrives last at the tile adds up all shares, in share order whoever it is, and finishes ----
+    // The shares may run on different XCDs, whose L2 caches are not coherent with each other.  A
+    // device-scope fence would write back and invalidate a whole L2 for every workgroup; instead
+    // everything the workgroups exchange (partial sums, arrival counter) is moved with device-scope
+    // relaxed atomic loads and stores, which go past the L2, and ordered by hand: the stores have
+    // been acknowledged (vmcnt 0) before the arrival is counted, and the sums are read only after
+    // the count has come back.
+    if (ka->split_wg > 1) {
+        __shared__ int arrived;
+        float* __restrict__ mine = ka->ws + (int64_t)slice * ka->out_elems;
+        for_each_output([&](int f, int rr, int64_t off, int) {
+            if (vec_store) {      // the same kind of store, 16 bytes wide
+                const f32x4 v = {acc[f][rr][0], acc[f][rr][1], acc[f][rr][2], acc[f][rr][3]};
+                asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(mine + off), "v"(v) : "memory");
             } else {
 #pragma unroll
                 for (int k = 0; k < 4; ++k)
-                    if (xcol + k < a.w) dst[k] = (T)o[k];
+                    if (xcol + k < ka->w) __hip_atomic_store(mine + off + k, acc[f][rr][k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
-        }
+        });
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (wave == 0 && lane_e == 0) arrived = __hip_atomic_fetch_add(ka->counters + tile_id, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (arrived != ka->split_wg - 1) return;
+        if (wave == 0 && lane_e == 0) __hip_atomic_store(ka->counters + tile_id, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next launch
+        for_each_output([&](int f, int rr, int64_t off, int) {
+            float sum[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+            for (int sh = 0; sh < ka->split_wg; ++sh) {
+                if (sh == slice) {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) sum[k] += acc[f][rr][k];
+                } else {
+                    const float* theirs = ka->ws + (int64_t)sh * ka->out_elems + off;
+                    if (vec_store) {
+                        f32x4 t;
+                        asm volatile("global_load_dwordx4 %0, %1, off sc0 sc1\n\ts_waitcnt vmcnt(0)" : "=v"(t) : "v"(theirs) : "memory");
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) sum[k] += t[k];
+                    } else {
+#pragma unroll
+                        for (int k = 0; k < 4; ++k)
+                            if (xcol + k < ka->w) sum[k] += __hip_atomic_load(theirs + k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) acc[f][rr][k] = sum[k];
+        });
     }
+
+    // ---- epilogue: bias, ReLU, store at the filter's original index ----
+    T* __restrict__ yout = static_cast<T*>(ka->y);
+    for_each_output([&](int f, int rr, int64_t off, int slot) {
+        const float bz = ka->bias_pad[slot];
+        float o[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            o[k] = acc[f][rr][k] + bz;
+            if (ka->relu) o[k] = o[k] > 0.0f ? o[k] : 0.0f;
+        }
+        T* dst = yout + off;
+        if (vec_store) {
+            typename VecOf<T, 4>::type ov;
+            ov[0] = (T)o[0];
+            ov[1] = (T)o[1];
+            ov[2] = (T)o[2];
+            ov[3] = (T)o[3];
+            *reinterpret_cast<typename VecOf<T, 4>::type*>(dst) = ov;
+        } else {
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                if (xcol + k < ka->w) dst[k] = (T)o[k];
+        }
+    });
 }
 
 typedef void (*k1_launch_fn)(const K1Args& a, int blocks, int threads, int lds_bytes, hipStream_t stream);

@@ -250,6 +250,9 @@ pp_status_t build_layouts(const pp_conv_desc_t& d, HostPlan& hp) {
     if (tl.ks == 0) {
         tl.ks = 1;
         while (tl.ks < 4 && base_waves * tl.ks < want_waves && hp.c_in >= 32 * tl.ks) tl.ks *= 2;
+        // one-row wavefronts are short of multiply-accumulates per dispatch and gain from a second
+        // resident workgroup per CU (measured on 28x28 layers of 256-512 channels)
+        if (tl.ks == 1 && tl.r == 1 && base_waves < 2 * want_waves && hp.c_in >= 64) tl.ks = 2;
     }
     if (tl.ks < 1 || tl.ks > max_waves) return PP_ERR_UNSUPPORTED;
     tl.wf = t.waves_f;
@@ -320,6 +323,12 @@ pp_status_t build_layouts(const pp_conv_desc_t& d, HostPlan& hp) {
     if (tl.cc < tl.ks || tl.cc % tl.ks != 0 || tl.cc > 512 || tl.cc * tg.rows >= 65536) return PP_ERR_UNSUPPORTED;
     tl.groups = groups_f;
     tl.chunks = (hp.c_in + tl.cc - 1) / tl.cc;
+    // Channel split across workgroups: each of sw workgroups takes a contiguous share of the chunks
+    // and the last one to finish adds the shares up.  Worth it when the layer has too few output
+    // tiles to fill the chip.
+    tl.sw = t.split_wg;
+    if (tl.sw == 0) tl.sw = 1;
+    if (tl.sw < 1 || tl.sw > 64 || tl.sw > tl.chunks) return PP_ERR_UNSUPPORTED;
     hp.chosen.filters_per_wave = tl.f;
     hp.chosen.rows_per_lane = tl.r;
     hp.chosen.lanes_x = tl.lw;
@@ -327,6 +336,7 @@ pp_status_t build_layouts(const pp_conv_desc_t& d, HostPlan& hp) {
     hp.chosen.split_c = tl.ks;
     hp.chosen.chunk_c = tl.cc;
     hp.chosen.staging = tl.mode ? tl.nbuf : 1;
+    hp.chosen.split_wg = tl.sw;
 
     // ---- device layout: which filter sits in which wavefront slot, which channel in which chunk ----
     // The wavefronts of a workgroup meet at a barrier once per channel chunk, so what a chunk costs
@@ -425,7 +435,8 @@ pp_status_t build_layouts(const pp_conv_desc_t& d, HostPlan& hp) {
     static const int kDenseSlot[3] = {4, 7, 8};                       // built-in slots of the three cover patterns
     static const int kDenseTap[3][4] = {{0, 1, 3, 4}, {-1, 5, 7, 8}, {-1, 2, -1, 6}};   // source tap of each weight, -1: zero
     tl.stream.clear();
-    tl.wave_off.assign((size_t)G * KS, 0);
+    const int SW = tl.sw;
+    tl.wave_off.assign((size_t)G * KS * SW, 0);
     std::vector<Item> items;
     std::vector<size_t> first(C + 1);
     auto push_entry = [&](uint32_t header, const float* w4) {
@@ -466,8 +477,9 @@ pp_status_t build_layouts(const pp_conv_desc_t& d, HostPlan& hp) {
         for (const Item& k : items) ++first[k.ci + 1];
         for (int ci = 0; ci < C; ++ci) first[ci + 1] += first[ci];
         for (int s = 0; s < KS; ++s) {
-            tl.wave_off[(size_t)g * KS + s] = (int32_t)(tl.stream.size() / EW);
             for (int q = 0; q < Q; ++q) {
+                for (int sh = 0; sh < SW; ++sh)       // a share starts here
+                    if (q == (int)((int64_t)sh * Q / SW)) tl.wave_off[((size_t)g * KS + s) * SW + sh] = (int32_t)(tl.stream.size() / EW);
                 for (int cl = s * CS; cl < (s + 1) * CS; ++cl) {    // this wavefront's channels of chunk q, by place in the chunk
                     const int ci = cmap[q * CC + cl];
                     if (ci < 0) continue;
@@ -514,7 +526,7 @@ pp_status_t unpack_stream(const HostPlan& hp, int32_t* kidx, uint8_t* kpat, floa
     std::vector<std::vector<Rec>> per_filter(hp.c_out);
     for (int g = 0; g < tl.groups; ++g)
         for (int s = 0; s < tl.ks; ++s) {
-            size_t e = (size_t)tl.wave_off[(size_t)g * tl.ks + s];
+            size_t e = (size_t)tl.wave_off[((size_t)g * tl.ks + s) * tl.sw];
             for (int q = 0; q < tl.chunks; ++q) {
                 int ci = -1;
                 for (;; ++e) {

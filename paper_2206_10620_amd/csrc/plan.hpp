@@ -36,12 +36,13 @@ struct TiledLayout {        // geometry of the tiled kernel for one plan
     int f = 0, r = 0, lw = 0, wf = 0, ks = 0, cc = 0;
     int mode = 0;           // input staging: 0 through registers, 1 direct loads in 16-byte slots, 2 in 4-byte slots
     int nbuf = 1;           // tile buffers in LDS: 1, or the ring size of direct staging (2..8)
+    int sw = 1;             // workgroups that share one output tile, each on its own range of channel chunks
     int groups = 0;         // G = ceil(c_out / f)
     int chunks = 0;         // Q = ceil(c_in / cc)
     int entry_words = 8;    // 32-bit words per entry: 8 (header, 3 spare, 4 fp32 weights) or 4 (header, 2 words of binary16 pairs, 1 spare)
     int32_t idle_off = 0;   // first entry of the run of end-of-chunk entries walked by wavefronts without a filter group
     std::vector<uint32_t> stream;      // entries
-    std::vector<int32_t> wave_off;     // [G*ks] first entry of each (group, split) wavefront stream
+    std::vector<int32_t> wave_off;     // [G*ks*sw] first entry of each (group, split) wavefront stream in each workgroup share
     std::vector<int32_t> slot_pos;     // [G*f] position in the reordered filter list of the filter in each slot, -1 for padding
     std::vector<int32_t> chan_map;     // [filter blocks][chunks*cc] input channel staged at each place of each chunk, -1 for padding
     std::vector<int32_t> perm_pad;     // [G*f] original filter index by slot, -1 for padding

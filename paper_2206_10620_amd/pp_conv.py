@@ -13,7 +13,7 @@ PP_FLAG_RELU, PP_FLAG_DENSE, PP_FLAG_HOST_ONLY = 1, 2, 4
 
 # Bumped whenever the device code of the tiled kernel changes (measurements that are tied to a
 # kernel build, such as hardware-counter readings, are keyed by it).
-KERNEL_REVISION = "k1-2026-11-27-g"
+KERNEL_REVISION = "k1-2026-11-27-h"
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libpp_conv.so")
@@ -28,7 +28,7 @@ class PPError(RuntimeError):
 class Tuning(C.Structure):
     _fields_ = [("variant", C.c_int32), ("filters_per_wave", C.c_int32), ("rows_per_lane", C.c_int32),
                 ("lanes_x", C.c_int32), ("waves_f", C.c_int32), ("split_c", C.c_int32), ("chunk_c", C.c_int32),
-                ("staging", C.c_int32), ("balance", C.c_int32)]
+                ("staging", C.c_int32), ("split_wg", C.c_int32), ("balance", C.c_int32)]
 
     def as_dict(self):
         return {k: getattr(self, k) for k, _ in self._fields_}

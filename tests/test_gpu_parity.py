@@ -121,6 +121,48 @@ def test_staging_default_is_direct_when_rows_are_aligned():
         assert (rep["chosen"]["staging"] >= 2) == want_direct, rep["chosen"]
 
 
+# Channel split across workgroups: shares of unequal length (chunks not divisible), with and without
+# the split inside the workgroup, both staging paths, ragged widths.
+SPLITS = [dict(filters_per_wave=4, rows_per_lane=2, lanes_x=8, waves_f=4, split_c=1, chunk_c=4, split_wg=2),
+          dict(filters_per_wave=4, rows_per_lane=1, lanes_x=14, waves_f=2, split_c=2, chunk_c=4, split_wg=3),
+          dict(filters_per_wave=8, rows_per_lane=2, lanes_x=4, waves_f=3, split_c=1, chunk_c=3, split_wg=5, staging=3),
+          dict(filters_per_wave=4, rows_per_lane=4, lanes_x=16, waves_f=1, split_c=1, chunk_c=2, split_wg=4, staging=1),
+          dict(filters_per_wave=16, rows_per_lane=1, lanes_x=7, waves_f=1, split_c=4, chunk_c=8, split_wg=2, balance=1)]
+
+
+@pytest.mark.parametrize("tune", SPLITS)
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_channel_split_across_workgroups(tune, dtype):
+    say(f"split {tune} {dtype}")
+    for (n, c_in, c_out, h, w) in [(2, 23, 40, 19, 48), (3, 17, 16, 9, 45), (1, 40, 9, 33, 50)]:
+        if dtype == "f16" and w % 2 and tune.get("staging", 0) >= 2:
+            continue                                           # direct loads need rows on 4-byte boundaries
+        lay = synth.random_pruned_layer("swg", n, c_in, c_out, h, w, dtype, synth.PSET16, 0.5, 0.3, seed=13)
+        rep, _ = check_layer(lay, tuning=T(variant=2, **tune), label=f"swg{tune}")
+        assert rep["chosen"]["split_wg"] == tune["split_wg"]
+    say(f"  E={rep['E']:.2e}")
+
+
+def test_channel_split_is_deterministic_and_batches_beyond_n_hint():
+    lay = synth.random_pruned_layer("swgdet", 5, 32, 24, 14, 24, "f32", synth.PSET8, 0.5, 0.3, seed=17)
+    x = lay.make_input()
+    tune = T(variant=2, filters_per_wave=4, rows_per_lane=1, waves_f=2, split_c=1, chunk_c=4, split_wg=4)
+    # planned for 2 images, run on 5: three launches through the same workspace
+    plan = pp.plan_from_layer(lay, tuning=tune, n_hint=2)
+    xd = to_device(x)
+    outs = []
+    for _ in range(3):                                         # arrival counters must be back at zero every time
+        yd = torch.full((lay.n, lay.c_out, lay.h, lay.w), float("nan"), dtype=xd.dtype, device="cuda")
+        plan.run(xd, yd, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        outs.append(yd.cpu().numpy())
+    plan.close()
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])   # whoever arrives last
+    ref, pre, scale = oracle.layer_reference(lay, x)
+    from oracle.compare import error_report
+    assert error_report(outs[0], ref, pre, scale)["E"] <= 1e-5
+
+
 def test_degenerate_sparsity():
     base = synth.random_pruned_layer("deg", 2, 12, 20, 10, 12, "f32", synth.PSET8, 0.5, 0.3, seed=3)
     # empty mask: bias only

@@ -45,7 +45,8 @@ def test_plan_metadata_with_empty_and_full_filters_and_seeds():
 
 @pytest.mark.parametrize("dtype", ["f32", "f16"])
 @pytest.mark.parametrize("tune", [dict(), dict(filters_per_wave=4, split_c=2, chunk_c=6, waves_f=3),
-                                  dict(filters_per_wave=16, rows_per_lane=1, lanes_x=7), dict(split_c=4, chunk_c=8)])
+                                  dict(filters_per_wave=16, rows_per_lane=1, lanes_x=7), dict(split_c=4, chunk_c=8),
+                                  dict(split_c=2, chunk_c=4, split_wg=3, waves_f=2), dict(split_c=1, chunk_c=5, split_wg=8, balance=1)])
 def test_stream_round_trip(dtype, tune):
     lay = synth.random_pruned_layer("p", 2, 37, 29, 12, 20, dtype, synth.PSET16, 0.4, 0.1, 5)
     t = pp.Tuning(variant=2, **tune)
@@ -140,6 +141,9 @@ def test_staging_choice_and_limits():
         chosen(lay("f16", 45), staging=2)                   # direct loads impossible
     with pytest.raises(pp.PPError):
         chosen(lay("f32", 48), staging=9)
+    assert chosen(lay("f32", 48), chunk_c=8, split_c=1, split_wg=5)["split_wg"] == 5      # 40 channels: 5 chunks
+    with pytest.raises(pp.PPError):
+        chosen(lay("f32", 48), chunk_c=8, split_c=1, split_wg=6)                       # more shares than chunks
     with pytest.raises(pp.PPError):
         chosen(lay("f32", 48), staging=8, chunk_c=32, lanes_x=16, rows_per_lane=4)   # ring larger than LDS
 
