@@ -275,6 +275,7 @@ static pp_status_t launch_tiled(const pp_conv_plan_t* plan, const void* x_dev, v
     a.strips = (hp.w + tg.tw - 1) / tg.tw;
     a.groups = tl.groups;
     a.wf = tl.wf;
+    a.wf_recip = 65536 / tl.wf + 1;
     a.ks = tl.ks;
     a.cc = tl.cc;
     a.chunks = tl.chunks;

@@ -54,6 +54,7 @@ struct K1Args {
     int32_t blocks_per_xcd;     // ceil(work_items / 8); the grid has 8 * blocks_per_xcd blocks
     int32_t groups;             // G
     int32_t wf, ks, cc, chunks;
+    int32_t wf_recip;           // 65536 / wf + 1: (wave * wf_recip) >> 16 == wave / wf for wave < 16
     int32_t vec;                // register staging: vector width in elements
     int32_t mode;               // 0: staging through registers; 1: direct-to-LDS loads, 16-byte slots; 2: 4-byte slots
     int32_t nbuf;               // direct modes: tile buffers in the ring (2..8)
@@ -246,8 +247,8 @@ template <> struct Entry<_Float16> {
 // ---------------------------------------------------------------------------------------------
 // LDS tile of one channel: [rows][TW] interior elements, then [rows][LW] halo pairs of two 32-bit
 // words each.  Everything outside the images (padding rows, columns beyond W, the pairs of
-// neighbours that do not exist) is zero: the staging code never writes those places and the
-// buffers are zeroed once per workgroup.
+// neighbours that do not exist) is zero: written as zeros by the register path, zeroed once per
+// workgroup and never written again by the direct path.
 //
 // (1) Staging through registers, VEC elements per global load, for shapes whose rows are not
 // aligned for the direct path.  Thread t takes vectors t, t + nthreads, ... of the chunk; two
@@ -353,9 +354,10 @@ template <typename P> __device__ __forceinline__ P* uniform_ptr(P* p) {
 // interior of a channel tile is ROWS*TW*sizeof(T)/SLOT slots, its halo area ROWS*LW*2 four-byte
 // slots: NI + NH instructions per channel.  Which global element a lane fetches for instruction
 // `it` of that sequence is the same for every channel and chunk, so it is tabulated once per
-// workgroup as a byte offset from the channel's first element in use; kNoSlot marks a lane that
-// must not write (outside the images, or past the end of its area).  Such places are never
-// written at all: the buffers are zeroed once, before the first load, and stay zero there.
+// workgroup as a byte offset from the channel's first element in use.  Two codes mark lanes that
+// load nothing: kZeroSlot for a place that is read but lies outside the images (it is zeroed
+// once per buffer, before the first load, and never written again), kNoSlot for a place nobody
+// reads (rows the tile does not use, or past the end of its area).
 //
 // Buffers form a ring of NB; the loads of up to NB-1 chunks are in flight while one chunk is
 // consumed.  Loads of one wavefront complete in order, so "chunk q has landed" is "at most as
@@ -370,7 +372,7 @@ template <typename T, int SLOT, int LW, int R> struct DirectStager {
     static constexpr bool kUsable = TW % ES == 0;                     // (fp16, LW = 7 has 56-byte rows: 4-byte slots only)
     static constexpr int HE = 4 / (int)sizeof(T);                     // elements per halo slot (one 32-bit word)
     static constexpr int NI = (ROWS * SPR + 63) / 64, NH = (ROWS * LW * 2 + 63) / 64, NPER = NI + NH;
-    static constexpr uint32_t kNoSlot = 0xFFFFFFFFu;
+    static constexpr uint32_t kNoSlot = 0xFFFFFFFFu, kZeroSlot = 0xFFFFFFFEu;   // anything below is a byte offset
 
     // How the NPER instructions of each of a chunk's channels are dealt to the wavefronts:
     // wavefront w issues instruction w % NPER (and, with fewer wavefronts than instructions,
@@ -388,7 +390,7 @@ template <typename T, int SLOT, int LW, int R> struct DirectStager {
             if (tr < trn) {
                 const int rb = rowtab[tr];
                 const int col = x0 + v * ES;
-                if (rb >= 0 && col < W) off = (uint32_t)(rb - rb0 + col) * (uint32_t)sizeof(T);
+                off = (rb >= 0 && col < W) ? (uint32_t)(rb - rb0 + col) * (uint32_t)sizeof(T) : kZeroSlot;
             }
             table[j] = off;
         }
@@ -403,7 +405,7 @@ template <typename T, int SLOT, int LW, int R> struct DirectStager {
                 // (x[-2], x[-1]) on the left, (x[4], x[5]) on the right
                 const int need = x0 + 4 * mc + (side ? 4 : -1);            // column of the neighbour element
                 const int first = side ? need : need - (HE - 1);           // first column of the word
-                if (rb >= 0 && need >= 0 && need < W) off = (uint32_t)(rb - rb0 + first) * (uint32_t)sizeof(T);
+                off = (rb >= 0 && need >= 0 && need < W) ? (uint32_t)(rb - rb0 + first) * (uint32_t)sizeof(T) : kZeroSlot;
             }
             htab[j] = off;
         }
@@ -419,7 +421,7 @@ template <typename T, int SLOT, int LW, int R> struct DirectStager {
             return;
         }
         for (int it = d.it0; it < NPER; it += nwaves)
-            if (__builtin_amdgcn_ballot_w64(table[it * 64 + lane] != kNoSlot) != 0) ++d.valid_its;
+            if (__builtin_amdgcn_ballot_w64(table[it * 64 + lane] < kZeroSlot) != 0) ++d.valid_its;
     }
     // load instructions this wavefront issues for a chunk of ccn channels
     static __device__ __forceinline__ int loads_per_chunk(const Deal& d, int ccn) {
@@ -438,6 +440,27 @@ template <typename T, int SLOT, int LW, int R> struct DirectStager {
         valid = d.valid_its;
         loads_full = loads_per_chunk(d, cc);
         loads_last = loads_per_chunk(d, ccn_last);
+    }
+
+    // Zero the places marked kZeroSlot in every channel of every buffer (nbuf * cc channel tiles in a
+    // row, CHS elements apart), with the instructions dealt to the wavefronts as the loads are.
+    static __device__ __forceinline__ void zero_holes(const Deal& d, const uint32_t* table, unsigned char* tiles, int nchan,
+                                                      int nwaves, int lane) {
+        for (int it = d.it0; it < NPER; it += nwaves) {
+            const bool hole = table[it * 64 + lane] == kZeroSlot;
+            if (__builtin_amdgcn_ballot_w64(hole) == 0) continue;
+            unsigned char* p = tiles + (it < NI ? (it * 64 + lane) * SLOT : HOFF * (int)sizeof(T) + ((it - NI) * 64 + lane) * 4);
+            for (int c = d.phase; c < nchan; c += d.nphase) {
+                unsigned char* pc = p + c * (CHS * (int)sizeof(T));
+                if (!hole) continue;
+                if (it < NI) {
+                    if constexpr (SLOT == 16) *reinterpret_cast<f32x4*>(pc) = f32x4(0);
+                    else *reinterpret_cast<uint32_t*>(pc) = 0u;
+                } else {
+                    *reinterpret_cast<uint32_t*>(pc) = 0u;
+                }
+            }
+        }
     }
 
     // One direct load: lanes with a slot fetch SLOT bytes at base + off into LDS at lds_dst + lane*SLOT.
@@ -464,7 +487,7 @@ template <typename T, int SLOT, int LW, int R> struct DirectStager {
         asm volatile("" : "+v"(lane));
         for (int it = d.it0; it < NPER; it += nwaves) {               // wave-uniform; one pass unless NPER > nwaves
             const uint32_t off = table[it * 64 + lane];
-            const bool ok = off != kNoSlot;
+            const bool ok = off < kZeroSlot;
             if (__builtin_amdgcn_ballot_w64(ok) == 0) continue;
             const uint32_t lds_it = lds_buf + (uint32_t)(it < NI ? it * 64 * SLOT : HOFF * (int)sizeof(T) + (it - NI) * 64 * 4);
             for (int c = d.phase; c < ccn; c += d.nphase) {
@@ -523,7 +546,7 @@ void k1_tiled(const K1Args a) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nwaves = a.wf * a.ks;
-    const int wfi = wave % a.wf, ksi = wave / a.wf;
+    const int ksi = (wave * a.wf_recip) >> 16, wfi = wave - ksi * a.wf;   // wave / wf, wave % wf (wave < 16)
 
     // Block -> work item.  Consecutive block ids are dealt round-robin to the 8 XCDs, each with
     // its own L2, so block id i is first turned into "slot i/8 of XCD i%8" and every XCD is given a
@@ -534,10 +557,14 @@ void k1_tiled(const K1Args a) {
     const int per_xcd = a.blocks_per_xcd;
     int item = (int)(blockIdx.x % 8u) * per_xcd + (int)(blockIdx.x / 8u);
     if (item >= a.work_items) return;            // grid is rounded up to a multiple of 8
-    const int slice = item % a.split_wg;         // which share of the channel chunks
-    item /= a.split_wg;
+    int slice = 0, q0 = 0, q1 = a.chunks;        // which share of the channel chunks
+    if (a.split_wg > 1) {
+        slice = item % a.split_wg;
+        item /= a.split_wg;
+        q0 = slice * a.chunks / a.split_wg;      // (products stay far below 2^31)
+        q1 = (slice + 1) * a.chunks / a.split_wg;
+    }
     const int tile_id = item;                    // the output tile: (filter block, strip, row band)
-    const int q0 = slice * a.chunks / a.split_wg, q1 = (slice + 1) * a.chunks / a.split_wg;   // (products stay far below 2^31)
     const int fb = item % a.nfb;
     item /= a.nfb;
     const int strip = item % a.strips;
@@ -603,10 +630,7 @@ void k1_tiled(const K1Args a) {
 #define PPC_DEAL(ST) typename ST::Deal{d_it0, d_phase, d_nphase, d_valid}
     const int ahead = a.nbuf - 1;
     if constexpr (DIRECT) {
-        // zero every buffer once: places without a slot are never written afterwards
-        for (int i = threadIdx.x * 16; i < a.table_offset; i += blockDim.x * 16)
-            *reinterpret_cast<f32x4*>(smem_raw + i) = f32x4(0);
-        __syncthreads();          // rowtab written, buffers zeroed
+        __syncthreads();          // rowtab written
         int rb0 = rowtab[0];
         if (rb0 < 0) rb0 = rowtab[1];
         if (rb0 < 0) rb0 = rowtab[2];          // two consecutive virtual rows are never both outside the images
@@ -620,6 +644,8 @@ void k1_tiled(const K1Args a) {
         PPC_DIRECT_DISPATCH(a.mode, run_setup(table, wave, nwaves, lane, a.cc, ccn_last, d_it0, d_phase, d_nphase,
                                                                d_valid, loads_full, loads_last))
         if (q1 != a.chunks) loads_last = loads_full;        // only the layer's last chunk can be short
+        // zero, once, the places inside the tiles that lie outside the images: no load ever writes them
+        PPC_DIRECT_DISPATCH(a.mode, zero_holes(PPC_DEAL(ST), table, smem_raw, a.nbuf * a.cc, nwaves, lane))
         for (int k = 0; k < ahead && q0 + k < q1; ++k) {
             const int c0 = (q0 + k) * a.cc;
             const int ccn = (a.c_in - c0 < a.cc) ? a.c_in - c0 : a.cc;
