@@ -296,6 +296,7 @@ static pp_status_t launch_tiled(const pp_conv_plan_t* plan, const void* x_dev, v
     a.blocks_per_xcd = (int)((items + 7) / 8);
     const int64_t blocks = (int64_t)a.blocks_per_xcd * 8;
     const int lds = (int)k1_lds_layout_bytes(tl.lw, tl.r, tl.f, tl.wf, tl.ks, tl.cc, eb, tl.mode, tl.nbuf);
+    a.red_par = tl.ks > 1 ? std::max(1, std::min(tl.ks - 1, lds / (tl.wf * tl.f * tl.r * 4 * 64 * 4))) : 1;
     plan->launch(a, (int)blocks, 64 * tl.wf * tl.ks, lds, stream);
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_DEVICE;
 }

@@ -55,6 +55,7 @@ struct K1Args {
     int32_t groups;             // G
     int32_t wf, ks, cc, chunks;
     int32_t wf_recip;           // 65536 / wf + 1: (wave * wf_recip) >> 16 == wave / wf for wave < 16
+    int32_t red_par;            // channel splits whose partial sums fit in LDS side by side (1 .. ks-1)
     int32_t vec;                // register staging: vector width in elements
     int32_t mode;               // 0: staging through registers; 1: direct-to-LDS loads, 16-byte slots; 2: 4-byte slots
     int32_t nbuf;               // direct modes: tile buffers in the ring (2..8)
@@ -206,17 +207,20 @@ __device__ __forceinline__ void mac_kernel(float (&acc)[F][R][4], const Window<T
 // Wave-uniform dispatch on code = filter slot * NP + pattern slot: a balanced tree of scalar
 // compares down to the specialised block.  COPY tells the two copies of the tree apart (the
 // stream walker is unrolled twice).
-template <typename T, int R, int F, int NP, int COPY, int LO, int HI>
-__device__ __forceinline__ void dispatch(int code, float (&acc)[F][R][4], const Window<T, R>& win, const Weights<T>& wt) {
+template <typename T, int R, int F, int NP, int COPY, int LO, int HI, typename P>
+__device__ __forceinline__ void dispatch(int code, float (&acc)[F][R][4], const Window<T, R>& win, const Weights<T>& wt, P&& at_block) {
     if constexpr (HI - LO == 1) {
-        mac_kernel<T, R, F, LO / NP, LO % NP>(acc, win, wt);
-        // A distinct marker per block: without it the optimiser merges the tails of blocks that
-        // differ only in their accumulator registers and pays for it with register copies.
+        // Distinct markers per block, before and after: without the first the optimiser hoists the
+        // blocks' common beginning (at_block) back above the tree; without the second it merges the
+        // tails of blocks that differ only in their accumulator registers and pays for it with copies.
         asm volatile("; kernel block %0 copy %1" ::"n"(LO), "n"(COPY));
+        at_block();
+        mac_kernel<T, R, F, LO / NP, LO % NP>(acc, win, wt);
+        asm volatile("; end of block %0 copy %1" ::"n"(LO), "n"(COPY));
     } else {
         constexpr int MID = (LO + HI) / 2;
-        if (code < MID) dispatch<T, R, F, NP, COPY, LO, MID>(code, acc, win, wt);
-        else dispatch<T, R, F, NP, COPY, MID, HI>(code, acc, win, wt);
+        if (code < MID) dispatch<T, R, F, NP, COPY, LO, MID>(code, acc, win, wt, at_block);
+        else dispatch<T, R, F, NP, COPY, MID, HI>(code, acc, win, wt, at_block);
     }
 }
 
@@ -705,20 +709,23 @@ void k1_tiled(const K1Args a) {
             const lds_cbyte_ptr pc = chunk_base + (head >> kChanShift) * (uint32_t)(CHS * sizeof(T));   \
             win.load(pc + lane_bytes, pc + HOFF * (int)sizeof(T) + lane_bytes / (RS / HRS),             \
                      RS * (int)sizeof(T), HRS * (int)sizeof(T));                                        \
-            /* Wait for the window here, before the next entry's scalar load is issued: LDS reads and   \
-               scalar loads share one counter, so a wait placed later (inside the kernel blocks) would  \
-               also wait for that prefetch and expose its latency on every kernel.  (0xC07F =           \
-               lgkmcnt(0), vmcnt and expcnt unconstrained; the builtin, unlike inline assembly, is      \
-               visible to the compiler's own wait-count bookkeeping) */                                 \
-            __builtin_amdgcn_s_waitcnt(0xC07F);                                                         \
         }                                                                                               \
-        ++sp;                     /* the stream is padded by one entry past the last wavefront */       \
-        NXT.v = sp[0];                                                                                  \
         if (head & kFlagEnd) {                                                                          \
+            ++sp;                 /* the stream is padded by one entry past the last wavefront */       \
+            NXT.v = sp[0];                                                                              \
             if (++q == q1) break;                                                                       \
             chunk_base = begin_chunk(q);                                                                \
         } else {                                                                                        \
-            dispatch<T, R, F, NP, COPY, 0, F * NP>((int)(head & kCodeMask), acc, win, CUR.weights());   \
+            /* The window's LDS reads are left in flight across the dispatch tree and awaited at the    \
+               head of the kernel block; only then is the next entry's scalar load issued: LDS reads    \
+               and scalar loads share one counter, so a wait with that load outstanding would expose    \
+               its latency too.  (0xC07F = lgkmcnt(0), vmcnt and expcnt unconstrained; the builtin,     \
+               unlike inline assembly, is visible to the compiler's own wait-count bookkeeping) */      \
+            dispatch<T, R, F, NP, COPY, 0, F * NP>((int)(head & kCodeMask), acc, win, CUR.weights(), [&]() { \
+                __builtin_amdgcn_s_waitcnt(0xC07F);                                                     \
+                ++sp;                                                                                   \
+                NXT.v = sp[0];                                                                          \
+            });                                                                                         \
         }                                                                                               \
     }
     for (;;) {
@@ -742,29 +749,35 @@ void k1_tiled(const K1Args a) {
     const int m_e = m0 + lane_e;
     const int mrow_e = m_e / LW, mcol_e = m_e - mrow_e * LW;
 
-    // ---- sum the channel splits through LDS, in a fixed order (deterministic) ----
+    // ---- sum the channel splits through LDS, in a fixed order (deterministic): as many splits at a
+    // time as LDS has room for (red_par slabs of [wf][F*R*4][64] floats), added in split order ----
     if (ka->ks > 1) {
-        float* red = reinterpret_cast<float*>(smem_raw);      // [wf][F*R*4][64]
-        for (int s = 1; s < ka->ks; ++s) {
+        float* red = reinterpret_cast<float*>(smem_raw);
+        const int slab = ka->wf * (F * R * 4 * 64);
+        for (int s0 = 1; s0 < ka->ks; s0 += ka->red_par) {
             __syncthreads();
-            if (ksi == s) {
+            if (ksi >= s0 && ksi < s0 + ka->red_par) {
+                float* mine = red + (ksi - s0) * slab;
 #pragma unroll
                 for (int f = 0; f < F; ++f)
 #pragma unroll
                     for (int rr = 0; rr < R; ++rr)
 #pragma unroll
                         for (int k = 0; k < 4; ++k)
-                            red[((wfi * F + f) * R * 4 + rr * 4 + k) * 64 + lane_e] = acc[f][rr][k];
+                            mine[((wfi * F + f) * R * 4 + rr * 4 + k) * 64 + lane_e] = acc[f][rr][k];
             }
             __syncthreads();
             if (ksi == 0) {
+                for (int s = s0; s < s0 + ka->red_par && s < ka->ks; ++s) {
+                    const float* theirs = red + (s - s0) * slab;
 #pragma unroll
-                for (int f = 0; f < F; ++f)
+                    for (int f = 0; f < F; ++f)
 #pragma unroll
-                    for (int rr = 0; rr < R; ++rr)
+                        for (int rr = 0; rr < R; ++rr)
 #pragma unroll
-                        for (int k = 0; k < 4; ++k)
-                            acc[f][rr][k] += red[((wfi * F + f) * R * 4 + rr * 4 + k) * 64 + lane_e];
+                            for (int k = 0; k < 4; ++k)
+                                acc[f][rr][k] += theirs[((wfi * F + f) * R * 4 + rr * 4 + k) * 64 + lane_e];
+                }
             }
         }
     }
