@@ -55,14 +55,16 @@ def workloads():
     return w
 
 
-def time_layer(lay, steps, warmup, tuning=None):
+def time_layer(lay, steps, warmup, tuning=None, autotune=False):
     """Returns dict with per-step times of pp_conv_run on the current stream."""
     import torch
     import paper_2206_10620_amd as pp
-    plan = pp.plan_from_layer(lay, tuning=tuning)
     x = torch.from_numpy(lay.make_input()).cuda()
     y = torch.empty((lay.n, lay.c_out, lay.h, lay.w), dtype=x.dtype, device="cuda")
     stream = torch.cuda.current_stream().cuda_stream
+    if autotune and tuning is None:
+        tuning, _ = pp.autotune(lay, x, y, stream)
+    plan = pp.plan_from_layer(lay, tuning=tuning)
     for _ in range(warmup):
         plan.run(x, y, stream)
     torch.cuda.synchronize()
@@ -103,6 +105,9 @@ def main():
                     help="also launch one plain device copy of this many MiB (a reference dispatch for scaling "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--tuning", default="", help="f,r,wf,ks,cc overrides for the timed workload (0 = automatic)")
+    ap.add_argument("--autotune", action="store_true",
+                    help="pick the parameters of every timed workload by measurement (paper_2206_10620_amd.autotune) "
+                         "instead of the plan's own rules; reported under config.params and 'tuned'")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this library runs on ONE GPU (no collectives, no sharding); run with --gpus 1")
@@ -127,12 +132,12 @@ def main():
     if args.tuning:
         f, r, wf, ks, cc = (int(v) for v in args.tuning.split(","))
         tuning = pp.Tuning(variant=2, filters_per_wave=f, rows_per_lane=r, waves_f=wf, split_c=ks, chunk_c=cc)
-    t = time_layer(lay, args.steps, args.warmup, tuning)
+    t = time_layer(lay, args.steps, args.warmup, tuning, args.autotune)
     s = summarize(lay, t)
     sec_wall = t["wall_ms_per_step"] * 1e-3
 
     rev, tbytes = MEASURED_TRAFFIC.get(args.workload, (None, None))
-    traffic = tbytes if (rev == pp.KERNEL_REVISION and not args.tuning) else None
+    traffic = tbytes if (rev == pp.KERNEL_REVISION and not args.tuning and not args.autotune) else None
 
     out = {
         "metric": "effective GMAC/s (nonzero MACs), pattern-pruned 3x3 conv",
@@ -140,7 +145,7 @@ def main():
         "unit": "GMAC/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": t["wall_ms_per_step"],
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "tuned": bool(args.autotune),
         "dtype": lay.dtype, "data": "synthetic",
         "config": {"workload": lay.name, "n": lay.n, "c_in": lay.c_in, "c_out": lay.c_out, "h": lay.h, "w": lay.w,
                    "patterns": int(len(lay.pattern_masks)), "k_kept": lay.k_kept, "keep": lay.k_kept / (lay.c_in * lay.c_out),
@@ -190,7 +195,7 @@ def main():
                 continue
             l2 = make()
             steps = max(20, min(args.steps, int(0.5 / max(l2.eff_macs / 20e12, 1e-5))))
-            t2 = time_layer(l2, steps, max(5, args.warmup // 5))
+            t2 = time_layer(l2, steps, max(5, args.warmup // 5), None, args.autotune)
             others.append(summarize(l2, t2))
             del t2
             torch.cuda.empty_cache()

@@ -8,3 +8,4 @@ from .pp_conv import (PP_OK, PP_ERR_NULL, PP_ERR_SHAPE, PP_ERR_PATTERN, PP_ERR_U
                       PPError, Tuning, Plan, KERNEL_REVISION, lib, library_path, pp_conv_plan, pp_conv_run, pp_conv_destroy,
                       pp_conv_plan_query, pp_conv_plan_unpack, pp_maxpool2x2_run, pp_status_string,
                       plan_from_layer)
+from .autotune import autotune, default_candidates

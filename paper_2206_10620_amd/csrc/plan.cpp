@@ -241,7 +241,12 @@ pp_status_t build_layouts(const pp_conv_desc_t& d, HostPlan& hp) {
     const int groups_f = (hp.c_out + tl.f - 1) / tl.f;
     const int64_t want_waves = 3000;
     tl.r = t.rows_per_lane;
-    if (tl.r == 0) tl.r = spatial_waves(hp.n_hint, hp.h, hp.w, tl.lw, 2) * groups_f >= want_waves ? 2 : 1;
+    if (tl.r == 0) {
+        // two rows per lane double the multiply-accumulates per dispatch; worth it even when the
+        // wavefront count then has to come from a two-way channel split (measured)
+        const int64_t w2 = spatial_waves(hp.n_hint, hp.h, hp.w, tl.lw, 2) * groups_f;
+        tl.r = (w2 >= want_waves || (2 * w2 >= want_waves && hp.c_in >= 64)) ? 2 : 1;
+    }
     if (tl.r != 1 && tl.r != 2 && tl.r != 4) return PP_ERR_UNSUPPORTED;
     if (tl.r == 4 && tl.f != 4) return PP_ERR_UNSUPPORTED;
     const int max_waves = 16;                      // the kernel's launch bound

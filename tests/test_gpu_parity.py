@@ -163,6 +163,21 @@ def test_channel_split_is_deterministic_and_batches_beyond_n_hint():
     assert error_report(outs[0], ref, pre, scale)["E"] <= 1e-5
 
 
+def test_autotune_returns_a_plan_that_passes_parity():
+    lay = synth.random_pruned_layer("auto", 2, 64, 48, 28, 28, "f16", synth.PSET8, 0.5, 0.3, seed=21)
+    x = to_device(lay.make_input())
+    y = torch.empty((lay.n, lay.c_out, lay.h, lay.w), dtype=x.dtype, device="cuda")
+    tuning, report = pp.autotune(lay, x, y, steps=3, rounds=2)
+    assert len(report) >= 3 and report[0][0] <= report[-1][0]
+    assert any(not cand for _, _, cand in report)              # the automatic plan was one of the contestants
+    rep, _ = check_layer(lay, tuning=tuning, label="autotuned")
+    if tuning is not None:
+        assert rep["chosen"] == tuning.as_dict()               # the returned tuning reproduces the measured plan
+    # plans that split channels across workgroups can be left out
+    _, report2 = pp.autotune(lay, x, y, steps=2, rounds=1, allow_split_wg=False)
+    assert all(ch["split_wg"] == 1 for _, ch, _ in report2)
+
+
 def test_degenerate_sparsity():
     base = synth.random_pruned_layer("deg", 2, 12, 20, 10, 12, "f32", synth.PSET8, 0.5, 0.3, seed=3)
     # empty mask: bias only
