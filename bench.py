@@ -35,9 +35,9 @@ PEAK_HBM_GBS = 8000.0
 # kernel of known size; see profiles/k1_tiled_<workload>.md.  Valid only for the kernel revision
 # it was measured on: reported as null for any other.
 MEASURED_TRAFFIC = {
-    "cfg2_vgg_mid": ("k1-2026-11-27-j", 21.60e6),
-    "cfg5_enhance_1080p": ("k1-2026-11-27-j", 590.37e6),
-    "cfg4_vgg_L6": ("k1-2026-11-27-j", 33.70e6),
+    "cfg2_vgg_mid": ("k1-2026-11-27-k", 20.47e6),
+    "cfg5_enhance_1080p": ("k1-2026-11-27-k", 590.16e6),
+    "cfg4_vgg_L6": ("k1-2026-11-27-k", 33.09e6),
 }
 
 
