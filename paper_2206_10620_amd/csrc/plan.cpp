@@ -169,10 +169,10 @@ namespace {
 
 bool valid_lw(int lw) { return lw == 2 || lw == 4 || lw == 7 || lw == 8 || lw == 14 || lw == 16; }
 
-// Lanes across a tile.  Sixteen whenever that idles at most an eighth of the lanes: 64 micro-tiles
-// are then exactly four tile rows (widths that do not divide 64 stage one more row band) and the
-// tile is the smallest per output pixel -- measured 4-7 % faster than the exact fit of 14 on the
-// 56-, 112- and 224-wide layers.  Otherwise the width that wastes the fewest lanes.
+// Lanes across a tile.  The largest power of two that idles at most an eighth of the lanes: 64
+// micro-tiles are then a whole number of tile rows (other widths stage one more row band) and the
+// tile is the smallest per output pixel -- measured 3-7 % faster than the exact fits of 14 and 7 on
+// the 28-, 56-, 112- and 224-wide fp16 layers.  Otherwise the width that wastes the fewest lanes.
 int pick_lw(int w) {
     const int cand[] = {16, 14, 8, 7, 4, 2};
     int best = 16;
@@ -181,7 +181,7 @@ int pick_lw(int w) {
         int tw = lw * kPW;
         int strips = (w + tw - 1) / tw;
         double waste = (double)strips * tw / w;
-        if (lw == 16 && waste <= 1.15) return 16;
+        if ((lw & (lw - 1)) == 0 && waste <= 1.15) return lw;
         if (waste < best_waste - 1e-9) {
             best_waste = waste;
             best = lw;
