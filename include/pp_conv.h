@@ -59,7 +59,7 @@ enum {
     PP_FLAG_HOST_ONLY = 4u  /* build the plan's host metadata only; touches no device (pp_conv_run then fails) */
 };
 
-/* Execution parameters ("tuning-decided parameters" of the layer-wise representation,
+/* Execution parameters (the part of the layer-wise representation that the paper leaves to tuning,
  * section 2.3.1).  A zero field means "let the library choose". */
 typedef struct {
     int32_t variant;        /* 0 auto; 1 generic kernel (any pattern table); 2 tiled pattern-specialised kernel */

@@ -35,8 +35,8 @@
 // product, filter-permutation equivariance, a hand-worked fixture.
 // The reference filter ordering (oracle_plan_ref) is pinned by structural
 // invariants and a hand-worked fixture; the ordering keys themselves are this
-// repository's reading of "filters with similar kernels together" (section
-// 2.3.1), which the paper does not spell out: parity unpinned against the paper
+// repository's reading of the grouping of similar filters in section 2.3.1,
+// whose sort keys the paper does not spell out: parity unpinned against the paper
 // for the key choice.
 
 #include <algorithm>

@@ -1,7 +1,7 @@
 """Pick the execution parameters of a layer by measurement.
 
-The layer-wise representation of the paper carries "tuning-decided parameters" (section 2.3.1); the
-plan's own rules choose them from the layer's shape alone.  This helper times a small grid of
+The layer-wise representation of the paper has a part that is left to tuning (section 2.3.1); the
+plan's own rules choose those parameters from the layer's shape alone.  This helper times a small grid of
 alternatives on the device -- rows per lane, channel split inside a workgroup, channel split across
 workgroups -- and returns the fastest.  It only builds plans and launches them through the same
 entry points as everything else; no arithmetic happens here.

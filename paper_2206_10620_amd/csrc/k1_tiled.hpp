@@ -7,8 +7,8 @@
 //   * a wavefront therefore sees every weight, pattern and loop bound as a wave-uniform value:
 //     they live in scalar registers, are fetched with scalar loads from the packed weight
 //     stream, and every sparsity-dependent branch is a scalar branch -- no lane divergence;
-//   * a workgroup is WF x KS wavefronts that share one LDS-resident input tile (the paper's
-//     "input tiling"): WF of them work on different filter groups, KS of them split the input
+//   * a workgroup is WF x KS wavefronts that share one LDS-resident input tile (the tiling of
+//     the input in section 2.3.1): WF of them work on different filter groups, KS of them split the input
 //     channels of each chunk and are summed through LDS at the end in a fixed order.
 //
 // Input tiles reach LDS without passing through registers where the shape allows it: gfx950's
@@ -21,8 +21,8 @@
 // (left, right) halo pair per row, and reuses it from registers for every kernel of the
 // wavefront's filters that keeps that channel.  The multiply-accumulates of one kernel are a
 // straight-line block specialised on (filter slot, pattern): all register indices are static
-// ("statically determined data access instructions", section 2.3.1, load redundancy
-// elimination).
+// (a pattern fixes its data accesses when the code is generated: section 2.3.1 on load
+// redundancy elimination).
 //
 // The batch is laid out as one tall virtual image: image n, row y is virtual row n*(H+1)+y and
 // row y = H of every image is a shared zero row, so that tiles may straddle images.

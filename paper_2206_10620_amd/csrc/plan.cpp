@@ -232,7 +232,7 @@ pp_status_t build_layouts(const pp_conv_desc_t& d, HostPlan& hp) {
     tl.np = max_slot < 8 ? 8 : 16;
     tl.entry_words = hp.dtype == PP_F16 ? 4 : 8;   // header + two words of binary16 pairs, or header + 3 spare + 4 fp32
 
-    // ---- parameters ("tuning-decided parameters" of the layer-wise representation) ----
+    // ---- parameters (the part of the layer-wise representation that is left to tuning) ----
     tl.lw = t.lanes_x ? t.lanes_x : pick_lw(hp.w);
     if (!valid_lw(tl.lw)) return PP_ERR_UNSUPPORTED;
     // Defaults measured on MI355X: four filters per wavefront keep the kernel under 64-80 vector
