@@ -35,9 +35,9 @@ PEAK_HBM_GBS = 8000.0
 # kernel of known size; see profiles/k1_tiled_<workload>.md.  Valid only for the kernel revision
 # it was measured on: reported as null for any other.
 MEASURED_TRAFFIC = {
-    "cfg2_vgg_mid": ("k1-2026-11-27-k", 20.47e6),
-    "cfg5_enhance_1080p": ("k1-2026-11-27-k", 590.16e6),
-    "cfg4_vgg_L6": ("k1-2026-11-27-k", 33.09e6),
+    "cfg2_vgg_mid": ("k1-2026-11-27-m", 20.43e6),
+    "cfg5_enhance_1080p": ("k1-2026-11-27-m", 590.66e6),
+    "cfg4_vgg_L6": ("k1-2026-11-27-m", 33.08e6),
 }
 
 

@@ -205,33 +205,51 @@ __device__ __forceinline__ void mac_kernel(float (&acc)[F][R][4], const Window<T
 }
 
 // Wave-uniform dispatch on code = filter slot * NP + pattern slot: a balanced tree of scalar
-// compares down to the specialised block.  COPY tells the two copies of the tree apart (the
-// stream walker is unrolled twice).
-template <typename T, int R, int F, int NP, int COPY, int LO, int HI, typename P>
-__device__ __forceinline__ void dispatch(int code, float (&acc)[F][R][4], const Window<T, R>& win, const Weights<T>& wt, P&& at_block) {
-    if constexpr (HI - LO == 1) {
-        // Distinct markers per block, before and after: without the first the optimiser hoists the
-        // blocks' common beginning (at_block) back above the tree; without the second it merges the
-        // tails of blocks that differ only in their accumulator registers and pays for it with copies.
-        asm volatile("; kernel block %0 copy %1" ::"n"(LO), "n"(COPY));
-        at_block();
-        mac_kernel<T, R, F, LO / NP, LO % NP>(acc, win, wt);
-        asm volatile("; end of block %0 copy %1" ::"n"(LO), "n"(COPY));
-    } else {
-        constexpr int MID = (LO + HI) / 2;
-        if (code < MID) dispatch<T, R, F, NP, COPY, LO, MID>(code, acc, win, wt, at_block);
-        else dispatch<T, R, F, NP, COPY, MID, HI>(code, acc, win, wt, at_block);
+// compares down to the specialised block.  The tree is spelled with macros rather than a recursive
+// template so that the end-of-chunk entry can be one more leaf of it (next to the last kernel
+// code: the end code is larger than every kernel code) and leave the walker's loop from there;
+// the kernels then pay no test of their own for it.  The expansion site provides: code, acc, win,
+// wt, the constant kCopy that tells the two copies of the tree apart (the stream walker is
+// unrolled twice), and the macros PPC_AT_BLOCK (statements at the head of a kernel block) and
+// PPC_AT_END (statements of the end-of-chunk leaf).
+// Distinct markers per block, before and after: without the first the optimiser hoists the blocks'
+// common beginning back above the tree; without the second it merges the tails of blocks that
+// differ only in their accumulator registers and pays for it with copies.
+#define PPC_KERNEL_BLOCK(LO)                                                       \
+    {                                                                              \
+        asm volatile("; kernel block %0 copy %1" ::"n"(LO), "n"(kCopy));           \
+        PPC_AT_BLOCK                                                               \
+        mac_kernel<T, R, F, (LO) / NP, (LO) % NP>(acc, win, wt);                   \
+        asm volatile("; end of block %0 copy %1" ::"n"(LO), "n"(kCopy));           \
     }
-}
+#define PPC_T1(LO)                                                                 \
+    if constexpr ((LO) == F * NP - 1) {                                            \
+        if (__builtin_expect(code == (uint32_t)(LO), 1)) PPC_KERNEL_BLOCK(LO) else { PPC_AT_END } \
+    } else PPC_KERNEL_BLOCK(LO)
+#define PPC_T2(LO) if (code < (uint32_t)((LO) + 1)) { PPC_T1(LO) } else { PPC_T1((LO) + 1) }
+#define PPC_T4(LO) if (code < (uint32_t)((LO) + 2)) { PPC_T2(LO) } else { PPC_T2((LO) + 2) }
+#define PPC_T8(LO) if (code < (uint32_t)((LO) + 4)) { PPC_T4(LO) } else { PPC_T4((LO) + 4) }
+#define PPC_T16(LO) if (code < (uint32_t)((LO) + 8)) { PPC_T8(LO) } else { PPC_T8((LO) + 8) }
+#define PPC_T32(LO) if (code < (uint32_t)((LO) + 16)) { PPC_T16(LO) } else { PPC_T16((LO) + 16) }
+#define PPC_T64(LO) if (code < (uint32_t)((LO) + 32)) { PPC_T32(LO) } else { PPC_T32((LO) + 32) }
+#define PPC_T128(LO) if (code < (uint32_t)((LO) + 64)) { PPC_T64(LO) } else { PPC_T64((LO) + 64) }
+#define PPC_T256(LO) if (code < (uint32_t)((LO) + 128)) { PPC_T128(LO) } else { PPC_T128((LO) + 128) }
+#define PPC_DISPATCH_TREE                                                          \
+    static_assert(F * NP == 32 || F * NP == 64 || F * NP == 128 || F * NP == 256); \
+    if constexpr (F * NP == 32) { PPC_T32(0) }                                     \
+    else if constexpr (F * NP == 64) { PPC_T64(0) }                                \
+    else if constexpr (F * NP == 128) { PPC_T128(0) }                              \
+    else { PPC_T256(0) }
 
 // One stream entry in scalar registers, fetched with a single scalar load.
-//   fp32: 8 words {header, -, -, -, w0, w1, w2, w3};   fp16: 4 words {header, w0|w1<<16, w2|w3<<16, -}
+//   fp32: 8 words {code, channel, -, -, w0, w1, w2, w3};   fp16: 4 words {code, w0|w1<<16, w2|w3<<16, channel}
 template <typename T> struct Entry;
 template <> struct Entry<float> {
     static constexpr int kWords = 8;
     typedef uint32_t vec_t __attribute__((ext_vector_type(8)));
     vec_t v;
-    __device__ __forceinline__ uint32_t head() const { return v[0]; }
+    __device__ __forceinline__ uint32_t code() const { return v[0]; }
+    __device__ __forceinline__ uint32_t channel() const { return v[1]; }
     __device__ __forceinline__ Weights<float> weights() const {
         // (element values are copied out first: a bit cast applied to a vector element expression
         // directly reads the wrong element with this compiler)
@@ -244,7 +262,8 @@ template <> struct Entry<_Float16> {
     static constexpr int kWords = 4;
     typedef uint32_t vec_t __attribute__((ext_vector_type(4)));
     vec_t v;
-    __device__ __forceinline__ uint32_t head() const { return v[0]; }
+    __device__ __forceinline__ uint32_t code() const { return v[0]; }
+    __device__ __forceinline__ uint32_t channel() const { return v[3]; }
     __device__ __forceinline__ Weights<_Float16> weights() const { return Weights<_Float16>{{v[1], v[2]}}; }
 };
 
@@ -693,45 +712,52 @@ void k1_tiled(const K1Args a) {
 
     // The stream walker.  Entries are fetched one ahead, so that the scalar-load latency hides behind
     // the previous kernel's multiply-accumulates, and alternately into two register sets, so that
-    // no entry is ever copied: the loop body exists twice, once per set.  An end-of-chunk entry
-    // switches to the next chunk's tile; the one after the last chunk of this workgroup's share ends
-    // the loop.
-    int q = q0;
-    lds_cbyte_ptr chunk_base = begin_chunk(q0);
+    // no entry is ever copied: the loop body exists twice, once per set, and the two copies fetch
+    // at fixed offsets from one pointer that moves once per pair.  An end-of-chunk entry leaves the
+    // inner loop; the outer loop switches to the next chunk's tile and restarts the pairs at the
+    // entry after it.
+    // The window's LDS reads are left in flight across the dispatch tree and awaited at the head of
+    // the kernel block; only then is the next entry's scalar load issued: LDS reads and scalar loads
+    // share one counter, so a wait with that load outstanding would expose its latency too.
+    // (0xC07F = lgkmcnt(0), vmcnt and expcnt unconstrained; the builtin, unlike inline assembly, is
+    // visible to the compiler's own wait-count bookkeeping)
     Window<T, R> win;
     win.clear();
     Entry<T> ea, eb;
-    ea.v = sp[0];
 #define PPC_STEP(CUR, NXT, COPY)                                                                        \
     {                                                                                                   \
-        const uint32_t head = CUR.head();                                                               \
-        if (head & kFlagNewChannel) {                                                                   \
-            const lds_cbyte_ptr pc = chunk_base + (head >> kChanShift) * (uint32_t)(CHS * sizeof(T));   \
+        constexpr int kCopy = COPY;                                                                     \
+        const uint32_t chan = CUR.channel();                                                            \
+        if (chan != kSameChannel) {                                                                     \
+            const lds_cbyte_ptr pc = chunk_base + chan;                                                 \
             win.load(pc + lane_bytes, pc + HOFF * (int)sizeof(T) + lane_bytes / (RS / HRS),             \
                      RS * (int)sizeof(T), HRS * (int)sizeof(T));                                        \
         }                                                                                               \
-        if (head & kFlagEnd) {                                                                          \
-            ++sp;                 /* the stream is padded by one entry past the last wavefront */       \
-            NXT.v = sp[0];                                                                              \
-            if (++q == q1) break;                                                                       \
-            chunk_base = begin_chunk(q);                                                                \
-        } else {                                                                                        \
-            /* The window's LDS reads are left in flight across the dispatch tree and awaited at the    \
-               head of the kernel block; only then is the next entry's scalar load issued: LDS reads    \
-               and scalar loads share one counter, so a wait with that load outstanding would expose    \
-               its latency too.  (0xC07F = lgkmcnt(0), vmcnt and expcnt unconstrained; the builtin,     \
-               unlike inline assembly, is visible to the compiler's own wait-count bookkeeping) */      \
-            dispatch<T, R, F, NP, COPY, 0, F * NP>((int)(head & kCodeMask), acc, win, CUR.weights(), [&]() { \
-                __builtin_amdgcn_s_waitcnt(0xC07F);                                                     \
-                ++sp;                                                                                   \
-                NXT.v = sp[0];                                                                          \
-            });                                                                                         \
-        }                                                                                               \
+        const uint32_t code = CUR.code();                                                               \
+        const Weights<T> wt = CUR.weights();                                                            \
+        PPC_DISPATCH_TREE                                                                               \
     }
-    for (;;) {
-        PPC_STEP(ea, eb, 0)
-        PPC_STEP(eb, ea, 1)
+#define PPC_AT_BLOCK                        \
+    __builtin_amdgcn_s_waitcnt(0xC07F);     \
+    NXT_ENTRY.v = sp[kCopy + 1];
+#define PPC_AT_END          \
+    sp += kCopy + 1;        \
+    break;
+    for (int q = q0; q < q1; ++q) {
+        const lds_cbyte_ptr chunk_base = begin_chunk(q);
+        ea.v = sp[0];
+        for (;;) {
+#define NXT_ENTRY eb
+            PPC_STEP(ea, eb, 0)
+#undef NXT_ENTRY
+#define NXT_ENTRY ea
+            PPC_STEP(eb, ea, 1)
+#undef NXT_ENTRY
+            sp += 2;
+        }
     }
+#undef PPC_AT_BLOCK
+#undef PPC_AT_END
 #undef PPC_STEP
 
     // The epilogue reads the kernel arguments again from the argument segment (through a pointer the

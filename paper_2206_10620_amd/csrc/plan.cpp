@@ -449,10 +449,13 @@ pp_status_t build_layouts(const pp_conv_desc_t& d, HostPlan& hp) {
     tl.wave_off.assign((size_t)G * KS * SW, 0);
     std::vector<Item> items;
     std::vector<size_t> first(C + 1);
-    auto push_entry = [&](uint32_t header, const float* w4) {
+    const int chan_word = hp.dtype == PP_F16 ? 3 : 1;      // where the channel word sits in an entry
+    const uint32_t chan_stride_bytes = (uint32_t)(tg.chs * eb);
+    auto push_entry = [&](uint32_t code, uint32_t chan, const float* w4) {
         size_t at = tl.stream.size();
         tl.stream.resize(at + EW, 0u);
-        tl.stream[at] = header;
+        tl.stream[at] = code;
+        tl.stream[at + chan_word] = chan;
         if (!w4) return;
         if (hp.dtype == PP_F16) {    // binary16 storage: the weights are rounded here, once
             uint16_t hb[4];
@@ -495,29 +498,29 @@ pp_status_t build_layouts(const pp_conv_desc_t& d, HostPlan& hp) {
                     if (ci < 0) continue;
                     for (size_t j = first[ci]; j < first[ci + 1]; ++j) {
                         const Item& k = items[j];
-                        uint32_t header = (uint32_t)(k.fl * tl.np + k.slot);
-                        if (j == first[ci]) header |= kFlagNewChannel;
-                        header |= (uint32_t)cl << kChanShift;
+                        const uint32_t code = (uint32_t)(k.fl * tl.np + k.slot);
+                        const uint32_t chan = j == first[ci] ? (uint32_t)cl * chan_stride_bytes : kSameChannel;
                         if (!dense) {
-                            push_entry(header, &cn.wpacked[(size_t)k.src * 4]);
+                            push_entry(code, chan, &cn.wpacked[(size_t)k.src * 4]);
                         } else {
                             float w4[4];
                             for (int j4 = 0; j4 < 4; ++j4) {
                                 const int tap = kDenseTap[k.part][j4];
                                 w4[j4] = tap < 0 ? 0.0f : cn.wpacked[(size_t)k.src * 9 + tap];
                             }
-                            push_entry(header, w4);
+                            push_entry(code, chan, w4);
                         }
                     }
                 }
-                push_entry(kFlagEnd, nullptr);
+                push_entry(kEndCode, kSameChannel, nullptr);
             }
         }
     }
     // what wavefronts without a filter group walk: one end-of-chunk entry per chunk
     tl.idle_off = (int32_t)(tl.stream.size() / EW);
-    for (int q = 0; q < Q; ++q) push_entry(kFlagEnd, nullptr);
-    push_entry(kFlagEnd, nullptr);     // the walker prefetches one entry ahead
+    for (int q = 0; q < Q; ++q) push_entry(kEndCode, kSameChannel, nullptr);
+    push_entry(kEndCode, kSameChannel, nullptr);     // the walker prefetches up to two entries ahead
+    push_entry(kEndCode, kSameChannel, nullptr);
     if (tl.stream.size() / EW >= ((size_t)1 << 31)) return PP_ERR_SHAPE;
     return PP_OK;
 }
@@ -532,6 +535,7 @@ pp_status_t unpack_stream(const HostPlan& hp, int32_t* kidx, uint8_t* kpat, floa
         int s = builtin_slot(hp.masks[p]);
         if (s >= 0) pid_of[s] = p;
     }
+    const uint32_t chan_stride = (uint32_t)(tile_geom(tl.lw, tl.r, hp.dtype == PP_F16 ? 2 : 4).chs * (hp.dtype == PP_F16 ? 2 : 4));
     struct Rec { int pat, ci; float w[4]; };
     std::vector<std::vector<Rec>> per_filter(hp.c_out);
     for (int g = 0; g < tl.groups; ++g)
@@ -541,13 +545,14 @@ pp_status_t unpack_stream(const HostPlan& hp, int32_t* kidx, uint8_t* kpat, floa
                 int ci = -1;
                 for (;; ++e) {
                     const uint32_t* ent = &tl.stream[e * EW];
-                    if (ent[0] & kFlagEnd) {
+                    if (ent[0] == kEndCode) {
                         ++e;
                         break;
                     }
-                    if (ent[0] & kFlagNewChannel)
-                        ci = tl.chan_map[((size_t)(g / tl.wf) * tl.chunks + q) * tl.cc + (int)(ent[0] >> kChanShift)];
-                    int code = (int)(ent[0] & kCodeMask);
+                    const uint32_t chan = ent[hp.dtype == PP_F16 ? 3 : 1];
+                    if (chan != kSameChannel)
+                        ci = tl.chan_map[((size_t)(g / tl.wf) * tl.chunks + q) * tl.cc + (int)(chan / chan_stride)];
+                    int code = (int)ent[0];
                     int pos = tl.slot_pos[(size_t)g * tl.f + code / tl.np];
                     if (pos < 0 || ci < 0) return PP_ERR_UNSUPPORTED;
                     Rec r;

@@ -18,11 +18,12 @@ constexpr int kBuiltinPatterns = 16;
 constexpr uint16_t kBuiltinMasks[kBuiltinPatterns] = {0x03A, 0x0B2, 0x0B8, 0x09A, 0x01B, 0x036, 0x0D8, 0x1B0,
                                                       0x055, 0x115, 0x151, 0x154, 0x152, 0x11C, 0x071, 0x095};
 
-// Weight-stream entry header bits (first 32-bit word of every entry).
-constexpr uint32_t kCodeMask = 0xFFu;      // bits 0-7 : local filter slot * NP + pattern slot
-constexpr uint32_t kFlagNewChannel = 0x100u;  // bit 8 : first kernel of an input channel: reload the lane's input window
-constexpr uint32_t kFlagEnd = 0x200u;         // bit 9 : end of this wavefront's work for the current channel chunk
-constexpr int kChanShift = 16;             // bits 16-31: channel index inside the chunk
+// Weight-stream entry: word 0 is the kernel's code = local filter slot * NP + pattern slot, or
+// kEndCode for the end of this wavefront's work in the current channel chunk; the channel word is
+// kSameChannel, or, on the first kernel of an input channel, the byte offset of that channel's
+// tile inside the LDS chunk buffer (place in chunk * channel stride): reload the lane's window.
+constexpr uint32_t kEndCode = 0x00FFFFFFu;
+constexpr uint32_t kSameChannel = 0xFFFFFFFFu;
 
 struct Canonical {          // tuning-independent result of the reorder
     std::vector<int32_t> perm, kcount, pat_off, kidx;
@@ -39,7 +40,7 @@ struct TiledLayout {        // geometry of the tiled kernel for one plan
     int sw = 1;             // workgroups that share one output tile, each on its own range of channel chunks
     int groups = 0;         // G = ceil(c_out / f)
     int chunks = 0;         // Q = ceil(c_in / cc)
-    int entry_words = 8;    // 32-bit words per entry: 8 (header, 3 spare, 4 fp32 weights) or 4 (header, 2 words of binary16 pairs, 1 spare)
+    int entry_words = 8;    // 32-bit words per entry: 8 (code, channel, 2 spare, 4 fp32 weights) or 4 (code, 2 words of binary16 pairs, channel)
     int32_t idle_off = 0;   // first entry of the run of end-of-chunk entries walked by wavefronts without a filter group
     std::vector<uint32_t> stream;      // entries
     std::vector<int32_t> wave_off;     // [G*ks*sw] first entry of each (group, split) wavefront stream in each workgroup share
