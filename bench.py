@@ -1,18 +1,28 @@
 #!/usr/bin/env python3
-"""Throughput of the pattern-pruned 3x3 convolution on one MI355X.
+"""Throughput of the pattern-pruned convolution on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--all] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-others] [--no-cpu]
 
-A step is one forward pass of the whole hot path (LDS staging, pattern-specialised
-multiply-accumulates, fused bias+ReLU epilogue) over one batch of seeded synthetic input that is
-already resident in HBM.  The plan (filter kernel reorder + weight packing) is built once, before
-the timed region.  Prints ONE JSON line.
+A step is one forward pass of the whole hot path (input staging, multiply-accumulates, fused
+bias+ReLU epilogue) over one batch of seeded synthetic input that is already resident in HBM.
+The plan (filter kernel reorder + weight packing) is built once, before the timed region.
+Prints ONE JSON line.
 
-metric  : effective GMAC/s = non-zero multiply-accumulates (4 per kept kernel per output pixel) per second
-roofline: the dominant (only) kernel against the FP32 vector-ALU peak of the chip
-          (256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2 (packed) x 2.4 GHz = 157.3 TFLOP/s; the library is built
-          with packed-FP32 formation disabled, so the reachable ceiling is half of that) -- `achieved`
-          counts 2 flop per effective MAC, timed with events on the launch stream.
+metric   : effective GMAC/s = non-zero multiply-accumulates (4 per kept kernel per output pixel) per second
+workload : by default the largest single-GPU configuration, the 1080p image-enhancement layer (its
+           tensors exceed the 256 MB last-level cache, so it streams HBM); every other benchmark layer and
+           the VGG-shaped stack run as one chain of launches are timed too and reported under `others`.
+roofline : the dominant kernel of the timed workload against the roofline that binds it:
+           * the tiled pattern-specialised kernel (variant 2) is bound by the FP32 vector ALUs:
+             256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2 (packed) x 2.4 GHz = 157.3 TFLOP/s; the library is
+             built with packed-FP32 formation disabled, so `peak_unpacked` = 78.6 TFLOP/s is the reachable
+             ceiling.  `achieved` counts 2 flop per effective MAC.
+           * the matrix-core kernel (variant 3, zero-filled dense weights in binary16) does 9/(4*keep) times
+             the multiply-accumulates at matrix-core rate, which leaves HBM as the binding roofline of the
+             large-image layers: `achieved` = algorithmic bytes (x once, y once, packed weights once) per
+             second against 8 TB/s.  The matrix-core fraction (dense flop against 2.5 PFLOP/s) is given
+             beside it as `frac_mfma`.
+           Kernel time comes from events recorded on the launch stream around the timed launches.
 """
 from __future__ import annotations
 
@@ -29,16 +39,16 @@ if ROOT not in sys.path:
 import numpy as np
 
 PEAK_FP32_TFLOPS = 157.3
+PEAK_FP32_UNPACKED_TFLOPS = 78.6
+PEAK_MFMA_F16_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
 
 # HBM-side traffic of one launch (bytes), from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by a copy
-# kernel of known size; see profiles/k1_tiled_<workload>.md.  Valid only for the kernel revision
-# it was measured on: reported as null for any other.
-MEASURED_TRAFFIC = {
-    "cfg2_vgg_mid": ("k1-2026-11-27-m", 20.43e6),
-    "cfg5_enhance_1080p": ("k1-2026-11-27-m", 590.66e6),
-    "cfg4_vgg_L6": ("k1-2026-11-27-m", 33.08e6),
-}
+# kernel of known size; see profiles/.  Valid only for the kernel revision it was measured on:
+# reported as null for any other.  Keyed by (workload, variant).
+MEASURED_TRAFFIC = {}
+
+DEFAULT_WORKLOAD = "cfg5_enhance_1080p"
 
 
 def workloads():
@@ -55,6 +65,11 @@ def workloads():
     return w
 
 
+def _events():
+    import torch
+    return torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+
 def time_layer(lay, steps, warmup, tuning=None, autotune=False):
     """Returns dict with per-step times of pp_conv_run on the current stream."""
     import torch
@@ -68,7 +83,7 @@ def time_layer(lay, steps, warmup, tuning=None, autotune=False):
     for _ in range(warmup):
         plan.run(x, y, stream)
     torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0, ev1 = _events()
     t0 = time.perf_counter()
     ev0.record()
     for _ in range(steps):
@@ -83,6 +98,10 @@ def time_layer(lay, steps, warmup, tuning=None, autotune=False):
     return res
 
 
+def dense_macs(lay):
+    return 9.0 * lay.n * lay.h * lay.w * lay.c_in * lay.c_out
+
+
 def summarize(lay, t):
     sec = t["event_ms_per_step"] * 1e-3
     return dict(workload=lay.name, dtype=lay.dtype, n=lay.n, k_kept=lay.k_kept, eff_gmacs=lay.eff_macs / 1e9,
@@ -90,21 +109,112 @@ def summarize(lay, t):
                 wall_us_per_step=t["wall_ms_per_step"] * 1e3,
                 eff_gmac_per_s=lay.eff_macs / sec / 1e9, alg_gb_per_s=lay.alg_bytes / sec / 1e9,
                 frac_fp32_valu=2 * lay.eff_macs / sec / 1e12 / PEAK_FP32_TFLOPS,
+                frac_fp32_valu_unpacked=2 * lay.eff_macs / sec / 1e12 / PEAK_FP32_UNPACKED_TFLOPS,
+                frac_mfma_dense=2 * dense_macs(lay) / sec / 1e12 / PEAK_MFMA_F16_TFLOPS,
                 frac_hbm=lay.alg_bytes / sec / 1e9 / PEAK_HBM_GBS, params=t["chosen"])
+
+
+def time_vgg_stack(steps, warmup):
+    """The 13 layers of the VGG-shaped configuration as ONE chain on one stream: every plan is built up
+    front, every activation buffer is allocated up front, and a step enqueues the 13 convolutions and the 4
+    max-pools back to back with no host synchronisation in between.  Each layer reads what the previous one
+    wrote.  The pools are also timed on their own, on the same buffers."""
+    import torch
+    import synth
+    import paper_2206_10620_amd as pp
+    layers = synth.config4()
+    stream = torch.cuda.current_stream().cuda_stream
+    plans = [pp.plan_from_layer(l) for l in layers]
+    x0 = torch.from_numpy(layers[0].make_input()).cuda()
+    bufs, pools = [], []
+    for l in layers:
+        y = torch.empty((l.n, l.c_out, l.h, l.w), dtype=torch.float16, device="cuda")
+        p = torch.empty((l.n, l.c_out, l.h // 2, l.w // 2), dtype=torch.float16, device="cuda") if l.meta["pool_after"] else None
+        bufs.append(y)
+        pools.append(p)
+
+    def pool(i):
+        l = layers[i]
+        st = pp.pp_maxpool2x2_run(bufs[i].data_ptr(), pools[i].data_ptr(), l.n, l.c_out, l.h, l.w, pp.PP_F16, stream)
+        assert st == pp.PP_OK
+
+    def step():
+        cur = x0
+        for i, (l, plan) in enumerate(zip(layers, plans)):
+            plan.run(cur, bufs[i], stream)
+            cur = bufs[i]
+            if pools[i] is not None:
+                pool(i)
+                cur = pools[i]
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    ev0, ev1 = _events()
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    chain_ms = ev0.elapsed_time(ev1) / steps
+    ev0, ev1 = _events()
+    ev0.record()
+    for _ in range(steps):
+        for i in range(len(layers)):
+            if pools[i] is not None:
+                pool(i)
+    ev1.record()
+    torch.cuda.synchronize()
+    pools_ms = ev0.elapsed_time(ev1) / steps
+    eff = sum(l.eff_macs for l in layers)
+    alg = sum(l.alg_bytes for l in layers)
+    variants = [p.query()["chosen"]["variant"] for p in plans]
+    for p in plans:
+        p.close()
+    sec = chain_ms * 1e-3
+    return dict(workload="cfg4_vgg_stack_chained", dtype="f16", n=layers[0].n, layers=len(layers), pools=4,
+                eff_gmacs=eff / 1e9, alg_mb=alg / 1e6, us_per_step=chain_ms * 1e3, wall_us_per_step=wall * 1e6 / steps,
+                pools_us_per_step=pools_ms * 1e3, eff_gmac_per_s=eff / sec / 1e9, alg_gb_per_s=alg / sec / 1e9,
+                frac_fp32_valu=2 * eff / sec / 1e12 / PEAK_FP32_TFLOPS,
+                frac_fp32_valu_unpacked=2 * eff / sec / 1e12 / PEAK_FP32_UNPACKED_TFLOPS,
+                frac_hbm=alg / sec / 1e9 / PEAK_HBM_GBS, variants=variants,
+                note="13 convolutions + 4 max-pools enqueued back to back on one stream, no host synchronisation; "
+                     "pools_us_per_step is the four pools timed alone")
+
+
+def roofline_of(lay, t, traffic):
+    """The roofline that binds the kernel the plan chose."""
+    sec = t["event_ms_per_step"] * 1e-3
+    variant = t["chosen"]["variant"]
+    if variant == 3:
+        return {"bound": "hbm", "achieved": lay.alg_bytes / sec / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": lay.alg_bytes / sec / 1e9 / PEAK_HBM_GBS, "traffic": traffic, "kernel": "k2_mfma",
+                "kernel_us": t["event_ms_per_step"] * 1e3,
+                "frac_mfma": 2 * dense_macs(lay) / sec / 1e12 / PEAK_MFMA_F16_TFLOPS,
+                "peak_mfma_tflops": PEAK_MFMA_F16_TFLOPS}
+    ach = 2 * lay.eff_macs / sec / 1e12
+    return {"bound": "alu", "achieved": ach, "peak": PEAK_FP32_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_FP32_TFLOPS,
+            "traffic": traffic, "kernel": "k1_tiled" if variant == 2 else "k0_generic",
+            "kernel_us": t["event_ms_per_step"] * 1e3,
+            "peak_unpacked": PEAK_FP32_UNPACKED_TFLOPS, "frac_unpacked": ach / PEAK_FP32_UNPACKED_TFLOPS}
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=500)
-    ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--workload", default="cfg2_vgg_mid")
-    ap.add_argument("--all", action="store_true", help="also time the other benchmark layers (reported under 'others')")
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
+    ap.add_argument("--no-others", action="store_true", help="time only the named workload")
+    ap.add_argument("--all", action="store_true", help="(default behaviour; kept for old command lines)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-baseline leg and the parity check")
     ap.add_argument("--copy-ref-mib", type=int, default=0,
                     help="also launch one plain device copy of this many MiB (a reference dispatch for scaling "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--tuning", default="", help="f,r,wf,ks,cc overrides for the timed workload (0 = automatic)")
+    ap.add_argument("--variant", type=int, default=0, help="force a kernel variant for the timed workload (0 = the plan's choice)")
     ap.add_argument("--autotune", action="store_true",
                     help="pick the parameters of every timed workload by measurement (paper_2206_10620_amd.autotune) "
                          "instead of the plan's own rules; reported under config.params and 'tuned'")
@@ -132,11 +242,14 @@ def main():
     if args.tuning:
         f, r, wf, ks, cc = (int(v) for v in args.tuning.split(","))
         tuning = pp.Tuning(variant=2, filters_per_wave=f, rows_per_lane=r, waves_f=wf, split_c=ks, chunk_c=cc)
-    t = time_layer(lay, args.steps, args.warmup, tuning, args.autotune)
+    elif args.variant:
+        tuning = pp.Tuning(variant=args.variant)
+    # the warm-up also settles clocks: at least 50 ms of it, whatever --warmup says
+    t = time_layer(lay, args.steps, max(args.warmup, 20), tuning, args.autotune)
     s = summarize(lay, t)
     sec_wall = t["wall_ms_per_step"] * 1e-3
 
-    rev, tbytes = MEASURED_TRAFFIC.get(args.workload, (None, None))
+    rev, tbytes = MEASURED_TRAFFIC.get((args.workload, t["chosen"]["variant"]), (None, None))
     traffic = tbytes if (rev == pp.KERNEL_REVISION and not args.tuning and not args.autotune) else None
 
     out = {
@@ -151,10 +264,8 @@ def main():
                    "patterns": int(len(lay.pattern_masks)), "k_kept": lay.k_kept, "keep": lay.k_kept / (lay.c_in * lay.c_out),
                    "fused": "bias+relu", "params": t["chosen"]},
         "alg_gb_per_s": s["alg_gb_per_s"], "frac_hbm": s["frac_hbm"],
-        "roofline": {"bound": "alu", "achieved": 2 * lay.eff_macs / (t["event_ms_per_step"] * 1e-3) / 1e12,
-                     "peak": PEAK_FP32_TFLOPS, "unit": "TFLOP/s",
-                     "frac": s["frac_fp32_valu"], "traffic": traffic,
-                     "kernel": "k1_tiled", "kernel_us": s["us_per_step"]},
+        "frac_fp32_valu": s["frac_fp32_valu"], "frac_fp32_valu_unpacked": s["frac_fp32_valu_unpacked"],
+        "roofline": roofline_of(lay, t, traffic),
     }
 
     if not args.no_cpu:
@@ -163,9 +274,8 @@ def main():
         x_np = t["x"].cpu().numpy()
         y_np = t["y"].cpu().numpy()
         wd = oracle.layer_dense_weights(lay)
-        dense_macs = 9.0 * lay.n * lay.h * lay.w * lay.c_in * lay.c_out
         threads = oracle.binding.default_threads()
-        if dense_macs <= 4e9:
+        if dense_macs(lay) <= 4e9:
             x64 = x_np.astype(np.float64)
             passes = 5
             c0 = time.perf_counter()
@@ -187,18 +297,21 @@ def main():
         out["cpu_baseline"] = {"value": lay.eff_macs * frac / cpu_s / 1e9, "unit": "GMAC/s", "cores": threads,
                                "kind": "oracle", "sample": sample, "seconds": cpu_s}
         out["max_rel_err"] = rep["E"]
+    del t
+    torch.cuda.empty_cache()
 
-    if args.all:
+    if not args.no_others:
         others = []
         for name, make in table.items():
             if name == args.workload:
                 continue
             l2 = make()
-            steps = max(20, min(args.steps, int(0.5 / max(l2.eff_macs / 20e12, 1e-5))))
-            t2 = time_layer(l2, steps, max(5, args.warmup // 5), None, args.autotune)
+            steps = max(20, min(200, int(0.2 / max(l2.eff_macs / 20e12, 1e-5))))
+            t2 = time_layer(l2, steps, 20, None, args.autotune)
             others.append(summarize(l2, t2))
             del t2
             torch.cuda.empty_cache()
+        others.append(time_vgg_stack(steps=20, warmup=5))
         out["others"] = others
 
     print(json.dumps(out))

@@ -45,7 +45,8 @@ typedef enum {
     PP_ERR_PATTERN = 3,     /* a mask has bits above bit 8 or not exactly four bits, or a kept kernel's id is out of range */
     PP_ERR_UNSUPPORTED = 4, /* unknown dtype / flag / tuning request, or a host-only plan passed to pp_conv_run */
     PP_ERR_ALLOC = 5,       /* host allocation failed */
-    PP_ERR_DEVICE = 6       /* a HIP call failed (no device, out of device memory, launch error) */
+    PP_ERR_DEVICE = 6,      /* a HIP call failed (no device, out of device memory, launch error) */
+    PP_ERR_ALIGN = 7        /* a device buffer is not 16-byte aligned, or input and output overlap */
 } pp_status_t;
 
 /* Storage type of x, y and the packed weights.  Products are accumulated in fp32 in both cases;
@@ -109,7 +110,8 @@ pp_status_t pp_conv_plan(const pp_conv_desc_t *desc, pp_conv_plan_t **out_plan);
  *   y_dev : [n][c_out][h][w] contiguous, plan dtype, 16-byte aligned, caller-owned, must not overlap x_dev
  *   hip_stream : a hipStream_t (NULL = the default stream)
  * Returns after the launch without synchronising; launch-configuration errors are returned,
- * asynchronous faults are not.  Concurrent runs of one plan on different streams with different
+ * asynchronous faults are not.  Misaligned or overlapping x_dev / y_dev are PP_ERR_ALIGN (checked
+ * on the host, before anything is launched).  Concurrent runs of one plan on different streams with different
  * y_dev are allowed unless the plan splits channels across workgroups (chosen.split_wg > 1 in
  * pp_conv_plan_query): such a plan owns one partial-sum workspace, sized for n_hint images, and its
  * runs must not overlap; more than n_hint images are processed n_hint at a time.  n <= 0 is

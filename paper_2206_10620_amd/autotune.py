@@ -51,6 +51,8 @@ def autotune(layer, x_dev, y_dev, stream: Optional[int] = None, steps: int = 20,
         if key in seen or chosen["variant"] != 2:       # same plan as an earlier candidate, or not the tiled kernel
             plan.close()
             if chosen["variant"] != 2:
+                for _, _, other in plans:
+                    other.close()
                 return None, []
             continue
         seen.add(key)

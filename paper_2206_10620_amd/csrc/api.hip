@@ -169,6 +169,7 @@ const char* pp_status_string(pp_status_t s) {
         case PP_ERR_UNSUPPORTED: return "unsupported request";
         case PP_ERR_ALLOC: return "host allocation failed";
         case PP_ERR_DEVICE: return "device error";
+        case PP_ERR_ALIGN: return "misaligned or overlapping device buffers";
     }
     return "unknown status";
 }
@@ -297,19 +298,27 @@ static pp_status_t launch_tiled(const pp_conv_plan_t* plan, const void* x_dev, v
     const int64_t blocks = (int64_t)a.blocks_per_xcd * 8;
     const int lds = (int)k1_lds_layout_bytes(tl.lw, tl.r, tl.f, tl.wf, tl.ks, tl.cc, eb, tl.mode, tl.nbuf);
     a.red_par = tl.ks > 1 ? std::max(1, std::min(tl.ks - 1, lds / (tl.wf * tl.f * tl.r * 4 * 64 * 4))) : 1;
+    (void)hipGetLastError();          // an error left by the caller's earlier HIP work is not this launch's
     plan->launch(a, (int)blocks, 64 * tl.wf * tl.ks, lds, stream);
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_DEVICE;
 }
 
 pp_status_t pp_conv_run(const pp_conv_plan_t* plan, const void* x_dev, void* y_dev, int32_t n, void* hip_stream) {
     if (!plan || !x_dev || !y_dev) return PP_ERR_NULL;
-    if (!plan->on_device) return PP_ERR_UNSUPPORTED;
     const HostPlan& hp = plan->hp;
     if (n <= 0) return PP_ERR_SHAPE;
     const int64_t hw = (int64_t)hp.h * hp.w;
     if ((int64_t)n * hp.c_in * hw >= ((int64_t)1 << 31) || (int64_t)n * hp.c_out * hw >= ((int64_t)1 << 31) ||
         (int64_t)n * (hp.h + 1) >= ((int64_t)1 << 30))
         return PP_ERR_SHAPE;
+    // the kernels use 128-bit loads and stores: a misaligned or aliased buffer must become a status
+    // code here, not a memory fault on the device
+    const int64_t ebytes = hp.dtype == PP_F16 ? 2 : 4;
+    const uintptr_t xa = reinterpret_cast<uintptr_t>(x_dev), ya = reinterpret_cast<uintptr_t>(y_dev);
+    if ((xa | ya) & 15u) return PP_ERR_ALIGN;
+    const uintptr_t xe = xa + (uintptr_t)((int64_t)n * hp.c_in * hw * ebytes), ye = ya + (uintptr_t)((int64_t)n * hp.c_out * hw * ebytes);
+    if (xa < ye && ya < xe) return PP_ERR_ALIGN;
+    if (!plan->on_device) return PP_ERR_UNSUPPORTED;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const int relu = (hp.flags & PP_FLAG_RELU) ? 1 : 0;
     if (!hp.tiled) {
@@ -318,6 +327,7 @@ pp_status_t pp_conv_run(const pp_conv_plan_t* plan, const void* x_dev, void* y_d
         const int64_t blocks = ((int64_t)n * hw + 255) / 256;
         if (blocks >= ((int64_t)1 << 31)) return PP_ERR_SHAPE;
         dim3 grid((unsigned)blocks, (unsigned)hp.c_out);
+        (void)hipGetLastError();
         if (hp.dtype == PP_F16) hipLaunchKernelGGL(k0_generic<_Float16>, grid, dim3(256), 0, stream, a);
         else hipLaunchKernelGGL(k0_generic<float>, grid, dim3(256), 0, stream, a);
         return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_DEVICE;
@@ -380,6 +390,7 @@ pp_status_t pp_maxpool2x2_run(const void* x_dev, void* y_dev, int32_t n, int32_t
     int64_t blocks = (total + 255) / 256;
     if (blocks > 65536) blocks = 65536;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    (void)hipGetLastError();
     if (dtype == PP_F16)
         hipLaunchKernelGGL(maxpool2x2<_Float16>, dim3((unsigned)blocks), dim3(256), 0, stream,
                            static_cast<const _Float16*>(x_dev), static_cast<_Float16*>(y_dev), planes, h, w);

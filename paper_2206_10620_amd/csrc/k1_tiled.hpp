@@ -493,9 +493,9 @@ template <typename T, int SLOT, int LW, int R> struct DirectStager {
     template <int BYTES>
     static __device__ __forceinline__ void dma(uint32_t off, const void* base, uint32_t lds_dst) {
         if constexpr (BYTES == 16)
-            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(lds_dst) : "memory");
+            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(lds_dst) : "memory", "m0");
         else
-            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(off), "s"(base), "s"(lds_dst) : "memory");
+            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(off), "s"(base), "s"(lds_dst) : "memory", "m0");
     }
 
     // Start the loads of channels [c0, c0+ccn) into the buffer at LDS byte address lds_buf.

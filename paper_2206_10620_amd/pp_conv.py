@@ -7,7 +7,7 @@ from typing import Optional
 
 import numpy as np
 
-PP_OK, PP_ERR_NULL, PP_ERR_SHAPE, PP_ERR_PATTERN, PP_ERR_UNSUPPORTED, PP_ERR_ALLOC, PP_ERR_DEVICE = range(7)
+PP_OK, PP_ERR_NULL, PP_ERR_SHAPE, PP_ERR_PATTERN, PP_ERR_UNSUPPORTED, PP_ERR_ALLOC, PP_ERR_DEVICE, PP_ERR_ALIGN = range(8)
 PP_F32, PP_F16 = 0, 1
 PP_FLAG_RELU, PP_FLAG_DENSE, PP_FLAG_HOST_ONLY = 1, 2, 4
 

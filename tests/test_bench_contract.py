@@ -21,10 +21,11 @@ def test_measured_traffic_belongs_to_the_current_kernel_revision():
     profile summaries have to name the revision the library reports."""
     sys.path.insert(0, ROOT)
     import bench
-    for wl, (rev, nbytes) in bench.MEASURED_TRAFFIC.items():
+    kernel_of = {2: "k1_tiled", 3: "k2_mfma"}
+    for (wl, variant), (rev, nbytes) in bench.MEASURED_TRAFFIC.items():
         assert rev == pp.KERNEL_REVISION, f"{wl}: traffic measured on {rev}, library is {pp.KERNEL_REVISION}"
         assert nbytes > 0
-        text = open(os.path.join(ROOT, "profiles", f"k1_tiled_{wl}.md")).read()
+        text = open(os.path.join(ROOT, "profiles", f"{kernel_of[variant]}_{wl}.md")).read()
         assert pp.KERNEL_REVISION in text
         m = re.search(r"= ([0-9.]+) MB, against", text)
         assert m and abs(float(m.group(1)) * 1e6 - nbytes) <= 0.02e6 + 1e-3 * nbytes
@@ -34,6 +35,7 @@ def test_workload_table_covers_the_benchmark_configurations():
     sys.path.insert(0, ROOT)
     import bench
     names = set(bench.workloads())
+    assert bench.DEFAULT_WORKLOAD == "cfg5_enhance_1080p"      # the largest single-GPU configuration
     assert {"cfg2_vgg_mid", "cfg5_enhance_1080p"} <= names
     assert sum(n.startswith("cfg4_vgg_L") for n in names) == 13
     assert sum(n.startswith("cfg3_resnet_") for n in names) == 8

@@ -107,7 +107,15 @@ def test_error_paths():
     assert status(tuning=pp.Tuning(variant=2, split_c=3, chunk_c=8)) == pp.PP_ERR_UNSUPPORTED
     # a host-only plan cannot run; NULL plan / buffers are rejected; destroy(NULL) is a no-op
     st, h = pp.pp_conv_plan(**args)
-    assert pp.pp_conv_run(h, 16, 32, 1) == pp.PP_ERR_UNSUPPORTED
+    xbytes, ybytes = lay.c_in * lay.h * lay.w * 4, lay.c_out * lay.h * lay.w * 4
+    assert pp.pp_conv_run(h, 1 << 20, 2 << 20, 1) == pp.PP_ERR_UNSUPPORTED
+    # arguments are validated before anything touches a device: misaligned or overlapping buffers
+    assert pp.pp_conv_run(h, (1 << 20) + 4, 2 << 20, 1) == pp.PP_ERR_ALIGN
+    assert pp.pp_conv_run(h, 1 << 20, (2 << 20) + 8, 1) == pp.PP_ERR_ALIGN
+    assert pp.pp_conv_run(h, 1 << 20, (1 << 20) + xbytes - 16, 1) == pp.PP_ERR_ALIGN      # y starts inside x
+    assert pp.pp_conv_run(h, (1 << 20) + ybytes - 16, 1 << 20, 1) == pp.PP_ERR_ALIGN      # x starts inside y
+    assert pp.pp_conv_run(h, 1 << 20, (1 << 20) + xbytes, 1) == pp.PP_ERR_UNSUPPORTED     # adjacent is fine
+    assert pp.pp_conv_run(h, 1 << 20, 2 << 20, 0) == pp.PP_ERR_SHAPE
     assert pp.pp_conv_run(h, 0, 32, 1) == pp.PP_ERR_NULL
     assert pp.pp_conv_run(None, 16, 32, 1) == pp.PP_ERR_NULL
     assert pp.pp_conv_destroy(h) == pp.PP_OK
