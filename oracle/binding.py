@@ -43,6 +43,14 @@ def lib() -> C.CDLL:
         L.oracle_widen_f16.restype = None
         L.oracle_plan_ref.argtypes = [i32, i32, i32] + [vp] * 8
         L.oracle_plan_ref.restype = i64
+        L.oracle_expand_weights_k.argtypes = [i32] * 5 + [vp] * 5
+        L.oracle_expand_weights_k.restype = i32
+        L.oracle_conv_k.argtypes = [i32] * 7 + [vp, vp, vp, i32, vp, vp, vp, i32]
+        L.oracle_conv_k.restype = None
+        L.oracle_conv_k_at.argtypes = [i32] * 7 + [vp, vp, i32, i32, vp, i64, vp, vp, vp, vp, i32]
+        L.oracle_conv_k_at.restype = None
+        L.oracle_brute_k.argtypes = [i32] * 8 + [vp] * 6 + [i32, vp]
+        L.oracle_brute_k.restype = None
         _lib = L
     return _lib
 
@@ -166,6 +174,74 @@ def plan_ref(c_in, c_out, num_patterns, pattern_id, conn):
                 wsel=wsel, k_kept=kk)
 
 
+# -- other kernel sizes and strides -------------------------------------------------------
+
+def out_size(size: int, stride: int) -> int:
+    return (size - 1) // stride + 1
+
+
+def expand_weights_k(c_in, c_out, ksize, masks, pattern_id, conn, weights, taps) -> np.ndarray:
+    """Masked dense weights Wd [c_out, c_in, K, K] (float64) from (K*K)-bit masks."""
+    masks = _c(masks, np.uint64)
+    pid = _c(pattern_id, np.int32)
+    cm = _c(conn, np.uint8)
+    w = _c(weights, np.float64).reshape(-1)
+    wd = np.empty((c_out, c_in, ksize, ksize), dtype=np.float64)
+    rc = lib().oracle_expand_weights_k(c_in, c_out, ksize, taps, len(masks), _p(masks), _p(pid), _p(cm), _p(w), _p(wd))
+    if rc != 0:
+        raise ValueError(f"invalid pruned-layer description (code {rc})")
+    return wd
+
+
+def conv_k(x, wd, stride=1, bias=None, relu=False, want_pre=False, want_scale=False, threads=None):
+    """Full-tensor reference result for K x K kernels (K = wd.shape[-1]), padding (K-1)/2, the given stride."""
+    x = _c(x, np.float64)
+    wd = _c(wd, np.float64)
+    n, c_in, h, w = x.shape
+    c_out, _, ksize, _ = wd.shape
+    assert wd.shape == (c_out, c_in, ksize, ksize)
+    b = None if bias is None else _c(bias, np.float64)
+    y = np.empty((n, c_out, out_size(h, stride), out_size(w, stride)), dtype=np.float64)
+    pre = np.empty_like(y) if want_pre else None
+    sc = np.empty_like(y) if want_scale else None
+    lib().oracle_conv_k(n, c_in, c_out, h, w, ksize, stride, _p(x), _p(wd), _p(b), int(relu), _p(y), _p(pre), _p(sc),
+                        threads or default_threads())
+    if want_pre or want_scale:
+        return y, pre, sc
+    return y
+
+
+def conv_k_at(x, wd, pts, stride=1, bias=None, relu=False, threads=None):
+    """Reference result at sampled outputs of the convolution's own output grid.  Returns (y, pre, scale)."""
+    assert x.dtype in (np.float32, np.float16) and x.flags.c_contiguous
+    wd = _c(wd, np.float64)
+    n, c_in, h, w = x.shape
+    c_out, _, ksize, _ = wd.shape
+    pts = _c(pts, np.int32)
+    npts = pts.shape[0]
+    b = None if bias is None else _c(bias, np.float64)
+    y = np.empty(npts, dtype=np.float64)
+    pre = np.empty(npts, dtype=np.float64)
+    sc = np.empty(npts, dtype=np.float64)
+    lib().oracle_conv_k_at(n, c_in, c_out, h, w, ksize, stride, _p(wd), _p(b), int(relu), int(x.dtype == np.float16),
+                           _p(x), npts, _p(pts), _p(y), _p(pre), _p(sc), threads or default_threads())
+    return y, pre, sc
+
+
+def brute_k(x, ksize, stride, taps, masks, pattern_id, conn, weights, c_out, bias=None, relu=False):
+    x = _c(x, np.float64)
+    n, c_in, h, w = x.shape
+    masks = _c(masks, np.uint64)
+    pid = _c(pattern_id, np.int32)
+    cm = _c(conn, np.uint8)
+    wt = _c(weights, np.float64).reshape(-1)
+    b = None if bias is None else _c(bias, np.float64)
+    y = np.empty((n, c_out, out_size(h, stride), out_size(w, stride)), dtype=np.float64)
+    lib().oracle_brute_k(n, c_in, c_out, h, w, ksize, stride, taps, _p(masks), _p(pid), _p(cm), _p(wt), _p(x), _p(b),
+                         int(relu), _p(y))
+    return y
+
+
 # -- conveniences over a synthetic layer description (duck-typed: any object with the
 #    fields of synth.Layer) ---------------------------------------------------------
 
@@ -174,13 +250,27 @@ def layer_dense_weights(layer) -> np.ndarray:
     w = np.asarray(layer.weights, dtype=np.float64)
     if layer.dtype == "f16":
         w = widen_f16(round_f16(w))
+    ksize = getattr(layer, "ksize", 3)
+    if ksize != 3:
+        return expand_weights_k(layer.c_in, layer.c_out, ksize, layer.pattern_masks, layer.pattern_id, layer.conn_mask,
+                                w, taps=layer.taps)
     return expand_weights(layer.c_in, layer.c_out, layer.pattern_masks, layer.pattern_id, layer.conn_mask, w,
                           taps=9 if layer.dense else 4)
 
 
 def layer_reference(layer, x, relu=None, threads=None):
-    """(y, pre, scale) of the whole layer on input x (already in the storage dtype)."""
+    """(y, pre, scale) of the whole layer on input x (already in the storage dtype).  For a layer with
+    a fused 2x2 max-pool y and scale are pooled; pre stays the convolution's own (it only sets the
+    error measure's floor)."""
     wd = layer_dense_weights(layer)
     relu = layer.relu if relu is None else relu
-    return conv(np.asarray(x, dtype=np.float64), wd, layer.bias, relu, want_pre=True, want_scale=True,
-                threads=threads)
+    stride, pool = getattr(layer, "stride", 1), getattr(layer, "pool", False)
+    if wd.shape[-1] == 3 and stride == 1:
+        y, pre, sc = conv(np.asarray(x, dtype=np.float64), wd, layer.bias, relu, want_pre=True, want_scale=True,
+                          threads=threads)
+    else:
+        y, pre, sc = conv_k(np.asarray(x, dtype=np.float64), wd, stride, layer.bias, relu, want_pre=True,
+                            want_scale=True, threads=threads)
+    if pool:
+        y, sc = maxpool2(y), maxpool2(sc)
+    return y, pre, sc

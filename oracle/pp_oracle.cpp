@@ -321,4 +321,157 @@ int64_t oracle_plan_ref(int c_in, int c_out, int num_patterns, const int32_t* pa
     return out;
 }
 
+// ---------------------------------------------------------------------------
+// Other kernel sizes, strides, and a fused pooling consumer.
+//
+// Section 2.1.1 ends by saying that pattern-based pruning applies where the
+// kernel size is one of 3x3, 5x5, 7x7 and that the scheme carries over to other
+// kernel sizes; connectivity pruning alone on a 1x1 layer is the K = 1 case (one
+// tap, one pattern).  ResNet-shaped blocks (section 3 evaluates ResNet-50) also
+// need stride 2.  The paper prints no formula for these either; the reading is
+// the CONV layer of the frameworks it names:
+//
+//   K odd, P = (K-1)/2 zero padding, stride S,
+//   H_out = floor((H - 1) / S) + 1,  W_out likewise,
+//   Wd[co][ci][r][c] = the kernel's j-th weight if the kernel is kept and tap
+//                      t = K*r + c is the j-th set bit of its pattern's mask (bit t
+//                      of a 64-bit word), else 0,
+//   pre[n][co][oy][ox] = bias[co] + sum_ci sum_r sum_c Wd[co][ci][r][c] * X(n, ci, S*oy + r - P, S*ox + c - P).
+//
+// Operator fusion (section 2.2, the mapping-type analysis of Table 1) folds a
+// consumer into its producer; the 2x2 max-pool that follows a CONV layer in a
+// VGG-shaped stack is evaluated by applying oracle_maxpool2 to the activated
+// result: no new arithmetic, two definitions composed.
+//
+// Pins (tests/test_oracle_pins_general.py): K = 3, S = 1 equals oracle_conv; S = 2
+// equals every second output of the S = 1 result; a float64 library convolution
+// with stride and padding; K = 1 is a matrix product; a brute-force gather written
+// against the mask bits; a hand-worked stride-2 example.
+
+// Masked dense weights Wd[c_out][c_in][K][K] from a table of (K*K)-bit masks with
+// `taps` bits set each.  Returns 0, or a negative code for an invalid description.
+int oracle_expand_weights_k(int c_in, int c_out, int ksize, int taps, int num_patterns, const uint64_t* masks,
+                            const int32_t* pattern_id, const uint8_t* conn, const double* w, double* Wd) {
+    const int kk = ksize * ksize;
+    if (ksize < 1 || ksize > 7 || !(ksize & 1) || taps < 1 || taps > kk) return -1;
+    for (int p = 0; p < num_patterns; ++p) {
+        int bits = 0;
+        for (int t = 0; t < 64; ++t) {
+            if (!((masks[p] >> t) & 1u)) continue;
+            if (t >= kk) return -2;
+            ++bits;
+        }
+        if (bits != taps) return -2;
+    }
+    for (int64_t k = 0; k < (int64_t)c_in * c_out; ++k) {
+        double* d = Wd + k * kk;
+        for (int t = 0; t < kk; ++t) d[t] = 0.0;
+        if (!conn[k]) continue;
+        int p = pattern_id[k];
+        if (p < 0 || p >= num_patterns) return -3;
+        int j = 0;
+        for (int t = 0; t < kk; ++t)
+            if ((masks[p] >> t) & 1u) d[t] = w[k * taps + j++];
+    }
+    return 0;
+}
+
+// The definition above as seven nested loops.  y, pre, scale are [n][c_out][H_out][W_out].
+void oracle_conv_k(int n, int c_in, int c_out, int h, int w, int ksize, int stride, const double* x, const double* Wd,
+                   const double* bias, int relu, double* y, double* pre, double* scale, int threads) {
+    const int pad = (ksize - 1) / 2;
+    const int ho = (h - 1) / stride + 1, wo = (w - 1) / stride + 1;
+    parallel_for((int64_t)n * c_out, threads, [=](int64_t job) {
+        int img = (int)(job / c_out), co = (int)(job % c_out);
+        for (int oy = 0; oy < ho; ++oy)
+            for (int ox = 0; ox < wo; ++ox) {
+                double acc = bias ? bias[co] : 0.0;
+                double mag = bias ? std::fabs(bias[co]) : 0.0;
+                for (int ci = 0; ci < c_in; ++ci)
+                    for (int r = 0; r < ksize; ++r)
+                        for (int c = 0; c < ksize; ++c) {
+                            int iy = stride * oy + r - pad, ix = stride * ox + c - pad;
+                            if (iy < 0 || iy >= h || ix < 0 || ix >= w) continue;
+                            double wt = Wd[(((int64_t)co * c_in + ci) * ksize + r) * ksize + c];
+                            double xv = x[(((int64_t)img * c_in + ci) * h + iy) * w + ix];
+                            acc += wt * xv;
+                            mag += std::fabs(wt) * std::fabs(xv);
+                        }
+                int64_t o = (((int64_t)img * c_out + co) * ho + oy) * wo + ox;
+                if (pre) pre[o] = acc;
+                if (scale) scale[o] = mag;
+                y[o] = (relu && acc < 0.0) ? 0.0 : acc;
+            }
+    });
+}
+
+// The same at chosen outputs: pts holds npts quadruples (n, co, oy, ox) of the
+// convolution's own output grid (before any pooling).
+void oracle_conv_k_at(int n, int c_in, int c_out, int h, int w, int ksize, int stride, const double* Wd,
+                      const double* bias, int relu, int x_is_f16, const void* x, int64_t npts, const int32_t* pts,
+                      double* y, double* pre, double* scale, int threads) {
+    (void)n;
+    (void)c_out;
+    const int pad = (ksize - 1) / 2;
+    const float* xf = (const float*)x;
+    const uint16_t* xh = (const uint16_t*)x;
+    parallel_for(npts, threads, [=](int64_t i) {
+        int img = pts[4 * i], co = pts[4 * i + 1], oy = pts[4 * i + 2], ox = pts[4 * i + 3];
+        double acc = bias ? bias[co] : 0.0;
+        double mag = bias ? std::fabs(bias[co]) : 0.0;
+        for (int ci = 0; ci < c_in; ++ci)
+            for (int r = 0; r < ksize; ++r)
+                for (int c = 0; c < ksize; ++c) {
+                    int iy = stride * oy + r - pad, ix = stride * ox + c - pad;
+                    if (iy < 0 || iy >= h || ix < 0 || ix >= w) continue;
+                    int64_t xi = (((int64_t)img * c_in + ci) * h + iy) * w + ix;
+                    double xv = x_is_f16 ? oracle_f16_bits_to_f64(xh[xi]) : (double)xf[xi];
+                    double wt = Wd[(((int64_t)co * c_in + ci) * ksize + r) * ksize + c];
+                    acc += wt * xv;
+                    mag += std::fabs(wt) * std::fabs(xv);
+                }
+        if (pre) pre[i] = acc;
+        if (scale) scale[i] = mag;
+        y[i] = (relu && acc < 0.0) ? 0.0 : acc;
+    });
+}
+
+// Brute-force pin for oracle_conv_k on tiny shapes, written against the pruned
+// description (mask bits, j-th stored weight) and the stride, not against Wd.
+void oracle_brute_k(int n, int c_in, int c_out, int h, int w, int ksize, int stride, int taps, const uint64_t* masks,
+                    const int32_t* pattern_id, const uint8_t* conn, const double* wts, const double* x,
+                    const double* bias, int relu, double* y) {
+    const int half = ksize / 2;
+    const int ho = (h + stride - 1) / stride, wo = (w + stride - 1) / stride;      // ceil(h / stride): the same count
+    std::vector<double> ws, xs;
+    for (int img = 0; img < n; ++img)
+        for (int co = 0; co < c_out; ++co)
+            for (int oy = 0; oy < ho; ++oy)
+                for (int ox = 0; ox < wo; ++ox) {
+                    ws.clear();
+                    xs.clear();
+                    const int cy = oy * stride, cx = ox * stride;                 // input pixel under the window's centre
+                    for (int ci = 0; ci < c_in; ++ci) {
+                        int64_t k = (int64_t)co * c_in + ci;
+                        if (!conn[k]) continue;
+                        uint64_t m = masks[pattern_id[k]];
+                        int j = 0;
+                        for (int t = 0; t < ksize * ksize; ++t) {
+                            if (!((m >> t) & 1u)) continue;
+                            double wt = wts[k * taps + j];
+                            ++j;
+                            int dy = t / ksize - half, dx = t % ksize - half;
+                            int iy = cy + dy, ix = cx + dx;
+                            if (iy < 0 || iy >= h || ix < 0 || ix >= w) continue;
+                            ws.push_back(wt);
+                            xs.push_back(x[(((int64_t)img * c_in + ci) * h + iy) * w + ix]);
+                        }
+                    }
+                    long double s = bias ? (long double)bias[co] : 0.0L;
+                    for (size_t i = 0; i < ws.size(); ++i) s += (long double)ws[i] * (long double)xs[i];
+                    double v = (double)s;
+                    y[(((int64_t)img * c_out + co) * ho + oy) * wo + ox] = (relu && v < 0.0) ? 0.0 : v;
+                }
+}
+
 }  // extern "C"

@@ -48,26 +48,46 @@ class Layer:
     seed: int = 0
     x_dist: str = "u11"             # "u11" U[-1,1], "u01" U[0,1], "relu_n" max(0, N(0,1))
     meta: dict = field(default_factory=dict)
+    ksize: int = 3                  # kernel is ksize x ksize (1, 3, 5 or 7), zero padding (ksize-1)/2
+    stride: int = 1                 # 1 or 2
+    pool: bool = False              # a 2x2 max-pool (stride 2) follows the activation
 
     @property
     def taps(self) -> int:
-        return 9 if self.dense else 4
+        """Weights stored per kept kernel."""
+        return int(self.weights.shape[1])
 
     @property
     def k_kept(self) -> int:
         return int(np.count_nonzero(self.conn_mask))
 
     @property
+    def conv_h(self) -> int:
+        return (self.h - 1) // self.stride + 1
+
+    @property
+    def conv_w(self) -> int:
+        return (self.w - 1) // self.stride + 1
+
+    @property
+    def out_h(self) -> int:
+        return self.conv_h // 2 if self.pool else self.conv_h
+
+    @property
+    def out_w(self) -> int:
+        return self.conv_w // 2 if self.pool else self.conv_w
+
+    @property
     def eff_macs(self) -> int:
         """Nonzero multiply-accumulates of one forward pass."""
-        return self.n * self.h * self.w * self.k_kept * self.taps
+        return self.n * self.conv_h * self.conv_w * self.k_kept * self.taps
 
     @property
     def alg_bytes(self) -> int:
         """Read x once, write y once, read the packed weights (+4 index bytes
         per kept kernel) and the bias once."""
         b = 4 if self.dtype == "f32" else 2
-        return (self.n * self.h * self.w * (self.c_in + self.c_out) * b
+        return (self.n * (self.h * self.w * self.c_in + self.out_h * self.out_w * self.c_out) * b
                 + self.k_kept * (self.taps * b + 4) + 4 * self.c_out)
 
     def make_input(self, n: Optional[int] = None) -> np.ndarray:
@@ -106,6 +126,43 @@ def random_pruned_layer(name, n, c_in, c_out, h, w, dtype, pset, keep, w_std, se
     bias = (rng.normal01(seed, rng.STREAM_BIAS, 0, c_out) * bias_std).astype(np.float32) if with_bias else None
     return Layer(name, n, c_in, c_out, h, w, dtype, np.asarray(pset, dtype=np.uint16), pid, conn, wts, bias,
                  relu=relu, seed=seed, x_dist=x_dist, meta={"keep": keep, "w_std": w_std})
+
+
+def random_pattern_set(ksize: int, taps: int, count: int, seed: int) -> np.ndarray:
+    """`count` distinct (ksize*ksize)-bit masks with `taps` bits each, all holding the centre tap;
+    uint64, ascending.  (The paper prints no pattern set for any kernel size.)"""
+    kk = ksize * ksize
+    centre = kk // 2
+    others = [t for t in range(kk) if t != centre]
+    found, i = set(), 0
+    while len(found) < count:
+        pick = rng.choose_k(seed + 7919 * i, rng.STREAM_PATTERN, len(others), taps - 1) if taps > 1 else []
+        m = 1 << centre
+        for j in pick:
+            m |= 1 << others[int(j)]
+        found.add(m)
+        i += 1
+        if i > 100000:
+            raise ValueError("not that many patterns exist")
+    return np.array(sorted(found), dtype=np.uint64)
+
+
+def random_pruned_layer_k(name, n, c_in, c_out, h, w, dtype, ksize, pset, keep, w_std, seed, stride=1, pool=False,
+                          x_dist="u11", relu=True, bias_std=0.01, with_bias=True) -> Layer:
+    """As random_pruned_layer for a ksize x ksize kernel, a stride and an optional fused 2x2 max-pool.
+    pset: masks of ksize*ksize bits with the same number of bits each (uint64 for ksize > 3)."""
+    pset = np.asarray(pset)
+    taps = bin(int(pset[0])).count("1")
+    k_total = c_in * c_out
+    pid = (rng.bits64(seed, rng.STREAM_PATTERN, 0, k_total) % np.uint64(len(pset))).astype(np.int32)
+    kept = rng.choose_k(seed, rng.STREAM_CONN, k_total, _round_half_even(keep * k_total))
+    conn = np.zeros(k_total, dtype=np.uint8)
+    conn[kept] = 1
+    wts = (rng.normal01(seed, rng.STREAM_WEIGHT, 0, k_total * taps) * w_std).astype(np.float32).reshape(k_total, taps)
+    bias = (rng.normal01(seed, rng.STREAM_BIAS, 0, c_out) * bias_std).astype(np.float32) if with_bias else None
+    masks = pset.astype(np.uint16 if ksize <= 3 else np.uint64)
+    return Layer(name, n, c_in, c_out, h, w, dtype, masks, pid, conn, wts, bias, relu=relu, seed=seed, x_dist=x_dist,
+                 meta={"keep": keep, "w_std": w_std}, ksize=ksize, stride=stride, pool=pool)
 
 
 def dense_layer(name, n, c_in, c_out, h, w, dtype, w_std, seed, x_dist="u11", relu=True, bias_std=0.01) -> Layer:
