@@ -46,7 +46,8 @@ typedef enum {
     PP_ERR_UNSUPPORTED = 4, /* unknown dtype / flag / tuning request, or a host-only plan passed to pp_conv_run */
     PP_ERR_ALLOC = 5,       /* host allocation failed */
     PP_ERR_DEVICE = 6,      /* a HIP call failed (no device, out of device memory, launch error) */
-    PP_ERR_ALIGN = 7        /* a device buffer is not 16-byte aligned, or input and output overlap */
+    PP_ERR_ALIGN = 7,       /* a device buffer is not 16-byte aligned, or input and output overlap */
+    PP_ERR_SCRATCH = 8      /* pp_conv_run_static: the call needs more scratch memory than the library's static buffer */
 } pp_status_t;
 
 /* Storage type of x, y and the packed weights.  Products are accumulated in fp32 in both cases;
@@ -117,6 +118,19 @@ pp_status_t pp_conv_plan(const pp_conv_desc_t *desc, pp_conv_plan_t **out_plan);
  * runs must not overlap; more than n_hint images are processed n_hint at a time.  n <= 0 is
  * PP_ERR_SHAPE. */
 pp_status_t pp_conv_run(const pp_conv_plan_t *plan, const void *x_dev, void *y_dev, int32_t n, void *hip_stream);
+
+/* pp_conv_run for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same result.  It calls no
+ * allocator and no allocating library routine; what pp_conv_run takes from a plan-owned workspace
+ * (the partial sums and arrival counters of a plan with chosen.split_wg > 1) lives in one static
+ * device array of 32 MiB instead -- 64 KiB of counters, the rest partial sums -- which every GPU
+ * the library runs on holds until the process ends.  The whole batch goes in one launch, so
+ * split_wg * n * c_out * h * w * 4 bytes must fit: otherwise PP_ERR_SCRATCH (likewise beyond 16384
+ * output tiles) and nothing is launched.  Plans that need no scratch run exactly as in pp_conv_run.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU race, whatever
+ * their plans and streams.  The counters are cleared on the stream by a small kernel before the
+ * launch (no memset node), so the call may be recorded into a HIP graph. */
+pp_status_t pp_conv_run_static(const pp_conv_plan_t *plan, const void *x_dev, void *y_dev, int32_t n, void *hip_stream);
 
 /* Free the plan's host and device memory.  NULL is a no-op returning PP_OK.  The caller must
  * make sure no pp_conv_run of this plan is still executing. */

@@ -104,9 +104,43 @@ __global__ __launch_bounds__(256) void maxpool2x2(const T* __restrict__ x, T* __
     }
 }
 
+__global__ __launch_bounds__(256) void fill_zero_i32(int32_t* p, int count) {
+    const int i = (int)(blockIdx.x * 256 + threadIdx.x);
+    if (i < count) p[i] = 0;
+}
+
 }  // namespace ppc
 
 using namespace ppc;
+
+// Device memory for pp_conv_run_static, the entry point that allocates nothing: the arrival counters
+// (first kScratchCounterBytes) and the partial sums of a plan that splits channels across workgroups.
+// Every GPU the library runs on holds its own copy at its own address until the process ends; in
+// host code the array's name is only a handle for hipGetSymbolAddress, never a device address.
+constexpr size_t kScratchBytes = (size_t)32 << 20;
+constexpr size_t kScratchCounterBytes = (size_t)64 << 10;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// The address of `scratch` on the current device, looked up once per device.
+hipError_t scratch_address(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+}  // namespace
 
 struct pp_conv_plan {
     HostPlan hp;
@@ -170,6 +204,7 @@ const char* pp_status_string(pp_status_t s) {
         case PP_ERR_ALLOC: return "host allocation failed";
         case PP_ERR_DEVICE: return "device error";
         case PP_ERR_ALIGN: return "misaligned or overlapping device buffers";
+        case PP_ERR_SCRATCH: return "request exceeds the static scratch buffer";
     }
     return "unknown status";
 }
@@ -244,13 +279,18 @@ pp_status_t pp_conv_plan(const pp_conv_desc_t* desc, pp_conv_plan_t** out_plan) 
         (void)hipGetLastError();
         return PP_ERR_DEVICE;
     }
+    {   // set-up is the place to look up this device's copy of the static scratch array
+        void* unused = nullptr;
+        if (scratch_address(&unused) != hipSuccess) (void)hipGetLastError();
+    }
     p->on_device = true;
     *out_plan = p;
     return PP_OK;
 }
 
 // One launch of the tiled kernel on n images.
-static pp_status_t launch_tiled(const pp_conv_plan_t* plan, const void* x_dev, void* y_dev, int32_t n, hipStream_t stream) {
+static pp_status_t launch_tiled(const pp_conv_plan_t* plan, const void* x_dev, void* y_dev, int32_t n, hipStream_t stream,
+                                float* ws, int32_t* counters) {
     const HostPlan& hp = plan->hp;
     const int relu = (hp.flags & PP_FLAG_RELU) ? 1 : 0;
     const TiledLayout& tl = hp.tl;
@@ -290,8 +330,8 @@ static pp_status_t launch_tiled(const pp_conv_plan_t* plan, const void* x_dev, v
     if (items >= ((int64_t)1 << 30)) return PP_ERR_SHAPE;
     a.split_wg = tl.sw;
     a.out_elems = (int32_t)((int64_t)n * hp.c_out * hp.h * hp.w);
-    a.ws = plan->d_ws;
-    a.counters = plan->d_counters;
+    a.ws = ws;
+    a.counters = counters;
     a.nfb = nfb;
     a.work_items = (int)items;
     a.blocks_per_xcd = (int)((items + 7) / 8);
@@ -303,7 +343,8 @@ static pp_status_t launch_tiled(const pp_conv_plan_t* plan, const void* x_dev, v
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_DEVICE;
 }
 
-pp_status_t pp_conv_run(const pp_conv_plan_t* plan, const void* x_dev, void* y_dev, int32_t n, void* hip_stream) {
+// Argument checks shared by the run entry points; nothing here touches a device.
+static pp_status_t check_run_args(const pp_conv_plan_t* plan, const void* x_dev, const void* y_dev, int32_t n) {
     if (!plan || !x_dev || !y_dev) return PP_ERR_NULL;
     const HostPlan& hp = plan->hp;
     if (n <= 0) return PP_ERR_SHAPE;
@@ -319,19 +360,31 @@ pp_status_t pp_conv_run(const pp_conv_plan_t* plan, const void* x_dev, void* y_d
     const uintptr_t xe = xa + (uintptr_t)((int64_t)n * hp.c_in * hw * ebytes), ye = ya + (uintptr_t)((int64_t)n * hp.c_out * hw * ebytes);
     if (xa < ye && ya < xe) return PP_ERR_ALIGN;
     if (!plan->on_device) return PP_ERR_UNSUPPORTED;
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    return PP_OK;
+}
+
+static pp_status_t launch_generic(const pp_conv_plan_t* plan, const void* x_dev, void* y_dev, int32_t n, hipStream_t stream) {
+    const HostPlan& hp = plan->hp;
+    const int64_t hw = (int64_t)hp.h * hp.w;
     const int relu = (hp.flags & PP_FLAG_RELU) ? 1 : 0;
-    if (!hp.tiled) {
-        K0Args a{x_dev, y_dev, plan->d_filt_off, plan->d_kidx, plan->d_kpat, plan->d_w, plan->d_tap, plan->d_perm,
-                 plan->d_bias, n, hp.c_in, hp.c_out, hp.h, hp.w, hp.taps, relu};
-        const int64_t blocks = ((int64_t)n * hw + 255) / 256;
-        if (blocks >= ((int64_t)1 << 31)) return PP_ERR_SHAPE;
-        dim3 grid((unsigned)blocks, (unsigned)hp.c_out);
-        (void)hipGetLastError();
-        if (hp.dtype == PP_F16) hipLaunchKernelGGL(k0_generic<_Float16>, grid, dim3(256), 0, stream, a);
-        else hipLaunchKernelGGL(k0_generic<float>, grid, dim3(256), 0, stream, a);
-        return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_DEVICE;
-    }
+    K0Args a{x_dev, y_dev, plan->d_filt_off, plan->d_kidx, plan->d_kpat, plan->d_w, plan->d_tap, plan->d_perm,
+             plan->d_bias, n, hp.c_in, hp.c_out, hp.h, hp.w, hp.taps, relu};
+    const int64_t blocks = ((int64_t)n * hw + 255) / 256;
+    if (blocks >= ((int64_t)1 << 31)) return PP_ERR_SHAPE;
+    dim3 grid((unsigned)blocks, (unsigned)hp.c_out);
+    (void)hipGetLastError();
+    if (hp.dtype == PP_F16) hipLaunchKernelGGL(k0_generic<_Float16>, grid, dim3(256), 0, stream, a);
+    else hipLaunchKernelGGL(k0_generic<float>, grid, dim3(256), 0, stream, a);
+    return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_DEVICE;
+}
+
+pp_status_t pp_conv_run(const pp_conv_plan_t* plan, const void* x_dev, void* y_dev, int32_t n, void* hip_stream) {
+    const pp_status_t chk = check_run_args(plan, x_dev, y_dev, n);
+    if (chk != PP_OK) return chk;
+    const HostPlan& hp = plan->hp;
+    const int64_t hw = (int64_t)hp.h * hp.w;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (!hp.tiled) return launch_generic(plan, x_dev, y_dev, n, stream);
     // A plan that splits channels across workgroups owns a workspace for n_hint images: larger
     // batches go through it n_hint images at a time.
     const TiledLayout& tl = hp.tl;
@@ -340,10 +393,42 @@ pp_status_t pp_conv_run(const pp_conv_plan_t* plan, const void* x_dev, void* y_d
     for (int n0 = 0; n0 < n; n0 += step) {
         const int nb = std::min(step, n - n0);
         const pp_status_t st = launch_tiled(plan, static_cast<const char*>(x_dev) + (int64_t)n0 * hp.c_in * hw * eb,
-                                            static_cast<char*>(y_dev) + (int64_t)n0 * hp.c_out * hw * eb, nb, stream);
+                                            static_cast<char*>(y_dev) + (int64_t)n0 * hp.c_out * hw * eb, nb, stream,
+                                            plan->d_ws, plan->d_counters);
         if (st != PP_OK) return st;
     }
     return PP_OK;
+}
+
+pp_status_t pp_conv_run_static(const pp_conv_plan_t* plan, const void* x_dev, void* y_dev, int32_t n, void* hip_stream) {
+    const pp_status_t chk = check_run_args(plan, x_dev, y_dev, n);
+    if (chk != PP_OK) return chk;
+    const HostPlan& hp = plan->hp;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (!hp.tiled) return launch_generic(plan, x_dev, y_dev, n, stream);
+    const TiledLayout& tl = hp.tl;
+    if (tl.sw <= 1) return launch_tiled(plan, x_dev, y_dev, n, stream, nullptr, nullptr);
+    // partial sums [sw][n][c_out][h][w] fp32 behind the arrival counters, one per output tile
+    const int eb = hp.dtype == PP_F16 ? 2 : 4;
+    const TileGeom tg = tile_geom(tl.lw, tl.r, eb);
+    const int64_t mrows = ((int64_t)n * (hp.h + 1) - 1 + tl.r - 1) / tl.r;
+    const int64_t tiles = ((hp.w + tg.tw - 1) / tg.tw) * ((mrows * tl.lw + 63) / 64) * ((tl.groups + tl.wf - 1) / tl.wf);
+    const int64_t ws_bytes = (int64_t)tl.sw * n * hp.c_out * hp.h * hp.w * 4;
+    if (tiles * 4 > (int64_t)kScratchCounterBytes || ws_bytes > (int64_t)(kScratchBytes - kScratchCounterBytes)) return PP_ERR_SCRATCH;
+    void* base = nullptr;
+    if (scratch_address(&base) != hipSuccess) {
+        (void)hipGetLastError();
+        return PP_ERR_DEVICE;
+    }
+    int32_t* counters = static_cast<int32_t*>(base);
+    float* ws = reinterpret_cast<float*>(static_cast<unsigned char*>(base) + kScratchCounterBytes);
+    // The array keeps whatever the last call left (a launch that did not complete leaves counts
+    // behind): the counters of this call's tiles start at zero.  A kernel, not a memset, so that the
+    // call can be recorded into a graph.
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(fill_zero_i32, dim3((unsigned)((tiles + 255) / 256)), dim3(256), 0, stream, counters, (int)tiles);
+    if (hipGetLastError() != hipSuccess) return PP_ERR_DEVICE;
+    return launch_tiled(plan, x_dev, y_dev, n, stream, ws, counters);
 }
 
 pp_status_t pp_conv_destroy(pp_conv_plan_t* plan) {

@@ -7,7 +7,7 @@ from typing import Optional
 
 import numpy as np
 
-PP_OK, PP_ERR_NULL, PP_ERR_SHAPE, PP_ERR_PATTERN, PP_ERR_UNSUPPORTED, PP_ERR_ALLOC, PP_ERR_DEVICE, PP_ERR_ALIGN = range(8)
+PP_OK, PP_ERR_NULL, PP_ERR_SHAPE, PP_ERR_PATTERN, PP_ERR_UNSUPPORTED, PP_ERR_ALLOC, PP_ERR_DEVICE, PP_ERR_ALIGN, PP_ERR_SCRATCH = range(9)
 PP_F32, PP_F16 = 0, 1
 PP_FLAG_RELU, PP_FLAG_DENSE, PP_FLAG_HOST_ONLY = 1, 2, 4
 
@@ -70,6 +70,8 @@ def lib() -> C.CDLL:
         L.pp_conv_plan.restype = C.c_int
         L.pp_conv_run.argtypes = [vp, vp, vp, C.c_int32, vp]
         L.pp_conv_run.restype = C.c_int
+        L.pp_conv_run_static.argtypes = [vp, vp, vp, C.c_int32, vp]
+        L.pp_conv_run_static.restype = C.c_int
         L.pp_conv_destroy.argtypes = [vp]
         L.pp_conv_destroy.restype = C.c_int
         L.pp_conv_plan_query.argtypes = [vp, C.POINTER(_Info)]
@@ -125,6 +127,10 @@ def pp_conv_run(plan, x_dev: int, y_dev: int, n: int, hip_stream: int = 0) -> in
     return lib().pp_conv_run(plan, C.c_void_p(x_dev), C.c_void_p(y_dev), int(n), C.c_void_p(hip_stream))
 
 
+def pp_conv_run_static(plan, x_dev: int, y_dev: int, n: int, hip_stream: int = 0) -> int:
+    return lib().pp_conv_run_static(plan, C.c_void_p(x_dev), C.c_void_p(y_dev), int(n), C.c_void_p(hip_stream))
+
+
 def pp_conv_destroy(plan) -> int:
     return lib().pp_conv_destroy(plan)
 
@@ -175,7 +181,9 @@ class Plan:
             raise PPError(st, "pp_conv_plan_query")
         return info
 
-    def run(self, x, y=None, stream: Optional[int] = None):
+    def run(self, x, y=None, stream: Optional[int] = None, static: bool = False):
+        """static=True goes through pp_conv_run_static (y must then be given: that entry point is for
+        callers that allocate nothing)."""
         import torch
         tdt = torch.float16 if self.dtype == PP_F16 else torch.float32
         assert x.is_cuda and x.is_contiguous() and x.dtype == tdt and tuple(x.shape[1:]) == (self.c_in, self.h, self.w)
@@ -185,9 +193,9 @@ class Plan:
         assert y.is_cuda and y.is_contiguous() and y.dtype == tdt and tuple(y.shape) == (n, self.c_out, self.h, self.w)
         if stream is None:
             stream = torch.cuda.current_stream(x.device).cuda_stream
-        st = pp_conv_run(self.handle, x.data_ptr(), y.data_ptr(), n, stream)
+        st = (pp_conv_run_static if static else pp_conv_run)(self.handle, x.data_ptr(), y.data_ptr(), n, stream)
         if st != PP_OK:
-            raise PPError(st, "pp_conv_run")
+            raise PPError(st, "pp_conv_run_static" if static else "pp_conv_run")
         return y
 
     def close(self):
