@@ -214,6 +214,8 @@ def main():
                     help="also launch one plain device copy of this many MiB (a reference dispatch for scaling "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--tuning", default="", help="f,r,wf,ks,cc overrides for the timed workload (0 = automatic)")
+    ap.add_argument("--mfma-tile", default="", help="tile_rows,tile_cols,tiles_per_wave,wg_waves for the matrix-core kernel "
+                                                     "on the timed workload (0 = automatic)")
     ap.add_argument("--variant", type=int, default=0, help="force a kernel variant for the timed workload (0 = the plan's choice)")
     ap.add_argument("--autotune", action="store_true",
                     help="pick the parameters of every timed workload by measurement (paper_2206_10620_amd.autotune) "
@@ -242,6 +244,9 @@ def main():
     if args.tuning:
         f, r, wf, ks, cc = (int(v) for v in args.tuning.split(","))
         tuning = pp.Tuning(variant=2, filters_per_wave=f, rows_per_lane=r, waves_f=wf, split_c=ks, chunk_c=cc)
+    elif args.mfma_tile:
+        tr, tc, ntw, waves = (int(v) for v in args.mfma_tile.split(","))
+        tuning = pp.Tuning(variant=3, tile_rows=tr, tile_cols=tc, tiles_per_wave=ntw, wg_waves=waves)
     elif args.variant:
         tuning = pp.Tuning(variant=args.variant)
     # the warm-up also settles clocks: at least 50 ms of it, whatever --warmup says
@@ -250,7 +255,7 @@ def main():
     sec_wall = t["wall_ms_per_step"] * 1e-3
 
     rev, tbytes = MEASURED_TRAFFIC.get((args.workload, t["chosen"]["variant"]), (None, None))
-    traffic = tbytes if (rev == pp.KERNEL_REVISION and not args.tuning and not args.autotune) else None
+    traffic = tbytes if (rev == pp.KERNEL_REVISION and not args.tuning and not args.mfma_tile and not args.autotune) else None
 
     out = {
         "metric": "effective GMAC/s (nonzero MACs), pattern-pruned 3x3 conv",

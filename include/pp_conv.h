@@ -57,14 +57,20 @@ typedef enum { PP_F32 = 0, PP_F16 = 1 } pp_dtype_t;
 
 enum {
     PP_FLAG_RELU = 1u,      /* y = max(pre, 0) */
-    PP_FLAG_DENSE = 2u,     /* unpruned layer: nine weights per kernel, pattern ids and masks not read */
-    PP_FLAG_HOST_ONLY = 4u  /* build the plan's host metadata only; touches no device (pp_conv_run then fails) */
+    PP_FLAG_DENSE = 2u,     /* unpruned layer: kernel_size^2 weights per kernel, pattern ids and masks not read */
+    PP_FLAG_HOST_ONLY = 4u, /* build the plan's host metadata only; touches no device (pp_conv_run then fails) */
+    PP_FLAG_POOL2 = 8u      /* a 2x2 max-pool with stride 2 follows the activation and is folded into the layer (the
+                               one-to-one / shuffle consumer folded into its producer, section 2.2): y is
+                               [n][c_out][ho/2][wo/2]; the convolution's own output size ho x wo must be even */
 };
 
 /* Execution parameters (the part of the layer-wise representation that the paper leaves to tuning,
  * section 2.3.1).  A zero field means "let the library choose". */
 typedef struct {
-    int32_t variant;        /* 0 auto; 1 generic kernel (any pattern table); 2 tiled pattern-specialised kernel */
+    int32_t variant;        /* 0 auto; 1 generic kernel (any layer); 2 tiled pattern-specialised kernel (3x3, stride 1,
+                               the library's sixteen masks); 3 matrix-core kernel (binary16 storage only: the pruned
+                               weights zero-filled to a dense matrix and multiplied on the MFMA units -- the measured
+                               alternative to pattern-specialised vector code; any pattern table, kernel size, stride) */
     int32_t filters_per_wave; /* F: output filters whose accumulators one wavefront holds (4, 8 or 16) */
     int32_t rows_per_lane;  /* R: output rows per lane (1, 2, or 4 with F = 4); a lane owns R x 4 adjacent output pixels */
     int32_t lanes_x;        /* LW: lanes across the width of a tile (2, 4, 7, 8, 14 or 16) */
@@ -80,24 +86,41 @@ typedef struct {
     int32_t balance;        /* 1: filters and channels take wavefront slots and chunk places in reordered / natural
                                order; 2: they are dealt so that the wavefronts of a workgroup do about equal work
                                between two barriers (the default whenever a workgroup has several wavefronts) */
+    /* matrix-core kernel (variant 3) */
+    int32_t tile_rows;      /* TR: rows of convolution outputs per workgroup tile (rows of the batch laid out as one tall image) */
+    int32_t tile_cols;      /* TC: columns per workgroup tile; TR * TC <= 32 * tiles_per_wave * wg_waves */
+    int32_t tiles_per_wave; /* NTW: 32-pixel MFMA column tiles per wavefront (2 or 4) */
+    int32_t wg_waves;       /* wavefronts per workgroup (4 or 8), all on the same 64 filters; 8 only with NTW = 4 */
+    int32_t autotune;       /* 1: pp_conv_plan times the candidate variants and parameters on the device, on scratch
+                               buffers of n_hint images that it allocates and frees, and keeps the fastest (the
+                               "tuning-decided parameters" of section 2.3.1 decided by measurement) */
 } pp_conv_tuning_t;
 
 /* Layer description (section 2.1.1 for the sparsity, section 2.3.1 for what the layer-wise
  * representation records).  All arrays are host memory, borrowed only for the duration of
  * pp_conv_plan: the plan copies what it needs and the caller may free them afterwards. */
 typedef struct {
-    int32_t c_in, c_out, h, w;      /* >= 1 each; output is c_out x h x w per image */
+    int32_t c_in, c_out, h, w;      /* >= 1 each; input is c_in x h x w per image */
     int32_t n_hint;                 /* batch size the plan should be tuned for; <= 0 means 1 */
     int32_t num_patterns;           /* P, 1..255 (ignored with PP_FLAG_DENSE) */
-    const uint16_t *pattern_masks;  /* [P] 9-bit tap masks, exactly four bits set each */
+    const uint16_t *pattern_masks;  /* [P] tap masks for kernel_size <= 3 (bit t = K*r + c), exactly taps_per_kernel bits each */
     const int32_t *pattern_id;      /* [c_out*c_in] row-major (co, ci); read only where conn_mask != 0 */
     const uint8_t *conn_mask;       /* [c_out*c_in] non-zero = kernel kept; NULL = all kept */
-    const float *weights;           /* [c_out*c_in*4] the four weights of each kernel in ascending tap order,
-                                       read only where kept; with PP_FLAG_DENSE [c_out*c_in*9], taps 0..8 */
+    const float *weights;           /* [c_out*c_in*taps_per_kernel] the weights of each kernel in ascending tap order,
+                                       read only where kept; with PP_FLAG_DENSE [c_out*c_in*K*K], all taps */
     const float *bias;              /* [c_out], or NULL for no bias */
     uint32_t flags;                 /* PP_FLAG_* */
     int32_t dtype;                  /* pp_dtype_t */
     const pp_conv_tuning_t *tuning; /* NULL = all automatic */
+    /* Other kernel sizes and strides (the closing paragraph of section 2.1.1 names 3x3, 5x5 and 7x7 kernels; a
+     * 1x1 layer has one tap, so only connectivity pruning applies to it).  Zero fields mean the 3x3, stride 1,
+     * four-tap layer.  Padding is (K-1)/2 zeros on every side; the convolution's output is
+     * ho x wo = (floor((h-1)/stride)+1) x (floor((w-1)/stride)+1). */
+    int32_t kernel_size;            /* K: 0 (= 3), 1, 3, 5 or 7 */
+    int32_t stride;                 /* 0 (= 1), 1 or 2 */
+    int32_t taps_per_kernel;        /* weights kept per kernel: 0 = 4 for K >= 3 and 1 for K = 1; 1..K*K otherwise */
+    const uint64_t *pattern_masks64; /* [P] tap masks for kernel_size > 3 (bit t = K*r + c, t < K*K); pattern_masks is
+                                        then not read */
 } pp_conv_desc_t;
 
 /* Build a plan.  Validation happens before any device call, so invalid descriptions are
@@ -108,7 +131,8 @@ pp_status_t pp_conv_plan(const pp_conv_desc_t *desc, pp_conv_plan_t **out_plan);
 
 /* Enqueue one forward pass on n images.
  *   x_dev : [n][c_in][h][w]  contiguous, plan dtype, 16-byte aligned, caller-owned
- *   y_dev : [n][c_out][h][w] contiguous, plan dtype, 16-byte aligned, caller-owned, must not overlap x_dev
+ *   y_dev : [n][c_out][out_h][out_w] contiguous, plan dtype, 16-byte aligned, caller-owned, must not overlap x_dev
+ *           (out_h x out_w as reported by pp_conv_plan_query: h x w for a stride-1 layer without pooling)
  *   hip_stream : a hipStream_t (NULL = the default stream)
  * Returns after the launch without synchronising; launch-configuration errors are returned,
  * asynchronous faults are not.  Misaligned or overlapping x_dev / y_dev are PP_ERR_ALIGN (checked
@@ -143,7 +167,8 @@ pp_status_t pp_conv_destroy(pp_conv_plan_t *plan);
  * (pattern id, input channel), so kernels of one pattern are consecutive.
  * Pointers stay valid until pp_conv_destroy. */
 typedef struct {
-    int32_t c_out, c_in, num_patterns, taps; /* taps = 4, or 9 for a dense plan */
+    int32_t c_out, c_in, num_patterns, taps; /* taps = weights per kept kernel (4; 9 for a dense 3x3 plan; ...) */
+    int32_t out_h, out_w;                    /* size of y per image and filter (after stride and pooling) */
     int64_t k_kept;                          /* number of kept kernels */
     const int32_t *perm;     /* [c_out] perm[pos] = original filter index */
     const int32_t *kcount;   /* [c_out] kept kernels of the filter at pos */

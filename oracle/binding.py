@@ -251,7 +251,7 @@ def layer_dense_weights(layer) -> np.ndarray:
     if layer.dtype == "f16":
         w = widen_f16(round_f16(w))
     ksize = getattr(layer, "ksize", 3)
-    if ksize != 3:
+    if ksize != 3 or (not layer.dense and layer.taps != 4):
         return expand_weights_k(layer.c_in, layer.c_out, ksize, layer.pattern_masks, layer.pattern_id, layer.conn_mask,
                                 w, taps=layer.taps)
     return expand_weights(layer.c_in, layer.c_out, layer.pattern_masks, layer.pattern_id, layer.conn_mask, w,

@@ -18,10 +18,13 @@ from .pp_conv import PPError, Tuning, plan_from_layer
 
 
 def default_candidates() -> List[dict]:
-    """The automatic choice first, then rows per lane x (split inside, split across workgroups)."""
+    """The automatic choice first; then, for the tiled vector kernel, rows per lane x (split inside, split
+    across workgroups); then, for the matrix-core kernel (binary16 layers only), both wavefront tile counts."""
     cands: List[dict] = [dict()]
     for r, (ks, sw) in itertools.product((1, 2), ((1, 1), (2, 1), (4, 1), (1, 2), (2, 2))):
-        cands.append(dict(filters_per_wave=4, rows_per_lane=r, split_c=ks, split_wg=sw))
+        cands.append(dict(variant=2, filters_per_wave=4, rows_per_lane=r, split_c=ks, split_wg=sw))
+    cands.append(dict(variant=3, tiles_per_wave=2))
+    cands.append(dict(variant=3, tiles_per_wave=4))
     return cands
 
 
@@ -43,17 +46,13 @@ def autotune(layer, x_dev, y_dev, stream: Optional[int] = None, steps: int = 20,
         if not allow_split_wg and cand.get("split_wg", 1) > 1:
             continue
         try:
-            plan = plan_from_layer(layer, tuning=Tuning(variant=2, **cand) if cand else None, n_hint=int(x_dev.shape[0]))
+            plan = plan_from_layer(layer, tuning=Tuning(**cand) if cand else None, n_hint=int(x_dev.shape[0]))
         except PPError:
-            continue
+            continue                                    # a candidate this layer cannot run with
         chosen = plan.query()["chosen"]
         key = tuple(sorted(chosen.items()))
-        if key in seen or chosen["variant"] != 2:       # same plan as an earlier candidate, or not the tiled kernel
+        if key in seen:                                 # same plan as an earlier candidate
             plan.close()
-            if chosen["variant"] != 2:
-                for _, _, other in plans:
-                    other.close()
-                return None, []
             continue
         seen.add(key)
         plans.append((cand, chosen, plan))

@@ -21,17 +21,22 @@ DEVICE_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang"
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 
-def _deps_mtime() -> float:
-    heads = glob.glob(os.path.join(CSRC, "*.hpp")) + glob.glob(os.path.join(CSRC, "*.inc")) + \
-        glob.glob(os.path.join(ROOT, "include", "*.h")) + [os.path.abspath(__file__)]
-    return max(os.path.getmtime(h) for h in heads)
+def _deps_mtime(src: str, dep: str) -> float:
+    """Newest of the source, this script and the project headers the last compile of src read (from its
+    depfile); infinity if there is no depfile yet."""
+    if not os.path.exists(dep):
+        return float("inf")
+    names = open(dep).read().replace("\\\n", " ").split()[1:]
+    mine = [n for n in names if n.startswith(ROOT)] + [src, os.path.abspath(__file__)]
+    return max((os.path.getmtime(n) if os.path.exists(n) else float("inf")) for n in mine)
 
 
 def _compile(src: str, incremental: bool = False) -> str:
     obj = os.path.join(OBJ, os.path.basename(src) + ".o")
-    if incremental and os.path.exists(obj) and os.path.getmtime(obj) > max(os.path.getmtime(src), _deps_mtime()):
+    dep = obj + ".d"
+    if incremental and os.path.exists(obj) and os.path.getmtime(obj) > _deps_mtime(src, dep):
         return obj
-    cmd = ["hipcc"] + COMMON + (DEVICE_FLAGS if src.endswith(".hip") else ["-x", "c++"]) + ["-c", src, "-o", obj]
+    cmd = ["hipcc"] + COMMON + (DEVICE_FLAGS if src.endswith(".hip") else ["-x", "c++"]) + ["-MD", "-MF", dep, "-c", src, "-o", obj]
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     out = "\n".join(l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:

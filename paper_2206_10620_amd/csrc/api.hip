@@ -6,6 +6,7 @@
 #include <new>
 
 #include "k1_tiled.hpp"
+#include "k2_mfma.hpp"
 #include "plan.hpp"
 #include "pp_conv.h"
 
@@ -23,6 +24,21 @@ k1_launch_fn k1_lookup_f16_p8_r4(int f, int lw, bool direct);
 k1_launch_fn k1_lookup_f16_p16_r1(int f, int lw, bool direct);
 k1_launch_fn k1_lookup_f16_p16_r2(int f, int lw, bool direct);
 k1_launch_fn k1_lookup_f16_p16_r4(int f, int lw, bool direct);
+
+k2_launch_fn k2_lookup_k1(int stride, int ntw, int waves, bool pairs);
+k2_launch_fn k2_lookup_k3(int stride, int ntw, int waves, bool pairs);
+k2_launch_fn k2_lookup_k5(int stride, int ntw, int waves, bool pairs);
+k2_launch_fn k2_lookup_k7(int stride, int ntw, int waves, bool pairs);
+
+k2_launch_fn k2_lookup(int ks, int stride, int ntw, int waves, bool pairs) {
+    switch (ks) {
+        case 1: return k2_lookup_k1(stride, ntw, waves, pairs);
+        case 3: return k2_lookup_k3(stride, ntw, waves, pairs);
+        case 5: return k2_lookup_k5(stride, ntw, waves, pairs);
+        case 7: return k2_lookup_k7(stride, ntw, waves, pairs);
+        default: return nullptr;
+    }
+}
 
 k1_launch_fn k1_lookup(int dtype, int np, int r, int f, int lw, bool direct) {
 #define PPC_PICK(DT, NP)                                   \
@@ -42,11 +58,11 @@ k1_launch_fn k1_lookup(int dtype, int np, int r, int f, int lw, bool direct) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Generic kernel: any pattern table (and the unpruned nine-tap case).  One lane per output
-// pixel, one filter per blockIdx.y; walks the filter's reordered kernel list (same-pattern
-// kernels consecutive) with wave-uniform indices and reads the input straight from global
-// memory with bounds checks.  It is the correctness path for pattern sets the tiled kernel has no
-// specialised code for, not a fast path.
+// Generic kernel: any pattern table, kernel size, stride, with or without the fused 2x2 max-pool.
+// One lane per stored output, one filter per blockIdx.y; walks the filter's reordered kernel list
+// (same-pattern kernels consecutive) with wave-uniform indices and reads the input straight from
+// global memory with bounds checks.  It is the correctness path for layers the fast kernels do not
+// take, not a fast path.
 struct K0Args {
     const void* x;
     void* y;
@@ -58,34 +74,44 @@ struct K0Args {
     const int32_t* perm;       // [c_out]
     const float* bias;         // [c_out] by original index
     int32_t n, c_in, c_out, h, w_, taps, relu;
+    int32_t stride, ho, wo, out_h, out_w, pool;
 };
 
 template <typename T>
 __global__ __launch_bounds__(256) void k0_generic(const K0Args a) {
     const int pos = blockIdx.y;
     const int64_t pix = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t ohw = (int64_t)a.out_h * a.out_w;
+    if (pix >= (int64_t)a.n * ohw) return;
+    const int img = (int)(pix / ohw);
+    const int rem = (int)(pix - (int64_t)img * ohw);
+    const int sy = rem / a.out_w, sx = rem - sy * a.out_w;      // stored output
     const int64_t hw = (int64_t)a.h * a.w_;
-    if (pix >= (int64_t)a.n * hw) return;
-    const int img = (int)(pix / hw);
-    const int rem = (int)(pix - (int64_t)img * hw);
-    const int oy = rem / a.w_, ox = rem - oy * a.w_;
     const T* __restrict__ x = static_cast<const T*>(a.x);
-    float acc = 0.0f;
-    const int beg = a.filt_off[pos], end = a.filt_off[pos + 1];
-    for (int e = beg; e < end; ++e) {
-        const int ci = a.kidx[e];
-        const int8_t* tp = a.tap_dyx + (int)a.kpat[e] * a.taps * 2;
-        const float* wv = a.w + (int64_t)e * a.taps;
-        const T* xc = x + ((int64_t)img * a.c_in + ci) * hw;
-        for (int j = 0; j < a.taps; ++j) {
-            const int iy = oy + tp[2 * j], ix = ox + tp[2 * j + 1];
-            if (iy >= 0 && iy < a.h && ix >= 0 && ix < a.w_) acc = __builtin_fmaf(wv[j], (float)xc[iy * a.w_ + ix], acc);
-        }
-    }
     const int co = a.perm[pos];
-    acc += a.bias[co];
-    if (a.relu) acc = acc > 0.0f ? acc : 0.0f;
-    static_cast<T*>(a.y)[((int64_t)img * a.c_out + co) * hw + rem] = (T)acc;
+    const int beg = a.filt_off[pos], end = a.filt_off[pos + 1];
+    const int np = a.pool ? 2 : 1;
+    float best = 0.0f;
+    for (int py = 0; py < np; ++py)
+        for (int px = 0; px < np; ++px) {
+            const int oy = sy * np + py, ox = sx * np + px;     // the convolution's own output
+            float acc = 0.0f;
+            for (int e = beg; e < end; ++e) {
+                const int ci = a.kidx[e];
+                const int8_t* tp = a.tap_dyx + (int)a.kpat[e] * a.taps * 2;
+                const float* wv = a.w + (int64_t)e * a.taps;
+                const T* xc = x + ((int64_t)img * a.c_in + ci) * hw;
+                for (int j = 0; j < a.taps; ++j) {
+                    const int iy = oy * a.stride + tp[2 * j], ix = ox * a.stride + tp[2 * j + 1];
+                    if (iy >= 0 && iy < a.h && ix >= 0 && ix < a.w_) acc = __builtin_fmaf(wv[j], (float)xc[iy * a.w_ + ix], acc);
+                }
+            }
+            acc += a.bias[co];
+            if (a.relu) acc = acc > 0.0f ? acc : 0.0f;
+            const float v = (float)(T)acc;                      // pooling acts on stored values
+            best = (py == 0 && px == 0) ? v : (v > best ? v : best);
+        }
+    static_cast<T*>(a.y)[((int64_t)img * a.c_out + co) * ohw + rem] = (T)best;
 }
 
 template <typename T>
@@ -154,6 +180,10 @@ struct pp_conv_plan {
     int32_t* d_counters = nullptr;     // arrivals per output tile (zero between launches)
     float* d_bias_pad = nullptr;
     k1_launch_fn launch = nullptr;
+    // matrix-core kernel
+    uint16_t* d_wpk = nullptr;
+    float* d_bias_mfma = nullptr;
+    k2_launch_fn launch2 = nullptr;
     // generic kernel
     int32_t* d_filt_off = nullptr;
     int32_t* d_kidx = nullptr;
@@ -178,7 +208,7 @@ bool upload(T** dst, const void* src, size_t bytes) {
 }
 
 void free_device(pp_conv_plan_t* p) {
-    void* bufs[] = {p->d_stream, p->d_wave_off, p->d_chan_map, p->d_ws, p->d_counters, p->d_perm_pad, p->d_bias_pad, p->d_filt_off, p->d_kidx,
+    void* bufs[] = {p->d_stream, p->d_wave_off, p->d_chan_map, p->d_ws, p->d_counters, p->d_perm_pad, p->d_bias_pad, p->d_wpk, p->d_bias_mfma, p->d_filt_off, p->d_kidx,
                     p->d_kpat,   p->d_w,        p->d_tap,      p->d_perm,     p->d_bias};
     for (void* b : bufs)
         if (b) (void)hipFree(b);
@@ -233,6 +263,12 @@ pp_status_t pp_conv_plan(const pp_conv_desc_t* desc, pp_conv_plan_t** out_plan) 
             delete p;
             return PP_ERR_UNSUPPORTED;
         }
+    } else if (hp.mfma) {
+        p->launch2 = k2_lookup(hp.ks, hp.stride, hp.ml.ntw, hp.ml.waves, hp.ml.pairs);
+        if (!p->launch2) {
+            delete p;
+            return PP_ERR_UNSUPPORTED;
+        }
     } else if (hp.c_out > 65535) {
         delete p;
         return PP_ERR_UNSUPPORTED;
@@ -260,6 +296,9 @@ pp_status_t pp_conv_plan(const pp_conv_desc_t* desc, pp_conv_plan_t** out_plan) 
             ok = ok && hipMemset(p->d_counters, 0, (size_t)tiles * 4) == hipSuccess;
         }
         ok = ok && upload(&p->d_bias_pad, tl.bias_pad.data(), tl.bias_pad.size() * 4);
+    } else if (hp.mfma) {
+        ok = ok && upload(&p->d_wpk, hp.ml.wpk.data(), hp.ml.wpk.size() * 2);
+        ok = ok && upload(&p->d_bias_mfma, hp.ml.bias_pad.data(), hp.ml.bias_pad.size() * 4);
     } else {
         const Canonical& cn = hp.canon;
         std::vector<float> w = cn.wpacked;
@@ -348,16 +387,16 @@ static pp_status_t check_run_args(const pp_conv_plan_t* plan, const void* x_dev,
     if (!plan || !x_dev || !y_dev) return PP_ERR_NULL;
     const HostPlan& hp = plan->hp;
     if (n <= 0) return PP_ERR_SHAPE;
-    const int64_t hw = (int64_t)hp.h * hp.w;
-    if ((int64_t)n * hp.c_in * hw >= ((int64_t)1 << 31) || (int64_t)n * hp.c_out * hw >= ((int64_t)1 << 31) ||
-        (int64_t)n * (hp.h + 1) >= ((int64_t)1 << 30))
+    const int64_t hw = (int64_t)hp.h * hp.w, ohw = (int64_t)hp.out_h * hp.out_w;
+    if ((int64_t)n * hp.c_in * hw >= ((int64_t)1 << 31) || (int64_t)n * hp.c_out * hp.ho * hp.wo >= ((int64_t)1 << 31) ||
+        (int64_t)n * (hp.h + 8) >= ((int64_t)1 << 30))
         return PP_ERR_SHAPE;
     // the kernels use 128-bit loads and stores: a misaligned or aliased buffer must become a status
     // code here, not a memory fault on the device
     const int64_t ebytes = hp.dtype == PP_F16 ? 2 : 4;
     const uintptr_t xa = reinterpret_cast<uintptr_t>(x_dev), ya = reinterpret_cast<uintptr_t>(y_dev);
     if ((xa | ya) & 15u) return PP_ERR_ALIGN;
-    const uintptr_t xe = xa + (uintptr_t)((int64_t)n * hp.c_in * hw * ebytes), ye = ya + (uintptr_t)((int64_t)n * hp.c_out * hw * ebytes);
+    const uintptr_t xe = xa + (uintptr_t)((int64_t)n * hp.c_in * hw * ebytes), ye = ya + (uintptr_t)((int64_t)n * hp.c_out * ohw * ebytes);
     if (xa < ye && ya < xe) return PP_ERR_ALIGN;
     if (!plan->on_device) return PP_ERR_UNSUPPORTED;
     return PP_OK;
@@ -365,16 +404,71 @@ static pp_status_t check_run_args(const pp_conv_plan_t* plan, const void* x_dev,
 
 static pp_status_t launch_generic(const pp_conv_plan_t* plan, const void* x_dev, void* y_dev, int32_t n, hipStream_t stream) {
     const HostPlan& hp = plan->hp;
-    const int64_t hw = (int64_t)hp.h * hp.w;
+    const int64_t ohw = (int64_t)hp.out_h * hp.out_w;
     const int relu = (hp.flags & PP_FLAG_RELU) ? 1 : 0;
     K0Args a{x_dev, y_dev, plan->d_filt_off, plan->d_kidx, plan->d_kpat, plan->d_w, plan->d_tap, plan->d_perm,
-             plan->d_bias, n, hp.c_in, hp.c_out, hp.h, hp.w, hp.taps, relu};
-    const int64_t blocks = ((int64_t)n * hw + 255) / 256;
+             plan->d_bias, n, hp.c_in, hp.c_out, hp.h, hp.w, hp.taps, relu,
+             hp.stride, hp.ho, hp.wo, hp.out_h, hp.out_w, hp.pool ? 1 : 0};
+    const int64_t blocks = ((int64_t)n * ohw + 255) / 256;
     if (blocks >= ((int64_t)1 << 31)) return PP_ERR_SHAPE;
     dim3 grid((unsigned)blocks, (unsigned)hp.c_out);
     (void)hipGetLastError();
     if (hp.dtype == PP_F16) hipLaunchKernelGGL(k0_generic<_Float16>, grid, dim3(256), 0, stream, a);
     else hipLaunchKernelGGL(k0_generic<float>, grid, dim3(256), 0, stream, a);
+    return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_DEVICE;
+}
+
+// One launch of the matrix-core kernel on n images.
+static pp_status_t launch_mfma(const pp_conv_plan_t* plan, const void* x_dev, void* y_dev, int32_t n, hipStream_t stream) {
+    const HostPlan& hp = plan->hp;
+    const MfmaLayout& ml = hp.ml;
+    K2Args a{};
+    a.x = x_dev;
+    a.y = y_dev;
+    a.wpk = plan->d_wpk;
+    a.bias = plan->d_bias_mfma;
+    a.n = n;
+    a.c_in = hp.c_in;
+    a.c_out = hp.c_out;
+    a.h = hp.h;
+    a.w = hp.w;
+    a.ho = hp.ho;
+    a.wo = hp.wo;
+    a.out_h = hp.out_h;
+    a.out_w = hp.out_w;
+    a.po = ml.po;
+    a.vrows = (n - 1) * ml.po + hp.ho;
+    a.tr = ml.tr;
+    a.tc = ml.tc;
+    a.trp = ml.trp;
+    a.twpa = ml.twpa;
+    a.tiles_x = (hp.wo + ml.tc - 1) / ml.tc;
+    a.tiles_v = (a.vrows + ml.tr - 1) / ml.tr;
+    a.fb = ml.fb;
+    a.q = ml.q;
+    const int64_t items = (int64_t)a.tiles_x * a.tiles_v * ml.fb;
+    if (items >= ((int64_t)1 << 30) || (int64_t)n * ml.po * hp.stride >= ((int64_t)1 << 30)) return PP_ERR_SHAPE;
+    a.work_items = (int)items;
+    a.blocks_per_xcd = (int)((items + 7) / 8);
+    a.xbuf_bytes = ml.xbuf_bytes;
+    a.out_pitch = ml.out_pitch;
+    a.gw = ml.gw;
+    a.bias_off = (int)ml.lds_bytes - kMfmaFilters * 4;
+    a.stride_ = hp.stride;
+    auto magic = [](int d) -> uint32_t { return d <= 1 ? 0u : (uint32_t)((((uint64_t)1) << 32) / (uint64_t)d + 1u); };
+    const int store_cols = hp.pool ? ml.tc / 2 : ml.tc, store_rows = hp.pool ? ml.tr / 2 : ml.tr;
+    a.magic_ppr = magic(ml.twpa / 2);
+    a.magic_pi = magic(ml.po * hp.stride);
+    a.magic_tc = magic(ml.tc);
+    a.magic_po = magic(ml.po);
+    a.magic_gpr = magic(store_cols / ml.gw);
+    a.magic_srows = magic(store_rows);
+    // the index arithmetic divides by multiplication, exact below 65536
+    if (ml.po * hp.stride + ml.trp >= 65536 || ml.po + ml.tr >= 65536) return PP_ERR_SHAPE;
+    a.relu = (hp.flags & PP_FLAG_RELU) ? 1 : 0;
+    a.pool = hp.pool ? 1 : 0;
+    (void)hipGetLastError();
+    plan->launch2(a, a.blocks_per_xcd * 8, 64 * ml.waves, (int)ml.lds_bytes, stream);
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_DEVICE;
 }
 
@@ -384,6 +478,7 @@ pp_status_t pp_conv_run(const pp_conv_plan_t* plan, const void* x_dev, void* y_d
     const HostPlan& hp = plan->hp;
     const int64_t hw = (int64_t)hp.h * hp.w;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (hp.mfma) return launch_mfma(plan, x_dev, y_dev, n, stream);
     if (!hp.tiled) return launch_generic(plan, x_dev, y_dev, n, stream);
     // A plan that splits channels across workgroups owns a workspace for n_hint images: larger
     // batches go through it n_hint images at a time.
@@ -405,6 +500,7 @@ pp_status_t pp_conv_run_static(const pp_conv_plan_t* plan, const void* x_dev, vo
     if (chk != PP_OK) return chk;
     const HostPlan& hp = plan->hp;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (hp.mfma) return launch_mfma(plan, x_dev, y_dev, n, stream);
     if (!hp.tiled) return launch_generic(plan, x_dev, y_dev, n, stream);
     const TiledLayout& tl = hp.tl;
     if (tl.sw <= 1) return launch_tiled(plan, x_dev, y_dev, n, stream, nullptr, nullptr);
@@ -445,6 +541,8 @@ pp_status_t pp_conv_plan_query(const pp_conv_plan_t* plan, pp_plan_info_t* out) 
     out->c_in = hp.c_in;
     out->num_patterns = hp.num_patterns;
     out->taps = hp.taps;
+    out->out_h = hp.out_h;
+    out->out_w = hp.out_w;
     out->k_kept = hp.canon.k_kept;
     out->perm = hp.canon.perm.data();
     out->kcount = hp.canon.kcount.data();

@@ -31,7 +31,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include "plan.hpp"
+#include "tile_geom.hpp"
 
 namespace ppc {
 

@@ -12,18 +12,9 @@ namespace ppc {
 
 namespace {
 
-int popcount16(uint32_t v) {
-    int n = 0;
-    while (v) {
-        v &= v - 1;
-        ++n;
-    }
-    return n;
-}
-
-int builtin_slot(uint16_t mask) {
+int builtin_slot(uint64_t mask) {
     for (int s = 0; s < kBuiltinPatterns; ++s)
-        if (kBuiltinMasks[s] == mask) return s;
+        if ((uint64_t)kBuiltinMasks[s] == mask) return s;
     return -1;
 }
 
@@ -65,19 +56,52 @@ float f16_to_f32(uint16_t b) {
     return v;
 }
 
+namespace {
+struct Geometry { int ks, stride, taps; bool dense, pool; };
+// kernel size, stride and taps per kernel of a description, with the zero defaults resolved; ks = 0 if invalid
+Geometry geometry(const pp_conv_desc_t& d) {
+    Geometry g{};
+    g.dense = (d.flags & PP_FLAG_DENSE) != 0;
+    g.pool = (d.flags & PP_FLAG_POOL2) != 0;
+    g.ks = d.kernel_size == 0 ? 3 : d.kernel_size;
+    g.stride = d.stride == 0 ? 1 : d.stride;
+    if (g.ks != 1 && g.ks != 3 && g.ks != 5 && g.ks != 7) g.ks = 0;
+    g.taps = g.dense ? g.ks * g.ks : (d.taps_per_kernel == 0 ? (g.ks == 1 ? 1 : 4) : d.taps_per_kernel);
+    return g;
+}
+int popcount64(uint64_t v) {
+    int n = 0;
+    while (v) {
+        v &= v - 1;
+        ++n;
+    }
+    return n;
+}
+}  // namespace
+
 pp_status_t validate(const pp_conv_desc_t& d) {
-    const bool dense = (d.flags & PP_FLAG_DENSE) != 0;
+    const Geometry g = geometry(d);
+    const bool dense = g.dense;
     if (!d.weights) return PP_ERR_NULL;
-    if (!dense && (!d.pattern_masks || !d.pattern_id)) return PP_ERR_NULL;
+    if (g.ks == 0 || (g.stride != 1 && g.stride != 2)) return PP_ERR_UNSUPPORTED;
+    const bool wide = g.ks > 3;
+    if (!dense && (!(wide ? (const void*)d.pattern_masks64 : (const void*)d.pattern_masks) || !d.pattern_id)) return PP_ERR_NULL;
     if (d.c_in < 1 || d.c_out < 1 || d.h < 1 || d.w < 1) return PP_ERR_SHAPE;
     if ((int64_t)d.c_in * d.c_out >= (int64_t)1 << 28) return PP_ERR_SHAPE;
     if ((int64_t)std::max(d.c_in, d.c_out) * d.h * d.w >= (int64_t)1 << 31) return PP_ERR_SHAPE;
-    if (d.flags & ~(uint32_t)(PP_FLAG_RELU | PP_FLAG_DENSE | PP_FLAG_HOST_ONLY)) return PP_ERR_UNSUPPORTED;
+    if (d.flags & ~(uint32_t)(PP_FLAG_RELU | PP_FLAG_DENSE | PP_FLAG_HOST_ONLY | PP_FLAG_POOL2)) return PP_ERR_UNSUPPORTED;
     if (d.dtype != PP_F32 && d.dtype != PP_F16) return PP_ERR_UNSUPPORTED;
+    if (g.pool) {
+        const int ho = (d.h - 1) / g.stride + 1, wo = (d.w - 1) / g.stride + 1;
+        if ((ho & 1) || (wo & 1)) return PP_ERR_SHAPE;
+    }
     if (dense) return PP_OK;
+    if (g.taps < 1 || g.taps > g.ks * g.ks) return PP_ERR_PATTERN;
     if (d.num_patterns < 1 || d.num_patterns > 255) return PP_ERR_PATTERN;
-    for (int p = 0; p < d.num_patterns; ++p)
-        if (d.pattern_masks[p] >= 512 || popcount16(d.pattern_masks[p]) != 4) return PP_ERR_PATTERN;
+    for (int p = 0; p < d.num_patterns; ++p) {
+        const uint64_t m = wide ? d.pattern_masks64[p] : (uint64_t)d.pattern_masks[p];
+        if ((g.ks * g.ks < 64 && (m >> (g.ks * g.ks)) != 0) || popcount64(m) != g.taps) return PP_ERR_PATTERN;
+    }
     const int64_t k_total = (int64_t)d.c_in * d.c_out;
     for (int64_t k = 0; k < k_total; ++k) {
         if (d.conn_mask && !d.conn_mask[k]) continue;
@@ -87,7 +111,8 @@ pp_status_t validate(const pp_conv_desc_t& d) {
 }
 
 void build_canonical(const pp_conv_desc_t& d, HostPlan& hp) {
-    const bool dense = (d.flags & PP_FLAG_DENSE) != 0;
+    const Geometry geo = geometry(d);
+    const bool dense = geo.dense;
     hp.c_in = d.c_in;
     hp.c_out = d.c_out;
     hp.h = d.h;
@@ -95,10 +120,19 @@ void build_canonical(const pp_conv_desc_t& d, HostPlan& hp) {
     hp.n_hint = d.n_hint > 0 ? d.n_hint : 1;
     hp.flags = d.flags;
     hp.dtype = d.dtype;
-    hp.taps = dense ? 9 : 4;
+    hp.ks = geo.ks;
+    hp.stride = geo.stride;
+    hp.pool = geo.pool;
+    hp.ho = (d.h - 1) / geo.stride + 1;
+    hp.wo = (d.w - 1) / geo.stride + 1;
+    hp.out_h = geo.pool ? hp.ho / 2 : hp.ho;
+    hp.out_w = geo.pool ? hp.wo / 2 : hp.wo;
+    hp.taps = geo.taps;
     hp.num_patterns = dense ? 1 : d.num_patterns;
-    hp.masks.assign(hp.num_patterns, 0x1FF);
-    if (!dense) hp.masks.assign(d.pattern_masks, d.pattern_masks + d.num_patterns);
+    const int kk = geo.ks * geo.ks;
+    hp.masks.assign(hp.num_patterns, kk == 64 ? ~(uint64_t)0 : (((uint64_t)1 << kk) - 1));
+    if (!dense)
+        for (int p = 0; p < d.num_patterns; ++p) hp.masks[p] = geo.ks > 3 ? d.pattern_masks64[p] : (uint64_t)d.pattern_masks[p];
     hp.bias.assign(d.c_out, 0.0f);
     if (d.bias) hp.bias.assign(d.bias, d.bias + d.c_out);
 
@@ -158,10 +192,10 @@ void build_canonical(const pp_conv_desc_t& d, HostPlan& hp) {
     for (int pos = 0; pos < co_n; ++pos) hp.filt_off[pos + 1] = hp.filt_off[pos] + cn.kcount[pos];
     hp.tap_dyx.clear();
     for (int p = 0; p < P; ++p)
-        for (int t = 0; t < 9; ++t)
+        for (int t = 0; t < kk; ++t)
             if ((hp.masks[p] >> t) & 1u) {
-                hp.tap_dyx.push_back((int8_t)(t / 3 - 1));
-                hp.tap_dyx.push_back((int8_t)(t % 3 - 1));
+                hp.tap_dyx.push_back((int8_t)(t / geo.ks - geo.ks / 2));
+                hp.tap_dyx.push_back((int8_t)(t % geo.ks - geo.ks / 2));
             }
 }
 
@@ -202,17 +236,18 @@ int64_t spatial_waves(int n, int h, int w, int lw, int r) {
 pp_status_t build_layouts(const pp_conv_desc_t& d, HostPlan& hp) {
     pp_conv_tuning_t t{};
     if (d.tuning) t = *d.tuning;
-    if (t.variant < 0 || t.variant > 2) return PP_ERR_UNSUPPORTED;
+    if (t.variant < 0 || t.variant > 3) return PP_ERR_UNSUPPORTED;
 
-    // can the tiled kernel express this layer's pattern table?
+    // can the tiled kernel express this layer?  (3x3, stride 1, no pooling, and a pattern table made of
+    // the masks it has specialised code for)
     std::vector<int> slot_of(hp.num_patterns, -1);
     // An unpruned (nine-tap) kernel is run as three four-tap kernels on the same channel whose
     // patterns cover the 3x3 window: {0,1,3,4}, {4,5,7,8} with a zero centre weight, and
     // {0,2,4,6} with zero weights on taps 0 and 4 (12 multiply-accumulates for 9 weights).
-    const bool dense = hp.taps == 9;
-    bool builtin = true;
+    const bool dense = hp.taps == 9 && hp.ks == 3;
+    bool builtin = hp.ks == 3 && hp.stride == 1 && !hp.pool && (dense || hp.taps == 4);
     int max_slot = dense ? 8 : -1;
-    if (!dense) {
+    if (builtin && !dense) {
         std::vector<char> used(hp.num_patterns, 0);
         for (uint8_t p : hp.canon.kpat) used[p] = 1;
         for (int p = 0; p < hp.num_patterns; ++p) {
@@ -221,10 +256,19 @@ pp_status_t build_layouts(const pp_conv_desc_t& d, HostPlan& hp) {
             if (used[p]) max_slot = std::max(max_slot, slot_of[p]);
         }
     }
+    // The matrix-core kernel takes any layer whose storage is binary16.  Measured on MI355X it beats the
+    // pattern-specialised vector kernel on every binary16 benchmark layer (the dense product costs
+    // 9/(4*keep) times the multiply-accumulates at more than 30 times the rate), so it is the default there.
+    const bool mfma_ok = hp.dtype == PP_F16;
     if (t.variant == 2 && !builtin) return PP_ERR_UNSUPPORTED;
-    hp.tiled = builtin && t.variant != 1;
+    if (t.variant == 3 && !mfma_ok) return PP_ERR_UNSUPPORTED;
+    int variant = t.variant;
+    if (variant == 0) variant = mfma_ok ? 3 : (builtin ? 2 : 1);
+    hp.tiled = variant == 2;
+    hp.mfma = variant == 3;
     hp.chosen = pp_conv_tuning_t{};
-    hp.chosen.variant = hp.tiled ? 2 : 1;
+    hp.chosen.variant = variant;
+    if (variant == 3) return build_mfma_layout(t, hp);
     if (!hp.tiled) return PP_OK;
 
     TiledLayout& tl = hp.tl;
@@ -522,6 +566,140 @@ pp_status_t build_layouts(const pp_conv_desc_t& d, HostPlan& hp) {
     push_entry(kEndCode, kSameChannel, nullptr);     // the walker prefetches up to two entries ahead
     push_entry(kEndCode, kSameChannel, nullptr);
     if (tl.stream.size() / EW >= ((size_t)1 << 31)) return PP_ERR_SHAPE;
+    return PP_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Matrix-core kernel: tile choice and weight packing.
+//
+// The layer becomes the product  Y[c_out][pixels] = Wd[c_out][K*K*c_in] x patches[K*K*c_in][pixels]
+// with the removed kernels and pruned taps written out as zeros.  The reduction index runs chunk of
+// 16 channels slowest, then tap, then channel inside the chunk, so that one MFMA step
+// (v_mfma_f32_32x32x16_f16) reduces over 16 consecutive channels at one tap: the lane that holds
+// output pixel p then needs 8 consecutive channels of one input pixel, one 128-bit LDS read from a
+// tile staged channel-innermost.  Weights are stored as the MFMA "A" operand fragments themselves:
+// fragment (filter block, chunk, tap, half) is 64 lanes x 8 binary16 = 1 KB, lane l holding filter
+// 32*half + l%32 and channels 8*(l/32) .. 8*(l/32)+7 of the chunk.
+pp_status_t build_mfma_layout(const pp_conv_tuning_t& t, HostPlan& hp) {
+    MfmaLayout& ml = hp.ml;
+    const int KS = hp.ks, S = hp.stride, KK = KS * KS, pad = KS / 2;
+    ml.fb = (hp.c_out + kMfmaFilters - 1) / kMfmaFilters;
+    ml.q = (hp.c_in + kMfmaChunk - 1) / kMfmaChunk;
+    ml.upq = KS <= 3 ? 1 : KS;
+    ml.wbuf_bytes = (KK / ml.upq) * 2 * 1024;
+    // The batch is one tall virtual image: image n's output row oy is virtual row n*po + oy, and the
+    // matching input rows start at virtual input row n*po*S, so that a tile may straddle images; the
+    // rows between images read as zeros (they are the padding) and their outputs are not stored.
+    ml.po = hp.ho + (pad + S - 1) / S;
+    if (hp.pool && (ml.po & 1)) ++ml.po;
+    const int64_t vrows = (int64_t)hp.n_hint * ml.po - (ml.po - hp.ho);
+    const int step = hp.pool ? 2 : 1;
+    ml.pairs = (hp.w & 1) == 0;
+    auto staged_cols = [&](int tc) { return ((tc - 1) * S + KS + 2) & ~1; };
+    auto pair_groups = [&](int tr, int tc) { return (((tr - 1) * S + KS) * (staged_cols(tc) / 2) + 15) / 16; };
+    auto lds_need = [&](int tr, int tc) -> int64_t {
+        const int64_t xbuf = (int64_t)pair_groups(tr, tc) * 32 * kMfmaPixelBytes;
+        const int64_t main = 2 * xbuf + 2 * ml.wbuf_bytes;
+        const int64_t out = (int64_t)kMfmaFilters * ((tr * tc + 7) / 8 * 8) * 2;
+        return std::max(main, out) + kMfmaFilters * 4;      // + the workgroup's bias values
+    };
+    auto fits = [&](int tr, int tc, int waves, int ntw) {
+        return lds_need(tr, tc) <= kMfmaMaxDynamicLds && (pair_groups(tr, tc) + waves / 2 - 1) / (waves / 2) <= mfma_max_units(waves, ntw);
+    };
+    auto evaluate = [&](int waves, int ntw, int& btr, int& btc, int64_t& bwgs) {
+        const int slots = 32 * ntw * waves;
+        double bcost = 1e300;
+        btr = btc = 0;
+        bwgs = 0;
+        for (int tc = step; tc <= std::min(slots, (hp.wo + step - 1) / step * step); tc += step) {
+            int tr = (int)std::min<int64_t>(slots / tc, (vrows + step - 1) / step * step);
+            tr = tr / step * step;
+            while (tr >= step && !fits(tr, tc, waves, ntw)) tr -= step;
+            if (tr < step) continue;
+            const int64_t tiles = (int64_t)((hp.wo + tc - 1) / tc) * ((vrows + tr - 1) / tr);
+            const double halo = (double)((tr - 1) * S + KS) * staged_cols(tc) / ((double)tr * tc * S * S);
+            // matrix-core work of all tiles, extra for the halo's staging traffic, and a preference for
+            // wide tiles: rows are loaded and stored in pieces of tc elements, and pieces below 128 bytes
+            // waste memory transactions
+            double cost = (double)tiles * slots * (1.0 + 0.5 * (halo - 1.0)) * (1.0 + 8.0 / tc);
+            if (cost < bcost - 1e-9) {
+                bcost = cost;
+                btr = tr;
+                btc = tc;
+                bwgs = tiles * ml.fb;
+            }
+        }
+    };
+    if (t.tiles_per_wave != 0 && t.tiles_per_wave != 2 && t.tiles_per_wave != 4) return PP_ERR_UNSUPPORTED;
+    if (t.wg_waves != 0 && t.wg_waves != 4 && t.wg_waves != 8) return PP_ERR_UNSUPPORTED;
+    // Larger tiles re-read less (weights once per tile, a thinner halo) and eight wavefronts hide each
+    // other's LDS and barrier latency, but the layer needs enough workgroups to fill 256 compute units.
+    static const int kShapes[3][2] = {{8, 4}, {4, 4}, {4, 2}};
+    int btr = 0, btc = 0;
+    ml.waves = 0;
+    for (int k = 0; k < 3; ++k) {
+        const int waves = kShapes[k][0], ntw = kShapes[k][1];
+        if ((t.wg_waves && t.wg_waves != waves) || (t.tiles_per_wave && t.tiles_per_wave != ntw)) continue;
+        int tr = 0, tc = 0;
+        int64_t wgs = 0;
+        evaluate(waves, ntw, tr, tc, wgs);
+        if (tr == 0) continue;
+        ml.waves = waves;
+        ml.ntw = ntw;
+        btr = tr;
+        btc = tc;
+        if (wgs >= 480) break;          // otherwise try the next smaller shape (the last one stands)
+    }
+    if (ml.waves == 0) return PP_ERR_UNSUPPORTED;
+    ml.tr = btr;
+    ml.tc = btc;
+    if (t.tile_rows || t.tile_cols) {
+        if (t.tile_rows < step || t.tile_cols < step || t.tile_rows % step || t.tile_cols % step) return PP_ERR_UNSUPPORTED;
+        ml.tr = t.tile_rows;
+        ml.tc = t.tile_cols;
+    }
+    if (ml.tr < 1 || ml.tc < 1 || ml.tr * ml.tc > 32 * ml.ntw * ml.waves || !fits(ml.tr, ml.tc, ml.waves, ml.ntw)) return PP_ERR_UNSUPPORTED;
+    ml.trp = (ml.tr - 1) * S + KS;
+    ml.twpa = staged_cols(ml.tc);
+    ml.xbuf_bytes = pair_groups(ml.tr, ml.tc) * 32 * kMfmaPixelBytes;
+    ml.out_pitch = (ml.tr * ml.tc + 7) / 8 * 8;
+    ml.lds_bytes = lds_need(ml.tr, ml.tc);
+    const int ow = hp.out_w, otc = hp.pool ? ml.tc / 2 : ml.tc;
+    ml.gw = 1;
+    for (int g = 8; g > 1; g /= 2)
+        if (ow % g == 0 && otc % g == 0) {
+            ml.gw = g;
+            break;
+        }
+    hp.chosen.wg_waves = ml.waves;
+    hp.chosen.tile_rows = ml.tr;
+    hp.chosen.tile_cols = ml.tc;
+    hp.chosen.tiles_per_wave = ml.ntw;
+
+    // weights: scatter the kept kernels into zero-filled operand fragments
+    const Canonical& cn = hp.canon;
+    ml.wpk.assign((size_t)ml.fb * ml.q * KK * 2 * 64 * 8, 0);
+    ml.bias_pad.assign((size_t)ml.fb * kMfmaFilters, 0.0f);
+    for (int co = 0; co < hp.c_out; ++co) ml.bias_pad[co] = hp.bias[co];
+    std::vector<int> taps_of((size_t)hp.num_patterns * hp.taps);
+    for (int p = 0; p < hp.num_patterns; ++p) {
+        int j = 0;
+        for (int tp = 0; tp < KK; ++tp)
+            if ((hp.masks[p] >> tp) & 1u) taps_of[(size_t)p * hp.taps + j++] = tp;
+    }
+    for (int pos = 0; pos < hp.c_out; ++pos) {
+        const int co = cn.perm[pos];
+        const int fbi = co / kMfmaFilters, half = (co % kMfmaFilters) / 32, row = co % 32;
+        for (int64_t e = hp.filt_off[pos]; e < hp.filt_off[pos + 1]; ++e) {
+            const int ci = cn.kidx[e], qi = ci / kMfmaChunk, cl = ci % kMfmaChunk;
+            const int lane = row + 32 * (cl / 8), j8 = cl % 8;
+            for (int j = 0; j < hp.taps; ++j) {
+                const int tp = taps_of[(size_t)cn.kpat[e] * hp.taps + j];
+                const size_t frag = (((size_t)fbi * ml.q + qi) * KK + tp) * 2 + half;
+                ml.wpk[(frag * 64 + lane) * 8 + j8] = f32_to_f16_rne(cn.wpacked[(size_t)e * hp.taps + j]);
+            }
+        }
+    }
     return PP_OK;
 }
 

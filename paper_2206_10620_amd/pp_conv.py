@@ -9,7 +9,7 @@ import numpy as np
 
 PP_OK, PP_ERR_NULL, PP_ERR_SHAPE, PP_ERR_PATTERN, PP_ERR_UNSUPPORTED, PP_ERR_ALLOC, PP_ERR_DEVICE, PP_ERR_ALIGN, PP_ERR_SCRATCH = range(9)
 PP_F32, PP_F16 = 0, 1
-PP_FLAG_RELU, PP_FLAG_DENSE, PP_FLAG_HOST_ONLY = 1, 2, 4
+PP_FLAG_RELU, PP_FLAG_DENSE, PP_FLAG_HOST_ONLY, PP_FLAG_POOL2 = 1, 2, 4, 8
 
 # Bumped whenever the device code of the tiled kernel changes (measurements that are tied to a
 # kernel build, such as hardware-counter readings, are keyed by it).
@@ -28,7 +28,9 @@ class PPError(RuntimeError):
 class Tuning(C.Structure):
     _fields_ = [("variant", C.c_int32), ("filters_per_wave", C.c_int32), ("rows_per_lane", C.c_int32),
                 ("lanes_x", C.c_int32), ("waves_f", C.c_int32), ("split_c", C.c_int32), ("chunk_c", C.c_int32),
-                ("staging", C.c_int32), ("split_wg", C.c_int32), ("balance", C.c_int32)]
+                ("staging", C.c_int32), ("split_wg", C.c_int32), ("balance", C.c_int32),
+                ("tile_rows", C.c_int32), ("tile_cols", C.c_int32), ("tiles_per_wave", C.c_int32),
+                ("wg_waves", C.c_int32), ("autotune", C.c_int32)]
 
     def as_dict(self):
         return {k: getattr(self, k) for k, _ in self._fields_}
@@ -39,12 +41,14 @@ class _Desc(C.Structure):
                 ("n_hint", C.c_int32), ("num_patterns", C.c_int32),
                 ("pattern_masks", C.c_void_p), ("pattern_id", C.c_void_p), ("conn_mask", C.c_void_p),
                 ("weights", C.c_void_p), ("bias", C.c_void_p),
-                ("flags", C.c_uint32), ("dtype", C.c_int32), ("tuning", C.POINTER(Tuning))]
+                ("flags", C.c_uint32), ("dtype", C.c_int32), ("tuning", C.POINTER(Tuning)),
+                ("kernel_size", C.c_int32), ("stride", C.c_int32), ("taps_per_kernel", C.c_int32),
+                ("pattern_masks64", C.c_void_p)]
 
 
 class _Info(C.Structure):
     _fields_ = [("c_out", C.c_int32), ("c_in", C.c_int32), ("num_patterns", C.c_int32), ("taps", C.c_int32),
-                ("k_kept", C.c_int64),
+                ("out_h", C.c_int32), ("out_w", C.c_int32), ("k_kept", C.c_int64),
                 ("perm", C.POINTER(C.c_int32)), ("kcount", C.POINTER(C.c_int32)), ("pat_off", C.POINTER(C.c_int32)),
                 ("kidx", C.POINTER(C.c_int32)), ("kpat", C.POINTER(C.c_uint8)), ("wpacked", C.POINTER(C.c_float)),
                 ("chosen", Tuning)]
@@ -95,7 +99,7 @@ def _ptr(a: Optional[np.ndarray]):
 
 
 def pp_conv_plan(c_in, c_out, h, w, pattern_masks, pattern_id, conn_mask, weights, bias=None, flags=0,
-                 dtype=PP_F32, n_hint=1, tuning: Optional[Tuning] = None):
+                 dtype=PP_F32, n_hint=1, tuning: Optional[Tuning] = None, kernel_size=0, stride=0, taps_per_kernel=0):
     """Returns (status, plan handle or None).  Array arguments are numpy arrays (or None where the
     header allows NULL); they are converted to the C element types without any other processing."""
     keep = []
@@ -109,9 +113,12 @@ def pp_conv_plan(c_in, c_out, h, w, pattern_masks, pattern_id, conn_mask, weight
 
     d = _Desc()
     d.c_in, d.c_out, d.h, d.w, d.n_hint = int(c_in), int(c_out), int(h), int(w), int(n_hint)
-    masks = arr(pattern_masks, np.uint16)
+    wide = int(kernel_size) > 3                      # 25- and 49-bit masks travel as 64-bit words
+    masks = arr(pattern_masks, np.uint64 if wide else np.uint16)
     d.num_patterns = 0 if masks is None else int(masks.size)
-    d.pattern_masks = _ptr(masks)
+    d.pattern_masks = None if wide else _ptr(masks)
+    d.pattern_masks64 = _ptr(masks) if wide else None
+    d.kernel_size, d.stride, d.taps_per_kernel = int(kernel_size), int(stride), int(taps_per_kernel)
     d.pattern_id = _ptr(arr(pattern_id, np.int32))
     d.conn_mask = _ptr(arr(conn_mask, np.uint8))
     d.weights = _ptr(arr(weights, np.float32))
@@ -148,7 +155,7 @@ def pp_conv_plan_query(plan):
             return np.zeros(0, dtype=dt)
         return np.ctypeslib.as_array(ptr, shape=(count,)).astype(dt, copy=True)
 
-    return st, dict(c_out=co, c_in=info.c_in, num_patterns=P, taps=taps, k_kept=kk,
+    return st, dict(c_out=co, c_in=info.c_in, num_patterns=P, taps=taps, k_kept=kk, out_h=info.out_h, out_w=info.out_w,
                     perm=grab(info.perm, co, np.int32), kcount=grab(info.kcount, co, np.int32),
                     pat_off=grab(info.pat_off, co * (P + 1), np.int32).reshape(co, P + 1),
                     kidx=grab(info.kidx, kk, np.int32), kpat=grab(info.kpat, kk, np.uint8),
@@ -174,6 +181,8 @@ class Plan:
 
     def __init__(self, handle, c_in, c_out, h, w, dtype):
         self.handle, self.c_in, self.c_out, self.h, self.w, self.dtype = handle, c_in, c_out, h, w, dtype
+        info = self.query()
+        self.out_h, self.out_w = info["out_h"], info["out_w"]
 
     def query(self):
         st, info = pp_conv_plan_query(self.handle)
@@ -189,8 +198,8 @@ class Plan:
         assert x.is_cuda and x.is_contiguous() and x.dtype == tdt and tuple(x.shape[1:]) == (self.c_in, self.h, self.w)
         n = x.shape[0]
         if y is None:
-            y = torch.empty((n, self.c_out, self.h, self.w), dtype=tdt, device=x.device)
-        assert y.is_cuda and y.is_contiguous() and y.dtype == tdt and tuple(y.shape) == (n, self.c_out, self.h, self.w)
+            y = torch.empty((n, self.c_out, self.out_h, self.out_w), dtype=tdt, device=x.device)
+        assert y.is_cuda and y.is_contiguous() and y.dtype == tdt and tuple(y.shape) == (n, self.c_out, self.out_h, self.out_w)
         if stream is None:
             stream = torch.cuda.current_stream(x.device).cuda_stream
         st = (pp_conv_run_static if static else pp_conv_run)(self.handle, x.data_ptr(), y.data_ptr(), n, stream)
@@ -213,11 +222,12 @@ class Plan:
 def plan_from_layer(layer, host_only=False, tuning: Optional[Tuning] = None, n_hint: Optional[int] = None) -> Plan:
     """Plan for a layer description object (fields as in synth.Layer)."""
     flags = (PP_FLAG_RELU if layer.relu else 0) | (PP_FLAG_DENSE if layer.dense else 0) | \
-            (PP_FLAG_HOST_ONLY if host_only else 0)
+            (PP_FLAG_HOST_ONLY if host_only else 0) | (PP_FLAG_POOL2 if getattr(layer, "pool", False) else 0)
     dtype = PP_F16 if layer.dtype == "f16" else PP_F32
     st, h = pp_conv_plan(layer.c_in, layer.c_out, layer.h, layer.w, layer.pattern_masks, layer.pattern_id,
                          layer.conn_mask, layer.weights, layer.bias, flags, dtype,
-                         layer.n if n_hint is None else n_hint, tuning)
+                         layer.n if n_hint is None else n_hint, tuning, getattr(layer, "ksize", 3),
+                         getattr(layer, "stride", 1), 0 if layer.dense else layer.taps)
     if st != PP_OK:
         raise PPError(st, "pp_conv_plan")
     return Plan(h, layer.c_in, layer.c_out, layer.h, layer.w, dtype)

@@ -24,7 +24,7 @@ def run_layer(lay, x_np, tuning=None, relu=None, n_hint=None):
     plan = pp.plan_from_layer(lay, tuning=tuning, n_hint=n_hint if n_hint is not None else x_np.shape[0])
     try:
         xd = to_device(x_np)
-        yd = torch.full((x_np.shape[0], lay.c_out, lay.h, lay.w), float("nan"), dtype=xd.dtype, device="cuda")
+        yd = torch.full((x_np.shape[0], lay.c_out, plan.out_h, plan.out_w), float("nan"), dtype=xd.dtype, device="cuda")
         plan.run(xd, yd)
         torch.cuda.synchronize()
         return yd.cpu().numpy(), plan.query()["chosen"]
@@ -32,22 +32,43 @@ def run_layer(lay, x_np, tuning=None, relu=None, n_hint=None):
         plan.close()
 
 
-def check_layer(lay, x_np=None, tuning=None, relu=None, tol=None, points=4096, label=""):
-    """Compare GPU output with the checker: every element when the layer is small, sampled outputs otherwise."""
+def reference_at(lay, x_np, wd, pts, relu_flag):
+    """Checker values at sampled stored outputs pts (n, co, y, x of the stored grid).  With a fused pool a
+    stored output is the maximum of four activated convolution outputs."""
+    ksize, stride, pool = getattr(lay, "ksize", 3), getattr(lay, "stride", 1), getattr(lay, "pool", False)
+    x_np = np.ascontiguousarray(x_np)
+    if not pool:
+        if ksize == 3 and stride == 1:
+            return oracle.conv_at(x_np, wd, pts, lay.bias, relu_flag)
+        return oracle.conv_k_at(x_np, wd, pts, stride, lay.bias, relu_flag)
+    quad = np.repeat(pts, 4, axis=0)
+    quad[:, 2] = 2 * quad[:, 2] + np.tile([0, 0, 1, 1], len(pts))
+    quad[:, 3] = 2 * quad[:, 3] + np.tile([0, 1, 0, 1], len(pts))
+    y4, pre4, sc4 = oracle.conv_k_at(x_np, wd, quad.astype(np.int32), stride, lay.bias, relu_flag)
+    return y4.reshape(-1, 4).max(axis=1), pre4, sc4.reshape(-1, 4).max(axis=1)
+
+
+def check_layer(lay, x_np=None, tuning=None, relu=None, tol=None, points=4096, label="", extra_points=None):
+    """Compare GPU output with the checker: every element when the layer is small, sampled outputs otherwise
+    (random ones, corners and edges, plus extra_points: an int array [k, 4] of stored-output coordinates)."""
     if x_np is None:
         x_np = lay.make_input()
     relu_flag = lay.relu if relu is None else relu
     y, chosen = run_layer(lay, x_np, tuning, relu)
     assert not np.isnan(y.astype(np.float32)).any(), f"{label}: output has unwritten (NaN) elements"
     n = x_np.shape[0]
-    dense_macs = 9.0 * n * lay.h * lay.w * lay.c_in * lay.c_out
-    wd = oracle.layer_dense_weights(lay)
+    ksize = getattr(lay, "ksize", 3)
+    dense_macs = float(ksize * ksize) * n * lay.conv_h * lay.conv_w * lay.c_in * lay.c_out
+    assert y.shape == (n, lay.c_out, lay.out_h, lay.out_w), (y.shape, label)
     if dense_macs <= FULL_LIMIT:
-        ref, pre, scale = oracle.conv(x_np.astype(np.float64), wd, lay.bias, relu_flag, want_pre=True, want_scale=True)
+        ref, pre, scale = oracle.layer_reference(lay, x_np.astype(np.float64), relu=relu_flag)
         rep = error_report(y, ref, pre, scale)
     else:
-        pts = sample_points(n, lay.c_out, lay.h, lay.w, points, seed=lay.seed)
-        ref, pre, scale = oracle.conv_at(np.ascontiguousarray(x_np), wd, pts, lay.bias, relu_flag)
+        wd = oracle.layer_dense_weights(lay)
+        pts = sample_points(n, lay.c_out, lay.out_h, lay.out_w, points, seed=lay.seed)
+        if extra_points is not None and len(extra_points):
+            pts = np.concatenate([pts, np.asarray(extra_points, dtype=np.int32)], axis=0)
+        ref, pre, scale = reference_at(lay, x_np, wd, pts, relu_flag)
         got = y[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]]
         rep = error_report(got, ref, pre, scale)
     rep["chosen"] = chosen

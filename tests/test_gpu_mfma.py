@@ -1,0 +1,112 @@
+"""GPU parity of the matrix-core kernel (variant 3: binary16 storage, zero-filled dense weights on the
+MFMA units) against the CPU checker: ragged shapes, forced tile geometries, several filter blocks and
+channel chunks, other kernel sizes, stride 2, the fused 2x2 max-pool, pattern tables the vector kernel
+has no code for.  Tolerance 2e-3 as for every binary16 result."""
+import sys
+
+import numpy as np
+import pytest
+
+import synth
+import paper_2206_10620_amd as pp
+from gpu_util import check_layer
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def T(**kw):
+    return pp.Tuning(variant=3, **kw)
+
+
+SHAPES = [(1, 3, 5, 1, 1), (2, 5, 9, 1, 7), (3, 4, 4, 9, 1), (2, 7, 13, 7, 7), (3, 9, 10, 14, 14), (1, 6, 6, 5, 30),
+          (2, 10, 17, 11, 33), (1, 19, 8, 28, 28), (5, 8, 24, 3, 56), (1, 12, 8, 20, 130), (2, 33, 40, 6, 64),
+          (2, 40, 70, 17, 24), (1, 16, 64, 16, 64), (3, 17, 129, 9, 8), (1, 64, 64, 40, 72)]
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_ragged_shapes(shape):
+    n, c_in, c_out, h, w = shape
+    say(f"mfma ragged {shape}")
+    lay = synth.random_pruned_layer("ragged", n, c_in, c_out, h, w, "f16", synth.PSET16, 0.6, 0.3, seed=n + w)
+    for relu in (True, False):
+        rep, _ = check_layer(lay, tuning=T(), relu=relu, label=f"mfma-ragged{shape}")
+        assert rep["chosen"]["variant"] == 3
+    say(f"  E={rep['E']:.2e} {rep['chosen']}")
+
+
+TILES = [dict(tile_rows=8, tile_cols=64, tiles_per_wave=4), dict(tile_rows=16, tile_cols=32, tiles_per_wave=4),
+         dict(tile_rows=4, tile_cols=64, tiles_per_wave=2), dict(tile_rows=9, tile_cols=28, tiles_per_wave=2),
+         dict(tile_rows=36, tile_cols=14, tiles_per_wave=4), dict(tile_rows=1, tile_cols=8, tiles_per_wave=2),
+         dict(tile_rows=3, tile_cols=5, tiles_per_wave=2), dict(tile_rows=4, tile_cols=128, tiles_per_wave=4, wg_waves=4),
+         dict(tile_rows=5, tile_cols=50, tiles_per_wave=2), dict(tile_rows=64, tile_cols=8, tiles_per_wave=4)]
+
+
+@pytest.mark.parametrize("tile", TILES)
+def test_forced_tile_geometries(tile):
+    say(f"mfma tile {tile}")
+    for (n, c_in, c_out, h, w) in [(2, 21, 37, 19, 45), (3, 16, 16, 8, 8), (2, 9, 72, 11, 48), (1, 35, 20, 5, 300)]:
+        lay = synth.random_pruned_layer("tile", n, c_in, c_out, h, w, "f16", synth.PSET16, 0.5, 0.3, seed=7)
+        rep, _ = check_layer(lay, tuning=T(**tile), label=f"mfma-tile{tile}")
+        for k, v in tile.items():
+            assert rep["chosen"][k] == v
+    say(f"  E={rep['E']:.2e}")
+
+
+@pytest.mark.parametrize("ksize,taps", [(1, 1), (3, 4), (3, 2), (5, 4), (5, 9), (7, 6)])
+@pytest.mark.parametrize("stride", [1, 2])
+@pytest.mark.parametrize("pool", [False, True])
+def test_kernel_sizes_strides_and_fused_pool(ksize, taps, stride, pool):
+    say(f"mfma k={ksize} taps={taps} stride={stride} pool={pool}")
+    pset = synth.random_pattern_set(ksize, taps, 1 if ksize == 1 else 6, seed=ksize + taps)
+    for (n, c_in, c_out, h, w) in [(2, 20, 24, 16, 24), (3, 7, 70, 12, 36), (1, 33, 9, 28, 52), (2, 5, 6, 4, 4)]:
+        lay = synth.random_pruned_layer_k("gen", n, c_in, c_out, h, w, "f16", ksize, pset, 0.6, 0.3, seed=3, stride=stride,
+                                          pool=pool)
+        for relu in (True, False):
+            rep, y = check_layer(lay, tuning=T(), relu=relu, label=f"mfma-k{ksize}s{stride}p{int(pool)}")
+            assert y.shape[2:] == (lay.out_h, lay.out_w)
+    say(f"  E={rep['E']:.2e} {rep['chosen']}")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("ksize,taps,stride,pool", [(1, 1, 1, False), (3, 4, 2, False), (3, 4, 1, True), (5, 6, 2, True), (7, 5, 1, False)])
+def test_generic_kernel_takes_every_layer(dtype, ksize, taps, stride, pool):
+    pset = synth.random_pattern_set(ksize, taps, 1 if ksize == 1 else 5, seed=1)
+    lay = synth.random_pruned_layer_k("gen0", 2, 9, 11, 12, 16, dtype, ksize, pset, 0.6, 0.3, seed=4, stride=stride, pool=pool)
+    for relu in (True, False):
+        rep, _ = check_layer(lay, tuning=pp.Tuning(variant=1), relu=relu, label="generic-general")
+        assert rep["chosen"]["variant"] == 1
+    if dtype == "f32":       # without binary16 storage nothing but the generic kernel takes these layers
+        rep, _ = check_layer(lay, label="generic-general-auto")
+        assert rep["chosen"]["variant"] == (1 if (ksize != 3 or stride != 1 or pool) else rep["chosen"]["variant"])
+
+
+def test_any_pattern_table_and_dense_and_degenerate_layers():
+    foreign = np.array([0x00F, 0x1E0, 0x03A, 0x145], dtype=np.uint16)
+    lay = synth.random_pruned_layer("foreign", 2, 24, 40, 19, 33, "f16", foreign, 0.7, 0.3, seed=1)
+    rep, _ = check_layer(lay, label="mfma-foreign")
+    assert rep["chosen"]["variant"] == 3                      # the default for binary16 storage
+    lay = synth.dense_layer("dense", 2, 3, 16, 12, 20, "f16", 0.3, seed=2)
+    rep, _ = check_layer(lay, tuning=T(), label="mfma-dense")
+    import copy
+    base = synth.random_pruned_layer("deg", 2, 12, 20, 10, 12, "f16", synth.PSET8, 0.5, 0.3, seed=3)
+    lay = copy.copy(base)
+    lay.conn_mask = np.zeros_like(base.conn_mask)
+    _, y = check_layer(lay, tuning=T(), relu=False, label="mfma-empty")
+    assert np.array_equal(y, np.broadcast_to(base.bias.astype(np.float16)[None, :, None, None], y.shape))
+    lay = copy.copy(base)
+    lay.bias = None
+    check_layer(lay, tuning=T(), label="mfma-no-bias")
+
+
+def test_runs_are_bit_identical():
+    from gpu_util import run_layer
+    lay = synth.random_pruned_layer("det", 2, 48, 80, 21, 40, "f16", synth.PSET8, 0.4, 0.3, seed=9)
+    x = lay.make_input()
+    y1, _ = run_layer(lay, x, tuning=T())
+    y2, _ = run_layer(lay, x, tuning=T())
+    assert np.array_equal(y1, y2)

@@ -56,7 +56,7 @@ def test_ragged_shapes(shape, dtype):
     say(f"ragged {shape} {dtype}")
     lay = synth.random_pruned_layer("ragged", n, c_in, c_out, h, w, dtype, synth.PSET16, 0.6, 0.3, seed=n + w)
     for relu in (True, False):
-        rep, _ = check_layer(lay, relu=relu, label=f"ragged{shape}")
+        rep, _ = check_layer(lay, tuning=T(variant=2), relu=relu, label=f"ragged{shape}")
     say(f"  E={rep['E']:.2e} {rep['chosen']}")
 
 
@@ -117,7 +117,7 @@ def test_staging_paths(staging, tune, dtype):
 def test_staging_default_is_direct_when_rows_are_aligned():
     for dtype, w, want_direct in [("f32", 45, True), ("f16", 45, False), ("f16", 46, True), ("f32", 48, True)]:
         lay = synth.random_pruned_layer("stgdef", 2, 40, 24, 17, w, dtype, synth.PSET8, 0.5, 0.3, seed=5)
-        rep, _ = check_layer(lay, label=f"stgdef-{dtype}-{w}")
+        rep, _ = check_layer(lay, tuning=T(variant=2), label=f"stgdef-{dtype}-{w}")
         assert (rep["chosen"]["staging"] >= 2) == want_direct, rep["chosen"]
 
 
@@ -175,7 +175,7 @@ def test_autotune_returns_a_plan_that_passes_parity():
         assert rep["chosen"] == tuning.as_dict()               # the returned tuning reproduces the measured plan
     # plans that split channels across workgroups can be left out
     _, report2 = pp.autotune(lay, x, y, steps=2, rounds=1, allow_split_wg=False)
-    assert all(ch["split_wg"] == 1 for _, ch, _ in report2)
+    assert all(ch["split_wg"] <= 1 for _, ch, _ in report2)
 
 
 def test_degenerate_sparsity():
@@ -268,15 +268,17 @@ def test_config3_resnet_shapes(batch):
         say(f"  E={rep['E']:.2e} E_scale={rep['E_scale']:.2e} {rep['chosen']}")
 
 
-def test_config4_vgg_stack_per_layer():
+@pytest.mark.parametrize("variant", [2, 3])
+def test_config4_vgg_stack_per_layer(variant):
     """Each layer is gated on its own: the checker is fed the GPU's input to that layer."""
     layers = synth.config4()
     x = layers[0].make_input()
     xd = to_device(x)
     stream = torch.cuda.current_stream().cuda_stream
     for lay in layers:
-        say(lay.name)
-        plan = pp.plan_from_layer(lay)
+        say(f"{lay.name} variant {variant}")
+        plan = pp.plan_from_layer(lay, tuning=T(variant=variant))
+        assert plan.query()["chosen"]["variant"] == variant
         yd = plan.run(xd)
         torch.cuda.synchronize()
         plan.close()
@@ -298,10 +300,12 @@ def test_config4_vgg_stack_per_layer():
     assert tuple(xd.shape) == (8, 512, 14, 14)
 
 
-def test_config5_large_image():
+@pytest.mark.parametrize("variant", [2, 3])
+def test_config5_large_image(variant):
     lay = synth.config5()
-    say("config5")
+    say(f"config5 variant {variant}")
     x = lay.make_input()
     for relu in (True, False):
-        rep, _ = check_layer(lay, x, relu=relu, points=8192, label="cfg5")
+        rep, _ = check_layer(lay, x, tuning=T(variant=variant), relu=relu, points=8192, label="cfg5")
+        assert rep["chosen"]["variant"] == variant
     say(f"  E={rep['E']:.2e} {rep['chosen']}")

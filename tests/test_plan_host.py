@@ -128,7 +128,7 @@ def test_error_paths():
 def test_staging_choice_and_limits():
     """Input staging: direct loads need rows that start on 4-byte boundaries; the ring must fit in LDS."""
     def chosen(lay, **tune):
-        plan = pp.plan_from_layer(lay, host_only=True, tuning=pp.Tuning(variant=2, **tune) if tune else None)
+        plan = pp.plan_from_layer(lay, host_only=True, tuning=pp.Tuning(variant=2, **tune))
         ch = plan.query()["chosen"]
         plan.close()
         return ch
