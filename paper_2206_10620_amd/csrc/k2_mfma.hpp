@@ -362,47 +362,61 @@ void k2_mfma(const K2Args a) {
         __syncthreads();
     }
 
-    // ---- epilogue: bias, ReLU, binary16, through LDS as [filter][pixel slot] ----
-    _Float16* ot = reinterpret_cast<_Float16*>(smem);
-    const int op = a.out_pitch;
+    // ---- epilogue: bias, ReLU, binary16 ----
+    _Float16* __restrict__ yout = static_cast<_Float16*>(a.y);
+    if (!a.pool) {
+        // Straight from the accumulators: an MFMA result register holds one filter for 32 consecutive
+        // pixel slots (lanes 0-31; lanes 32-63 hold the filter four further on), so one store
+        // instruction writes two runs of 64 bytes, and the neighbouring column tile of the same
+        // wavefront completes the 128-byte lines a few instructions later.  The filter term of the
+        // address is wave-uniform and goes into the scalar base; everything per lane (image, row,
+        // column, the +4 filters of the upper lanes) is one 32-bit offset per column tile.
+        const int64_t fstride = (int64_t)a.ho * a.wo * 2;        // bytes between filters
+        unsigned char* ybase = reinterpret_cast<unsigned char*>(yout);
+        const bool whole_block = (fbi + 1) * kMfmaFilters <= a.c_out;
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
+        for (int nt = 0; nt < NTW; ++nt) {
+            const int slot = (wave * NTW + nt) * 32 + p;
+            const int vr = k2_div(slot, a.magic_tc), px = slot - vr * a.tc;
+            const int t = oy0 + vr, di = k2_div(t, a.magic_po);
+            const int img = oimg0 + di, oy = t - di * a.po, ox = ox0 + px;
+            const bool valid = slot < a.tr * a.tc && img < a.n && oy < a.ho && ox < a.wo;
+            const uint32_t off = (uint32_t)(((img * a.c_out + fbi * kMfmaFilters + kb * 4) * a.ho + oy) * a.wo + ox) * 2u;
+            if (valid) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int f = mt * 32 + (r >> 2) * 8 + kb * 4 + (r & 3);
-            const float bz = bias_lds[f];
+                for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-            for (int nt = 0; nt < NTW; ++nt) {
-                const int slot = (wave * NTW + nt) * 32 + p;
-                float v = acc[mt][nt][r] + bz;
-                if (a.relu) v = v > 0.0f ? v : 0.0f;
-                if (slot < op) ot[f * op + slot] = (_Float16)v;
+                    for (int r = 0; r < 16; ++r) {
+                        const int fl = mt * 32 + (r >> 2) * 8 + (r & 3);     // the lower lanes' filter inside the block
+                        float v = acc[mt][nt][r] + bias_lds[fl + kb * 4];
+                        if (a.relu) v = v > 0.0f ? v : 0.0f;
+                        if (whole_block || fbi * kMfmaFilters + fl + kb * 4 < a.c_out)
+                            *reinterpret_cast<_Float16*>(ybase + fl * fstride + off) = (_Float16)v;
+                    }
             }
         }
-    __syncthreads();
-
-    _Float16* __restrict__ yout = static_cast<_Float16*>(a.y);
-    const int gw = a.gw;
-    if (!a.pool) {
-        const int gpr = a.tc / gw;                       // groups per tile row
-        const int total = kMfmaFilters * a.tr * gpr;
-        for (int g = tid; g < total; g += NT) {
-            const int rest = k2_div(g, a.magic_gpr), cg = g - rest * gpr;
-            const int f = k2_div(rest, a.magic_srows), row = rest - f * a.tr;
-            const int co = fbi * kMfmaFilters + f;
-            const int ox = ox0 + cg * gw;
-            const int t = oy0 + row, di = k2_div(t, a.magic_po);
-            const int img = oimg0 + di, oy = t - di * a.po;
-            if (co >= a.c_out || img >= a.n || oy >= a.ho || ox >= a.wo) continue;
-            const _Float16* src = ot + f * op + row * a.tc + cg * gw;
-            _Float16* dst = yout + (((int64_t)img * a.c_out + co) * a.ho + oy) * a.wo + ox;
-            if (gw == 8) *reinterpret_cast<k2_h8*>(dst) = *reinterpret_cast<const k2_h8*>(src);
-            else if (gw == 4) *reinterpret_cast<k2_h4*>(dst) = *reinterpret_cast<const k2_h4*>(src);
-            else if (gw == 2) *reinterpret_cast<k2_h2*>(dst) = *reinterpret_cast<const k2_h2*>(src);
-            else *dst = *src;
-        }
     } else {
-        // 2x2 max-pool: tile rows and columns are even and tiles start on even rows and columns
+        // With a fused 2x2 max-pool the tile goes through LDS as [filter][pixel slot], so that the four
+        // inputs of a pooled pixel, which sit in different lanes and column tiles, meet.  Tile rows and
+        // columns are even and tiles start on even rows and columns.
+        _Float16* ot = reinterpret_cast<_Float16*>(smem);
+        const int op = a.out_pitch;
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int f = mt * 32 + (r >> 2) * 8 + kb * 4 + (r & 3);
+                const float bz = bias_lds[f];
+#pragma unroll
+                for (int nt = 0; nt < NTW; ++nt) {
+                    const int slot = (wave * NTW + nt) * 32 + p;
+                    float v = acc[mt][nt][r] + bz;
+                    if (a.relu) v = v > 0.0f ? v : 0.0f;
+                    if (slot < op) ot[f * op + slot] = (_Float16)v;
+                }
+            }
+        __syncthreads();
+        const int gw = a.gw;
         const int ptc = a.tc / 2, prows = a.tr / 2;
         const int gpr = ptc / gw;
         const int total = kMfmaFilters * prows * gpr;
