@@ -94,6 +94,11 @@ typedef struct {
     int32_t autotune;       /* 1: pp_conv_plan times the candidate variants and parameters on the device, on scratch
                                buffers of n_hint images that it allocates and frees, and keeps the fastest (the
                                "tuning-decided parameters" of section 2.3.1 decided by measurement) */
+    int32_t mfma_kind;      /* which matrix-core kernel: 0 auto; 1 the general one (tiles transposed in registers on
+                               their way into LDS; any kernel size, stride, channel count, fused pool); 2 the
+                               direct-load one (3x3, stride 1, c_in a multiple of 16, no fused pool: tiles copied
+                               memory-to-LDS as they are and transposed by the LDS read; tile_cols is then a multiple
+                               of 30 or of 14, tile_rows = 8 * 30 / tile_cols or 16 * 14 / tile_cols) */
 } pp_conv_tuning_t;
 
 /* Layer description (section 2.1.1 for the sparsity, section 2.3.1 for what the layer-wise

@@ -7,6 +7,7 @@
 
 #include "k1_tiled.hpp"
 #include "k2_mfma.hpp"
+#include "k3_mfma_direct.hpp"
 #include "plan.hpp"
 #include "pp_conv.h"
 
@@ -184,6 +185,7 @@ struct pp_conv_plan {
     uint16_t* d_wpk = nullptr;
     float* d_bias_mfma = nullptr;
     k2_launch_fn launch2 = nullptr;
+    k3_launch_fn launch3 = nullptr;
     // generic kernel
     int32_t* d_filt_off = nullptr;
     int32_t* d_kidx = nullptr;
@@ -264,8 +266,9 @@ pp_status_t pp_conv_plan(const pp_conv_desc_t* desc, pp_conv_plan_t** out_plan) 
             return PP_ERR_UNSUPPORTED;
         }
     } else if (hp.mfma) {
-        p->launch2 = k2_lookup(hp.ks, hp.stride, hp.ml.ntw, hp.ml.waves, hp.ml.pairs);
-        if (!p->launch2) {
+        if (hp.ml.direct) p->launch3 = k3_lookup(hp.ml.g3.sw);
+        else p->launch2 = k2_lookup(hp.ks, hp.stride, hp.ml.ntw, hp.ml.waves, hp.ml.pairs);
+        if (!p->launch2 && !p->launch3) {
             delete p;
             return PP_ERR_UNSUPPORTED;
         }
@@ -418,10 +421,59 @@ static pp_status_t launch_generic(const pp_conv_plan_t* plan, const void* x_dev,
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_DEVICE;
 }
 
+// One launch of the direct-load matrix-core kernel on n images.
+static pp_status_t launch_mfma_direct(const pp_conv_plan_t* plan, const void* x_dev, void* y_dev, int32_t n, hipStream_t stream) {
+    const HostPlan& hp = plan->hp;
+    const MfmaLayout& ml = hp.ml;
+    const K3Geom& g = ml.g3;
+    K3Args a{};
+    a.x = x_dev;
+    a.y = y_dev;
+    a.wpk = plan->d_wpk;
+    a.bias = plan->d_bias_mfma;
+    a.n = n;
+    a.c_in = hp.c_in;
+    a.c_out = hp.c_out;
+    a.h = hp.h;
+    a.w = hp.w;
+    a.po = ml.po;
+    a.vrows = n * ml.po - 1;
+    a.tr = g.tr;
+    a.nseg = g.nseg;
+    const int valid = g.sw - 2;
+    a.tiles_x = (hp.w + g.nseg * valid - 1) / (g.nseg * valid);
+    a.tiles_v = (a.vrows + g.tr - 1) / g.tr;
+    a.fb = ml.fb;
+    a.q = ml.q;
+    const int64_t items = (int64_t)a.tiles_x * a.tiles_v * ml.fb;
+    // piece offsets are 32-bit byte offsets (+16) from a chunk's first element
+    if (items >= ((int64_t)1 << 30) || (int64_t)n * hp.c_in * hp.h * hp.w >= ((int64_t)1 << 31) - 16) return PP_ERR_SHAPE;
+    a.work_items = (int)items;
+    a.blocks_per_xcd = (int)((items + 7) / 8);
+    a.chs = g.chs;
+    a.ppc = g.ppc;
+    a.ppcp = g.ppcp;
+    a.nxi = g.nxi;
+    a.xbuf_bytes = g.xbuf_bytes;
+    auto magic = [](int d) -> uint32_t { return d <= 1 ? 0u : (uint32_t)((((uint64_t)1) << 32) / (uint64_t)d + 1u); };
+    a.magic_ppcp = magic(g.ppcp);
+    a.magic_ppr = magic(g.nseg * (g.segb / 16));
+    a.magic_nseg = magic(g.nseg);
+    a.magic_po = magic(ml.po);
+    // the index arithmetic divides by multiplication, exact below 65536
+    if (ml.po + g.trp >= 65536) return PP_ERR_SHAPE;
+    a.relu = (hp.flags & PP_FLAG_RELU) ? 1 : 0;
+    a.x_elems = (int64_t)n * hp.c_in * hp.h * hp.w;
+    (void)hipGetLastError();
+    plan->launch3(a, a.blocks_per_xcd * 8, g.lds_bytes, stream);
+    return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_DEVICE;
+}
+
 // One launch of the matrix-core kernel on n images.
 static pp_status_t launch_mfma(const pp_conv_plan_t* plan, const void* x_dev, void* y_dev, int32_t n, hipStream_t stream) {
     const HostPlan& hp = plan->hp;
     const MfmaLayout& ml = hp.ml;
+    if (ml.direct) return launch_mfma_direct(plan, x_dev, y_dev, n, stream);
     K2Args a{};
     a.x = x_dev;
     a.y = y_dev;

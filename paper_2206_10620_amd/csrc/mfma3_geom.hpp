@@ -1,0 +1,55 @@
+// Geometry of the direct-load matrix-core kernel (k3), shared by the host-side plan, the launcher and
+// the device code.
+#pragma once
+
+#include <cstdint>
+
+namespace ppc {
+
+constexpr int kK3Waves = 4;            // wavefronts per workgroup
+constexpr int kK3ColTiles = 2;         // 32-lane MFMA column tiles per wavefront
+constexpr int kK3MaxXUnits = 5;        // input-staging instructions one wavefront issues per chunk, at most
+constexpr int kK3WeightBytes = 18 * 1024;   // operand fragments of one 16-channel chunk: 9 taps x 2 filter halves x 1 KB
+
+// A workgroup computes kK3Waves * kK3ColTiles column tiles of 32 lanes.  A column tile holds 32 / sw
+// row segments ("units") of sw computed columns, each with its own halo column on either side, so a
+// unit yields sw - 2 outputs.  The workgroup's units form a tile of tr rows x nseg segments.
+struct K3Geom {
+    int sw = 32;          // computed columns per segment (32 or 16)
+    int nseg = 1;         // segments per tile row
+    int tr = 8;           // tile rows = units / nseg
+    int units = 8;        // kK3Waves * kK3ColTiles * (32 / sw)
+    int trp = 10;         // staged input rows = tr + 2
+    int segb = 64;        // bytes per staged segment row (sw binary16 values)
+    int ppc = 40;         // 16-byte pieces per channel in LDS
+    int ppcp = 44;        // ... including padding: LDS bytes per channel / 16 (an odd multiple of 64 bytes,
+                          // so that the four channels one transposing read touches fall into different banks)
+    int chs = 704;        // LDS bytes per channel
+    int nxi = 11;         // staging instructions per chunk: ceil(16 channels * ppcp / 64 lanes)
+    int xbuf_bytes = 0;   // nxi * 1024
+    int lds_bytes = 0;    // two input buffers + two weight buffers
+    bool ok = false;
+};
+
+inline K3Geom k3_geom(int sw, int nseg) {
+    K3Geom g;
+    g.sw = sw;
+    g.nseg = nseg;
+    g.units = kK3Waves * kK3ColTiles * (32 / sw);
+    if ((sw != 32 && sw != 16) || nseg < 1 || g.units % nseg != 0) return g;
+    g.tr = g.units / nseg;
+    g.trp = g.tr + 2;
+    g.segb = sw * 2;
+    g.ppc = g.trp * nseg * g.segb / 16;
+    int blocks64 = (g.ppc * 16 + 63) / 64;
+    if ((blocks64 & 1) == 0) ++blocks64;
+    g.chs = blocks64 * 64;
+    g.ppcp = g.chs / 16;
+    g.nxi = (16 * g.ppcp + 63) / 64;
+    g.xbuf_bytes = g.nxi * 1024;
+    g.lds_bytes = 2 * g.xbuf_bytes + 2 * kK3WeightBytes;
+    g.ok = g.nxi <= kK3MaxXUnits * kK3Waves;
+    return g;
+}
+
+}  // namespace ppc

@@ -587,94 +587,144 @@ pp_status_t build_mfma_layout(const pp_conv_tuning_t& t, HostPlan& hp) {
     ml.q = (hp.c_in + kMfmaChunk - 1) / kMfmaChunk;
     ml.upq = KS <= 3 ? 1 : KS;
     ml.wbuf_bytes = (KK / ml.upq) * 2 * 1024;
+    // The direct-load kernel takes 3x3, stride-1 layers without a fused pool whose channels fill whole
+    // chunks of 16; measured on MI355X it is the faster of the two wherever it applies.
+    const bool direct_ok = KS == 3 && S == 1 && !hp.pool && hp.c_in % kMfmaChunk == 0 && hp.h + 1 + 66 < 65536;
+    if (t.mfma_kind < 0 || t.mfma_kind > 2 || (t.mfma_kind == 2 && !direct_ok)) return PP_ERR_UNSUPPORTED;
+    // A request for a tile the direct kernel has no geometry for goes to the general kernel, unless the
+    // direct one was asked for by name.
+    auto direct_layout = [&]() -> bool {
+        // Segment width: the one that computes the fewest columns per image row (a segment of sw computed
+        // columns yields sw - 2 outputs).  Segments per tile row: the divisor of the workgroup's units
+        // with the least matrix-core work (ragged last tiles) plus a quarter of the staged rows (halo).
+        const int64_t vr = (int64_t)hp.n_hint * (hp.h + 1) - 1;
+        int sw = ((hp.w + 29) / 30) * 32 <= ((hp.w + 13) / 14) * 16 ? 32 : 16;
+        int nseg = 0;
+        if (t.tile_cols) {
+            if (t.tile_cols % 30 == 0) sw = 32, nseg = t.tile_cols / 30;
+            else if (t.tile_cols % 14 == 0) sw = 16, nseg = t.tile_cols / 14;
+            else return false;
+        } else {
+            const int units = kK3Waves * kK3ColTiles * (32 / sw), spr = (hp.w + sw - 3) / (sw - 2);
+            double best = 1e300;
+            for (int ns = 1; ns <= units; ++ns) {
+                const K3Geom g = k3_geom(sw, ns);
+                if (!g.ok || (t.tile_rows && t.tile_rows != g.tr)) continue;
+                const double tiles = (double)((spr + ns - 1) / ns) * (double)((vr + g.tr - 1) / g.tr);
+                const double cost = tiles * (g.units + 0.25 * g.trp * ns);
+                if (cost < best - 1e-9) best = cost, nseg = ns;
+            }
+        }
+        const K3Geom g = k3_geom(sw, nseg);
+        if (!g.ok || (t.tile_rows && t.tile_rows != g.tr)) return false;
+        if ((t.tiles_per_wave && t.tiles_per_wave != kK3ColTiles) || (t.wg_waves && t.wg_waves != kK3Waves)) return false;
+        ml.g3 = g;
+        ml.po = hp.h + 1;
+        ml.tr = g.tr;
+        ml.tc = nseg * (sw - 2);
+        ml.ntw = kK3ColTiles;
+        ml.waves = kK3Waves;
+        ml.lds_bytes = g.lds_bytes;
+        hp.chosen.wg_waves = ml.waves;
+        hp.chosen.tile_rows = ml.tr;
+        hp.chosen.tile_cols = ml.tc;
+        hp.chosen.tiles_per_wave = ml.ntw;
+        hp.chosen.mfma_kind = 2;
+        return true;
+    };
+    ml.direct = direct_ok && t.mfma_kind != 1 && direct_layout();
+    if (t.mfma_kind == 2 && !ml.direct) return PP_ERR_UNSUPPORTED;
     // The batch is one tall virtual image: image n's output row oy is virtual row n*po + oy, and the
     // matching input rows start at virtual input row n*po*S, so that a tile may straddle images; the
     // rows between images read as zeros (they are the padding) and their outputs are not stored.
-    ml.po = hp.ho + (pad + S - 1) / S;
-    if (hp.pool && (ml.po & 1)) ++ml.po;
-    const int64_t vrows = (int64_t)hp.n_hint * ml.po - (ml.po - hp.ho);
-    const int step = hp.pool ? 2 : 1;
-    ml.pairs = (hp.w & 1) == 0;
-    auto staged_cols = [&](int tc) { return ((tc - 1) * S + KS + 2) & ~1; };
-    auto pair_groups = [&](int tr, int tc) { return (((tr - 1) * S + KS) * (staged_cols(tc) / 2) + 15) / 16; };
-    auto lds_need = [&](int tr, int tc) -> int64_t {
-        const int64_t xbuf = (int64_t)pair_groups(tr, tc) * 32 * kMfmaPixelBytes;
-        const int64_t main = 2 * xbuf + 2 * ml.wbuf_bytes;
-        const int64_t out = (int64_t)kMfmaFilters * ((tr * tc + 7) / 8 * 8) * 2;
-        return std::max(main, out) + kMfmaFilters * 4;      // + the workgroup's bias values
-    };
-    auto fits = [&](int tr, int tc, int waves, int ntw) {
-        return lds_need(tr, tc) <= kMfmaMaxDynamicLds && (pair_groups(tr, tc) + waves / 2 - 1) / (waves / 2) <= mfma_max_units(waves, ntw);
-    };
-    auto evaluate = [&](int waves, int ntw, int& btr, int& btc, int64_t& bwgs) {
-        const int slots = 32 * ntw * waves;
-        double bcost = 1e300;
-        btr = btc = 0;
-        bwgs = 0;
-        for (int tc = step; tc <= std::min(slots, (hp.wo + step - 1) / step * step); tc += step) {
-            int tr = (int)std::min<int64_t>(slots / tc, (vrows + step - 1) / step * step);
-            tr = tr / step * step;
-            while (tr >= step && !fits(tr, tc, waves, ntw)) tr -= step;
-            if (tr < step) continue;
-            const int64_t tiles = (int64_t)((hp.wo + tc - 1) / tc) * ((vrows + tr - 1) / tr);
-            const double halo = (double)((tr - 1) * S + KS) * staged_cols(tc) / ((double)tr * tc * S * S);
-            // matrix-core work of all tiles, extra for the halo's staging traffic, and a preference for
-            // wide tiles: rows are loaded and stored in pieces of tc elements, and pieces below 128 bytes
-            // waste memory transactions
-            double cost = (double)tiles * slots * (1.0 + 0.5 * (halo - 1.0)) * (1.0 + 8.0 / tc);
-            if (cost < bcost - 1e-9) {
-                bcost = cost;
-                btr = tr;
-                btc = tc;
-                bwgs = tiles * ml.fb;
+    if (!ml.direct) {
+        ml.po = hp.ho + (pad + S - 1) / S;
+        if (hp.pool && (ml.po & 1)) ++ml.po;
+        const int64_t vrows = (int64_t)hp.n_hint * ml.po - (ml.po - hp.ho);
+        const int step = hp.pool ? 2 : 1;
+        ml.pairs = (hp.w & 1) == 0;
+        auto staged_cols = [&](int tc) { return ((tc - 1) * S + KS + 2) & ~1; };
+        auto pair_groups = [&](int tr, int tc) { return (((tr - 1) * S + KS) * (staged_cols(tc) / 2) + 15) / 16; };
+        auto lds_need = [&](int tr, int tc) -> int64_t {
+            const int64_t xbuf = (int64_t)pair_groups(tr, tc) * 32 * kMfmaPixelBytes;
+            const int64_t main = 2 * xbuf + 2 * ml.wbuf_bytes;
+            const int64_t out = (int64_t)kMfmaFilters * ((tr * tc + 7) / 8 * 8) * 2;
+            return std::max(main, out) + kMfmaFilters * 4;      // + the workgroup's bias values
+        };
+        auto fits = [&](int tr, int tc, int waves, int ntw) {
+            return lds_need(tr, tc) <= kMfmaMaxDynamicLds && (pair_groups(tr, tc) + waves / 2 - 1) / (waves / 2) <= mfma_max_units(waves, ntw);
+        };
+        auto evaluate = [&](int waves, int ntw, int& btr, int& btc, int64_t& bwgs) {
+            const int slots = 32 * ntw * waves;
+            double bcost = 1e300;
+            btr = btc = 0;
+            bwgs = 0;
+            for (int tc = step; tc <= std::min(slots, (hp.wo + step - 1) / step * step); tc += step) {
+                int tr = (int)std::min<int64_t>(slots / tc, (vrows + step - 1) / step * step);
+                tr = tr / step * step;
+                while (tr >= step && !fits(tr, tc, waves, ntw)) tr -= step;
+                if (tr < step) continue;
+                const int64_t tiles = (int64_t)((hp.wo + tc - 1) / tc) * ((vrows + tr - 1) / tr);
+                const double halo = (double)((tr - 1) * S + KS) * staged_cols(tc) / ((double)tr * tc * S * S);
+                // matrix-core work of all tiles, extra for the halo's staging traffic, and a preference for
+                // wide tiles: rows are loaded and stored in pieces of tc elements, and pieces below 128 bytes
+                // waste memory transactions
+                double cost = (double)tiles * slots * (1.0 + 0.5 * (halo - 1.0)) * (1.0 + 8.0 / tc);
+                if (cost < bcost - 1e-9) {
+                    bcost = cost;
+                    btr = tr;
+                    btc = tc;
+                    bwgs = tiles * ml.fb;
+                }
             }
+        };
+        if (t.tiles_per_wave != 0 && t.tiles_per_wave != 2 && t.tiles_per_wave != 4) return PP_ERR_UNSUPPORTED;
+        if (t.wg_waves != 0 && t.wg_waves != 4 && t.wg_waves != 8) return PP_ERR_UNSUPPORTED;
+        // Larger tiles re-read less (weights once per tile, a thinner halo) and eight wavefronts hide each
+        // other's LDS and barrier latency, but the layer needs enough workgroups to fill 256 compute units.
+        static const int kShapes[3][2] = {{8, 4}, {4, 4}, {4, 2}};
+        int btr = 0, btc = 0;
+        ml.waves = 0;
+        for (int k = 0; k < 3; ++k) {
+            const int waves = kShapes[k][0], ntw = kShapes[k][1];
+            if ((t.wg_waves && t.wg_waves != waves) || (t.tiles_per_wave && t.tiles_per_wave != ntw)) continue;
+            int tr = 0, tc = 0;
+            int64_t wgs = 0;
+            evaluate(waves, ntw, tr, tc, wgs);
+            if (tr == 0) continue;
+            ml.waves = waves;
+            ml.ntw = ntw;
+            btr = tr;
+            btc = tc;
+            if (wgs >= 480) break;          // otherwise try the next smaller shape (the last one stands)
         }
-    };
-    if (t.tiles_per_wave != 0 && t.tiles_per_wave != 2 && t.tiles_per_wave != 4) return PP_ERR_UNSUPPORTED;
-    if (t.wg_waves != 0 && t.wg_waves != 4 && t.wg_waves != 8) return PP_ERR_UNSUPPORTED;
-    // Larger tiles re-read less (weights once per tile, a thinner halo) and eight wavefronts hide each
-    // other's LDS and barrier latency, but the layer needs enough workgroups to fill 256 compute units.
-    static const int kShapes[3][2] = {{8, 4}, {4, 4}, {4, 2}};
-    int btr = 0, btc = 0;
-    ml.waves = 0;
-    for (int k = 0; k < 3; ++k) {
-        const int waves = kShapes[k][0], ntw = kShapes[k][1];
-        if ((t.wg_waves && t.wg_waves != waves) || (t.tiles_per_wave && t.tiles_per_wave != ntw)) continue;
-        int tr = 0, tc = 0;
-        int64_t wgs = 0;
-        evaluate(waves, ntw, tr, tc, wgs);
-        if (tr == 0) continue;
-        ml.waves = waves;
-        ml.ntw = ntw;
-        btr = tr;
-        btc = tc;
-        if (wgs >= 480) break;          // otherwise try the next smaller shape (the last one stands)
-    }
-    if (ml.waves == 0) return PP_ERR_UNSUPPORTED;
-    ml.tr = btr;
-    ml.tc = btc;
-    if (t.tile_rows || t.tile_cols) {
-        if (t.tile_rows < step || t.tile_cols < step || t.tile_rows % step || t.tile_cols % step) return PP_ERR_UNSUPPORTED;
-        ml.tr = t.tile_rows;
-        ml.tc = t.tile_cols;
-    }
-    if (ml.tr < 1 || ml.tc < 1 || ml.tr * ml.tc > 32 * ml.ntw * ml.waves || !fits(ml.tr, ml.tc, ml.waves, ml.ntw)) return PP_ERR_UNSUPPORTED;
-    ml.trp = (ml.tr - 1) * S + KS;
-    ml.twpa = staged_cols(ml.tc);
-    ml.xbuf_bytes = pair_groups(ml.tr, ml.tc) * 32 * kMfmaPixelBytes;
-    ml.out_pitch = (ml.tr * ml.tc + 7) / 8 * 8;
-    ml.lds_bytes = lds_need(ml.tr, ml.tc);
-    const int ow = hp.out_w, otc = hp.pool ? ml.tc / 2 : ml.tc;
-    ml.gw = 1;
-    for (int g = 8; g > 1; g /= 2)
-        if (ow % g == 0 && otc % g == 0) {
-            ml.gw = g;
-            break;
+        if (ml.waves == 0) return PP_ERR_UNSUPPORTED;
+        ml.tr = btr;
+        ml.tc = btc;
+        if (t.tile_rows || t.tile_cols) {
+            if (t.tile_rows < step || t.tile_cols < step || t.tile_rows % step || t.tile_cols % step) return PP_ERR_UNSUPPORTED;
+            ml.tr = t.tile_rows;
+            ml.tc = t.tile_cols;
         }
-    hp.chosen.wg_waves = ml.waves;
-    hp.chosen.tile_rows = ml.tr;
-    hp.chosen.tile_cols = ml.tc;
-    hp.chosen.tiles_per_wave = ml.ntw;
+        if (ml.tr < 1 || ml.tc < 1 || ml.tr * ml.tc > 32 * ml.ntw * ml.waves || !fits(ml.tr, ml.tc, ml.waves, ml.ntw)) return PP_ERR_UNSUPPORTED;
+        ml.trp = (ml.tr - 1) * S + KS;
+        ml.twpa = staged_cols(ml.tc);
+        ml.xbuf_bytes = pair_groups(ml.tr, ml.tc) * 32 * kMfmaPixelBytes;
+        ml.out_pitch = (ml.tr * ml.tc + 7) / 8 * 8;
+        ml.lds_bytes = lds_need(ml.tr, ml.tc);
+        const int ow = hp.out_w, otc = hp.pool ? ml.tc / 2 : ml.tc;
+        ml.gw = 1;
+        for (int g = 8; g > 1; g /= 2)
+            if (ow % g == 0 && otc % g == 0) {
+                ml.gw = g;
+                break;
+            }
+        hp.chosen.wg_waves = ml.waves;
+        hp.chosen.tile_rows = ml.tr;
+        hp.chosen.tile_cols = ml.tc;
+        hp.chosen.tiles_per_wave = ml.ntw;
+        hp.chosen.mfma_kind = 1;
+    }
 
     // weights: scatter the kept kernels into zero-filled operand fragments
     const Canonical& cn = hp.canon;

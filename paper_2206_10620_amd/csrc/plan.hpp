@@ -9,6 +9,7 @@
 #include "pp_conv.h"
 #include "tile_geom.hpp"
 #include "mfma_geom.hpp"
+#include "mfma3_geom.hpp"
 
 namespace ppc {
 
@@ -42,6 +43,8 @@ struct TiledLayout {        // geometry of the tiled kernel for one plan
 struct MfmaLayout {
     int tr = 0, tc = 0, ntw = 0;      // workgroup tile (rows of the tall virtual image x columns) and MFMA column tiles per wavefront
     int waves = 4;                    // wavefronts per workgroup (4 or 8)
+    bool direct = false;              // the direct-load kernel (3x3, stride 1, whole chunks of 16 channels) runs this plan
+    K3Geom g3;                        // ... with this geometry
     bool pairs = true;                // even image width: input staged as aligned 32-bit pixel pairs
     int po = 0;                       // rows per image in the tall virtual output image (ho + separator rows)
     int trp = 0, twpa = 0;            // staged input rows per tile: (tr-1)*stride + K; staged columns: (tc-1)*stride + K + 2, rounded down to even

@@ -30,7 +30,7 @@ class Tuning(C.Structure):
                 ("lanes_x", C.c_int32), ("waves_f", C.c_int32), ("split_c", C.c_int32), ("chunk_c", C.c_int32),
                 ("staging", C.c_int32), ("split_wg", C.c_int32), ("balance", C.c_int32),
                 ("tile_rows", C.c_int32), ("tile_cols", C.c_int32), ("tiles_per_wave", C.c_int32),
-                ("wg_waves", C.c_int32), ("autotune", C.c_int32)]
+                ("wg_waves", C.c_int32), ("autotune", C.c_int32), ("mfma_kind", C.c_int32)]
 
     def as_dict(self):
         return {k: getattr(self, k) for k, _ in self._fields_}

@@ -110,3 +110,71 @@ def test_runs_are_bit_identical():
     y1, _ = run_layer(lay, x, tuning=T())
     y2, _ = run_layer(lay, x, tuning=T())
     assert np.array_equal(y1, y2)
+
+
+# ---- the direct-load matrix-core kernel (mfma_kind = 2): 3x3, stride 1, channels in whole chunks of 16 ----
+
+def TD(**kw):
+    return pp.Tuning(variant=3, mfma_kind=2, **kw)
+
+
+DIRECT_SHAPES = [(1, 16, 5, 1, 1), (2, 16, 9, 1, 7), (3, 32, 64, 9, 1), (2, 16, 13, 7, 7), (3, 48, 10, 14, 14), (1, 16, 6, 5, 30),
+                 (2, 32, 17, 11, 31), (1, 16, 8, 28, 28), (5, 16, 24, 3, 56), (1, 16, 70, 20, 130), (2, 32, 40, 6, 61),
+                 (2, 64, 129, 17, 29), (1, 16, 64, 16, 60), (3, 16, 8, 9, 15), (1, 64, 64, 40, 72), (2, 16, 4, 33, 2)]
+
+
+@pytest.mark.parametrize("shape", DIRECT_SHAPES)
+def test_direct_ragged_shapes(shape):
+    n, c_in, c_out, h, w = shape
+    say(f"mfma direct ragged {shape}")
+    lay = synth.random_pruned_layer("dragged", n, c_in, c_out, h, w, "f16", synth.PSET16, 0.6, 0.3, seed=n + w)
+    for relu in (True, False):
+        rep, _ = check_layer(lay, tuning=TD(), relu=relu, label=f"mfma-direct{shape}")
+        assert rep["chosen"]["variant"] == 3 and rep["chosen"]["mfma_kind"] == 2
+    say(f"  E={rep['E']:.2e} {rep['chosen']}")
+
+
+@pytest.mark.parametrize("tile_cols", [30, 60, 120, 14, 28, 56, 112])
+def test_direct_forced_tile_geometries(tile_cols):
+    say(f"mfma direct tile_cols {tile_cols}")
+    for (n, c_in, c_out, h, w) in [(2, 32, 37, 19, 45), (3, 16, 16, 8, 8), (2, 16, 72, 11, 48), (1, 48, 20, 5, 300)]:
+        lay = synth.random_pruned_layer("dtile", n, c_in, c_out, h, w, "f16", synth.PSET16, 0.5, 0.3, seed=7)
+        rep, _ = check_layer(lay, tuning=TD(tile_cols=tile_cols), label=f"mfma-direct-tile{tile_cols}")
+        assert rep["chosen"]["tile_cols"] == tile_cols and rep["chosen"]["mfma_kind"] == 2
+    say(f"  E={rep['E']:.2e} {rep['chosen']}")
+
+
+def test_direct_is_the_default_where_it_applies_and_matches_the_general_kernel():
+    from gpu_util import run_layer
+    foreign = np.array([0x00F, 0x1E0, 0x03A, 0x145], dtype=np.uint16)
+    lay = synth.random_pruned_layer("dauto", 2, 32, 40, 19, 33, "f16", foreign, 0.7, 0.3, seed=1)
+    rep, y = check_layer(lay, label="mfma-direct-auto")
+    assert rep["chosen"]["variant"] == 3 and rep["chosen"]["mfma_kind"] == 2
+    y1, chosen1 = run_layer(lay, lay.make_input(), tuning=pp.Tuning(variant=3, mfma_kind=1))
+    assert chosen1["mfma_kind"] == 1
+    # same products, summed in a different order: equal to within binary16 output rounding
+    assert np.max(np.abs(y.astype(np.float32) - y1.astype(np.float32))) <= 2e-3 * max(1.0, float(np.abs(y1).max()))
+    # layers it does not take fall to the general kernel; asking for it by name is refused
+    lay2 = synth.random_pruned_layer("dno", 1, 12, 8, 9, 9, "f16", synth.PSET8, 0.5, 0.3, seed=2)
+    rep2, _ = check_layer(lay2, tuning=pp.Tuning(variant=3), label="mfma-general-auto")
+    assert rep2["chosen"]["mfma_kind"] == 1
+    with pytest.raises(pp.PPError):
+        pp.plan_from_layer(lay2, tuning=TD())
+    # empty filters, no bias, identity activation
+    import copy
+    lay3 = copy.copy(lay)
+    lay3.conn_mask = np.zeros_like(lay.conn_mask)
+    _, y3 = check_layer(lay3, tuning=TD(), relu=False, label="mfma-direct-empty")
+    assert np.array_equal(y3, np.broadcast_to(lay.bias.astype(np.float16)[None, :, None, None], y3.shape))
+    lay4 = copy.copy(lay)
+    lay4.bias = None
+    check_layer(lay4, tuning=TD(), label="mfma-direct-no-bias")
+
+
+def test_direct_runs_are_bit_identical():
+    from gpu_util import run_layer
+    lay = synth.random_pruned_layer("ddet", 2, 48, 80, 21, 40, "f16", synth.PSET8, 0.4, 0.3, seed=9)
+    x = lay.make_input()
+    y1, _ = run_layer(lay, x, tuning=TD())
+    y2, _ = run_layer(lay, x, tuning=TD())
+    assert np.array_equal(y1, y2)
