@@ -266,7 +266,7 @@ pp_status_t pp_conv_plan(const pp_conv_desc_t* desc, pp_conv_plan_t** out_plan) 
             return PP_ERR_UNSUPPORTED;
         }
     } else if (hp.mfma) {
-        if (hp.ml.direct) p->launch3 = k3_lookup(hp.ml.g3.sw);
+        if (hp.ml.direct) p->launch3 = k3_lookup(hp.ml.g3.sw, hp.ml.g3.waves);
         else p->launch2 = k2_lookup(hp.ks, hp.stride, hp.ml.ntw, hp.ml.waves, hp.ml.pairs);
         if (!p->launch2 && !p->launch3) {
             delete p;
@@ -462,10 +462,14 @@ static pp_status_t launch_mfma_direct(const pp_conv_plan_t* plan, const void* x_
     a.magic_po = magic(ml.po);
     // the index arithmetic divides by multiplication, exact below 65536
     if (ml.po + g.trp >= 65536) return PP_ERR_SHAPE;
+    if (ml.q < k3_stages(g.waves) - 1) return PP_ERR_UNSUPPORTED;      // the kernel's pipeline fill stays inside the first tile
     a.relu = (hp.flags & PP_FLAG_RELU) ? 1 : 0;
     a.x_elems = (int64_t)n * hp.c_in * hp.h * hp.w;
     (void)hipGetLastError();
-    plan->launch3(a, a.blocks_per_xcd * 8, g.lds_bytes, stream);
+    // persistent workgroups: as many as are resident at once (16 wavefronts of this kernel per compute unit), fewer
+    // if the layer has fewer tiles
+    const int grid = std::min(a.blocks_per_xcd * 8, 256 * 8 / g.waves);
+    plan->launch3(a, grid, g.lds_bytes, stream);
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_DEVICE;
 }
 

@@ -1,23 +1,25 @@
-// Direct-load matrix-core kernel instantiations (segment widths 32 and 16) and their lookup.
+// Direct-load matrix-core kernel instantiations (segment widths 32 and 16, workgroups of 4 and 8 wavefronts) and their lookup.
 #include "k3_mfma_direct.hpp"
 
 namespace ppc {
 namespace {
 
-template <int SW>
+template <int SW, int WAVES>
 void launch(const K3Args& a, int blocks, int lds_bytes, hipStream_t stream) {
     // the kernel may use more than the default 64 KB of dynamic LDS; set once per instantiation
-    static const hipError_t lds_attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&k3_mfma<SW>),
+    static const hipError_t lds_attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&k3_mfma<SW, WAVES>),
                                                            hipFuncAttributeMaxDynamicSharedMemorySize, kMfmaMaxDynamicLds);
     (void)lds_attr;
-    hipLaunchKernelGGL((k3_mfma<SW>), dim3(blocks), dim3(64 * kK3Waves), lds_bytes, stream, a);
+    hipLaunchKernelGGL((k3_mfma<SW, WAVES>), dim3(blocks), dim3(64 * WAVES), lds_bytes, stream, a);
 }
 
 }  // namespace
 
-k3_launch_fn k3_lookup(int sw) {
-    if (sw == 32) return launch<32>;
-    if (sw == 16) return launch<16>;
+k3_launch_fn k3_lookup(int sw, int waves) {
+    if (sw == 32 && waves == 4) return launch<32, 4>;
+    if (sw == 16 && waves == 4) return launch<16, 4>;
+    if (sw == 32 && waves == 8) return launch<32, 8>;
+    if (sw == 16 && waves == 8) return launch<16, 8>;
     return nullptr;
 }
 

@@ -28,11 +28,26 @@
 // column of the accumulators, so the two places where such a column would leak into a stored output
 // (input column -1 through P_0, input column W through P_2) are cleared in the accumulators instead.
 // Rows outside the images (padding and the separator row between two images of the batch) are never
-// loaded; their places in LDS are zeroed once per workgroup.
+// loaded; their places in LDS are zeroed whenever a ring place is filled for a tile that has such rows.
+//
+// Time.  On this chip a SIMD's vector ALU and its matrix core do not run side by side (measured: a
+// wavefront of FMAs and a wavefront of MFMAs on one SIMD take the sum of their times), so every vector
+// instruction is time taken from the MFMAs, and the kernel is written to have few of them:
+//   * workgroups are persistent and walk through their tiles; the steps (chunk after chunk, tile after
+//     tile) are staged one or two ahead into a ring of LDS buffers, with the load instructions dealt out
+//     between the MFMAs of the step before and awaited by count (loads return in order);
+//   * what a lane fetches is worked out once per tile from per-lane constants kept in LDS, at the head
+//     of the tile before, and parked in LDS until the ring gets there (registers are short: 192 of 256
+//     are accumulators);
+//   * the bias arrives by a direct load and enters as the C operand of a tile's first MFMAs;
+//   * the epilogue turns the outputs round through LDS so that one store instruction writes 64-byte runs
+//     of 16 filters: a store costs the same whether a lane carries 2 or 16 bytes.
 #pragma once
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <type_traits>
 
 #include "mfma3_geom.hpp"
 #include "mfma_geom.hpp"
@@ -59,9 +74,12 @@ struct K3Args {
 };
 
 typedef __fp16 k3_hh4 __attribute__((__vector_size__(4 * sizeof(__fp16))));
+typedef _Float16 k3_h2 __attribute__((ext_vector_type(2)));
 typedef _Float16 k3_h4 __attribute__((ext_vector_type(4)));
 typedef _Float16 k3_h8 __attribute__((ext_vector_type(8)));
+typedef float k3_f2 __attribute__((ext_vector_type(2)));
 typedef float k3_f16 __attribute__((ext_vector_type(16)));
+typedef uint32_t k3_u3 __attribute__((ext_vector_type(3)));
 typedef uint32_t k3_u4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) unsigned char* k3_lds_ptr;
 
@@ -74,11 +92,39 @@ template <typename P> __device__ __forceinline__ P* k3_uniform_ptr(P* p) {
     return (P*)(uintptr_t)(((uint64_t)hi << 32) | lo);
 }
 
-// One direct load: every active lane fetches 16 bytes at base + off into LDS at lds_dst + 16 * lane.
+// One direct load: every active lane fetches 16 (or 4) bytes at base + off into LDS at lds_dst + 16 (4) * lane.
 // Inline assembly rather than the compiler builtin: the compiler cannot tell which buffer an
 // in-flight direct load fills and would make the first LDS read after it wait for all of them.
 __device__ __forceinline__ void k3_dma16(uint32_t off, const void* base, uint32_t lds_dst) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(lds_dst) : "memory", "m0");
+}
+__device__ __forceinline__ void k3_dma4(uint32_t off, const void* base, uint32_t lds_dst) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(off), "s"(base), "s"(lds_dst) : "memory", "m0");
+}
+
+// A staged piece that reaches outside the tensor (the halo column in front of the very first row, the
+// columns behind the very last one): eight guarded element loads, zeros outside.  Rare; kept out of line.
+__device__ __attribute__((noinline)) void k3_edge_piece(const uint16_t* x, int64_t e0, int64_t n_elems, unsigned char* lds_dst) {
+    uint32_t v[4];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const int64_t idx = e0 + e;
+        const uint32_t bits = (idx >= 0 && idx < n_elems) ? (uint32_t)x[idx] : 0u;
+        v[e >> 1] = (e & 1) ? (v[e >> 1] | (bits << 16)) : bits;
+    }
+    k3_u4 v4;
+    v4.x = v[0], v4.y = v[1], v4.z = v[2], v4.w = v[3];
+    *reinterpret_cast<k3_u4*>(lds_dst) = v4;
+}
+
+// s_waitcnt vmcnt(n) for a wave-uniform n (0..10; anything else waits for everything)
+__device__ __forceinline__ void k3_wait_vm(int n) {
+    switch (n) {
+#define PPC_K3_W(N) case N: asm volatile("s_waitcnt vmcnt(" #N ")" ::: "memory"); break;
+        PPC_K3_W(1) PPC_K3_W(2) PPC_K3_W(3) PPC_K3_W(4) PPC_K3_W(5) PPC_K3_W(6) PPC_K3_W(7) PPC_K3_W(8) PPC_K3_W(9) PPC_K3_W(10)
+#undef PPC_K3_W
+        default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+    }
 }
 
 // lane i <- lane i + 1 over the whole wavefront (the last lane receives 0)
@@ -86,104 +132,196 @@ __device__ __forceinline__ float k3_shl1(float v) {
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x130, 0xf, 0xf, true));
 }
 
-template <int SW>
-__global__ __launch_bounds__(64 * kK3Waves) __attribute__((amdgpu_waves_per_eu(2, 2)))
+template <int SW, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void k3_mfma(const K3Args a) {
-    constexpr int NT = kK3ColTiles, WAVES = kK3Waves, UPT = 32 / SW, SEGB = SW * 2, PPS = SEGB / 16, VALID = SW - 2;
-    constexpr int MAXX = kK3MaxXUnits;
+    constexpr int NT = kK3ColTiles, UPT = 32 / SW, SEGB = SW * 2, PPS = SEGB / 16, VALID = SW - 2;
+    constexpr int MAXX = k3_max_x_units(WAVES);
+    constexpr int NS = k3_stages(WAVES);             // ring of staged steps
     constexpr int NWU = 18, WU = (NWU + WAVES - 1) / WAVES;
+    constexpr int NL = 64 * WAVES;                   // lanes of the workgroup
+    static_assert(WU + MAXX <= 9, "one staging slot per tap");
     extern __shared__ __align__(16) unsigned char smem[];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
-    // block -> work item, XCD-aware: consecutive block ids go round-robin to the 8 XCDs, so each XCD
-    // gets a contiguous range of items (filter block fastest, then tile column, then tile row) and
-    // workgroups that read the same or neighbouring input tiles share an L2.
-    int item = (int)(blockIdx.x % 8u) * a.blocks_per_xcd + (int)(blockIdx.x / 8u);
-    if (item >= a.work_items) return;
-    const int fbi = item % a.fb;
-    item /= a.fb;
-    const int tx = item % a.tiles_x;
-    const int tv = item / a.tiles_x;
-    const int ox0 = tx * a.nseg * VALID;            // first output column of the tile
-    const int v0 = tv * a.tr;                       // first virtual output row
-    const int u0 = v0 - 1;                          // virtual input row held by staged row 0
-    const int hw = a.h * a.w;
-    // image and row inside it of staged row 0 (u0 = -1 belongs to "image -1")
-    const int img0 = (u0 + a.po) / a.po - 1, iy0 = u0 - img0 * a.po;
-    const int oimg0 = v0 / a.po, oy0 = v0 - oimg0 * a.po;
+    // Workgroups are persistent: the grid holds as many as are resident at once, and each walks through
+    // its share of the work items (filter block fastest, then tile column, then tile row).  Block ids go
+    // round-robin to the 8 XCDs, so XCD i gets the contiguous item range [i * blocks_per_xcd, ...) and
+    // its workgroups take the items of that range in turn: at any moment an XCD works on neighbouring
+    // tiles, which share input rows, and its L2 sees them together.
+    const int xcd = (int)(blockIdx.x % 8u), slot = (int)(blockIdx.x / 8u), gslots = (int)(gridDim.x / 8u);
+    const int first_item = xcd * a.blocks_per_xcd;
+    const int left = a.work_items - first_item, avail = left < a.blocks_per_xcd ? left : a.blocks_per_xcd;
+    const int my_n = avail > slot ? (avail - slot + gslots - 1) / gslots : 0;
+    if (my_n == 0) return;
 
+    const int hw = a.h * a.w;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(k3_lds_ptr)smem;
     const int xb_bytes = a.xbuf_bytes;
     const int rowb = a.nseg * SEGB;                 // LDS bytes per staged row of one channel
     const _Float16* __restrict__ xin = static_cast<const _Float16*>(a.x);
+    // LDS behind the ring: per wavefront 64 bias values and a [32 filters][32 columns] binary16 tile for
+    // the epilogue; per lane the parked staging set of the next tile and the lane's staging constants
+    const int corner0 = NS * (xb_bytes + kK3WeightBytes);
+    float* bias_lds = reinterpret_cast<float*>(smem + corner0) + wave * kMfmaFilters;
+    unsigned char* tb = smem + corner0 + WAVES * kMfmaFilters * 4 + wave * 2048;
+    uint32_t* park = reinterpret_cast<uint32_t*>(smem + corner0 + WAVES * (kMfmaFilters * 4 + 2048)) + tid;   // [MAXX + 1][NL]
+    uint32_t* lconst = park + (MAXX + 1) * NL;                                                                  // [2 * MAXX][NL]
 
-    // ---- staging set-up: which piece each lane fetches in each of this wavefront's instructions ----
-    // Instruction `it` fills LDS bytes [1024 it, 1024 it + 1024) of a buffer; piece g = 64 it + lane is
-    // piece g % ppcp of channel g / ppcp.  xoff = byte offset of the piece from (chunk base - 16 bytes):
-    // the piece that holds input column -1 of a row starts 2 bytes before that row.
-    uint32_t xoff[MAXX];
-    uint32_t okmask = 0u;                           // bit k: the lane fetches a piece in its k-th instruction
+    // ---- staging: which piece each lane fetches in each of this wavefront's instructions ----
+    // Instruction `it` fills LDS bytes [1024 it, 1024 it + 1024) of a ring place; piece g = 64 it + lane is
+    // piece g % ppcp of channel g / ppcp.  What does not depend on the tile is worked out here, once:
+    // the piece's element offset from (channel 0, image 0, row 0, the tile's first output column), and its
+    // staged row and first column relative to the tile (bit 31: no place of the tile, padding).
     const int nx = wave < a.nxi ? (a.nxi - wave + WAVES - 1) / WAVES : 0;
+    const int nwu = (NWU - wave + WAVES - 1) / WAVES;                     // weight instructions of this wavefront per step
 #pragma unroll
     for (int k = 0; k < MAXX; ++k) {
-        xoff[k] = 16u;
-        if (k < nx) {
-            const int g = (wave + WAVES * k) * 64 + lane;
-            const int ch = k3_div(g, a.magic_ppcp), pr = g - ch * a.ppcp;
-            const int srow = k3_div(pr, a.magic_ppr), rem = pr - srow * (a.nseg * PPS);
-            const int seg = rem / PPS, piece = rem - seg * PPS;
-            const int t = iy0 + srow, di = k3_div(t, a.magic_po);
-            const int img = img0 + di, iy = t - di * a.po;
-            const int col = ox0 + seg * VALID - 1 + piece * 8;       // input column of the piece's first pixel
-            const bool ok = ch < kMfmaChunk && pr < a.ppc && img >= 0 && img < a.n && iy < a.h && col < a.w;
-            if (ok) {
-                xoff[k] = (uint32_t)(16 + 2 * (((img * a.c_in + ch) * a.h + iy) * a.w + col));
-                okmask |= 1u << k;
-            } else {
-                // a place no load ever writes: zero it in both buffers, once
-                *reinterpret_cast<k3_u4*>(smem + (wave + WAVES * k) * 1024 + lane * 16) = k3_u4(0u);
-                *reinterpret_cast<k3_u4*>(smem + xb_bytes + (wave + WAVES * k) * 1024 + lane * 16) = k3_u4(0u);
-            }
-        }
+        const int g = (wave + WAVES * k) * 64 + lane;
+        const int ch = k3_div(g, a.magic_ppcp), pr = g - ch * a.ppcp;
+        const int srow = k3_div(pr, a.magic_ppr), rem = pr - srow * (a.nseg * PPS);
+        const int seg = rem / PPS, piece = rem - seg * PPS;
+        const int colrel = seg * VALID - 1 + piece * 8;                   // first column of the piece, from the tile's first output column
+        const bool place = k < nx && ch < kMfmaChunk && pr < a.ppc;
+        lconst[(2 * k) * NL] = (uint32_t)(ch * hw + colrel);
+        lconst[(2 * k + 1) * NL] = place ? (uint32_t)(srow | ((colrel + 1) << 8)) : 0x80000000u;
     }
 
-    // Start the loads of chunk qi into buffer `buf`.  Nothing here waits.
-    auto issue = [&](int qi, int buf) {
-        const int64_t chunk_elem0 = (int64_t)qi * kMfmaChunk * hw;
-        const unsigned char* xbase = k3_uniform_ptr(reinterpret_cast<const unsigned char*>(xin + chunk_elem0) - 16);
-        const uint32_t ldsx = lds0 + (uint32_t)(buf * xb_bytes);
+    // tile coordinates of a work item (wave-uniform)
+    auto decode = [&](int item, int& fbi_o, int& ox0_o, int& v0_o) {
+        fbi_o = item % a.fb;
+        item /= a.fb;
+        const int tx = item % a.tiles_x, tv = item / a.tiles_x;
+        ox0_o = tx * a.nseg * VALID;
+        v0_o = tv * a.tr;
+    };
+
+    // Per tile: the offset of each of the lane's pieces and what is to be done with it.
+    uint32_t xoff[MAXX];                            // byte offset of the lane's k-th piece from (first element of the chunk's channel 0) - 16
+    uint32_t cls = 0u;                              // bit k: fetch; 4+k: zero instead (outside the images); 8+k / 12+k: the piece
+                                                    // reaches below / beyond the tensor in the first / last chunk
+    bool any_hole = false, any_edge = false;        // wave-uniform
+    int fbi_s = 0;                                  // filter block of the tile being staged
+    const int last_chunk_elems = (int)(a.x_elems - (int64_t)(a.q - 1) * kMfmaChunk * hw);   // the tensor has fewer than 2^31 elements
+    // The set of the workgroup's next tile is worked out at the head of a tile, while the accumulators are
+    // not yet in use, and parked in this lane's own words of LDS until the ring gets there.
+    auto setup_tile = [&](int item) {
+        int ox0, v0, fbi_n;
+        decode(item, fbi_n, ox0, v0);
+        const int u0 = v0 - 1;                                            // virtual input row of staged row 0
+        const int img0 = (u0 + a.po) / a.po - 1, iy0 = u0 - img0 * a.po;  // u0 = -1 belongs to "image -1"
+        const int img_hw = a.c_in * hw;
+        uint32_t cls_n = 0u;
 #pragma unroll
         for (int k = 0; k < MAXX; ++k) {
-            if (k < nx) {
-                const bool ok = (okmask >> k) & 1u;
-                // A piece may reach a few bytes outside the tensor at its two ends (the halo column of the
-                // very first row, the columns past the very last row): those lanes assemble their piece
-                // from guarded element loads instead.
-                const int64_t e0 = chunk_elem0 + ((int64_t)xoff[k] - 16) / 2;
-                const bool edge = ok && (e0 < 0 || e0 + 8 > a.x_elems);
-                if (ok && !edge) k3_dma16(xoff[k], xbase, ldsx + (uint32_t)((wave + WAVES * k) * 1024));
-                if (__builtin_amdgcn_ballot_w64(edge) != 0) {
-                    if (edge) {
-                        k3_h8 v;
+            const int cbase = (int)lconst[(2 * k) * NL], crow = (int)lconst[(2 * k + 1) * NL];
+            const int t = iy0 + (crow & 255), di = k3_div(t, a.magic_po);
+            const int img = img0 + di, iy = t - di * a.po;
+            const bool place = crow >= 0;
+            const bool ok = place && img >= 0 && img < a.n && iy < a.h && ox0 + ((crow >> 8) & 0xFFFF) - 1 < a.w;
+            // the piece that holds input column -1 of a row starts 2 bytes before that row, and offsets must
+            // not be negative: they count from 16 bytes before the chunk's first element
+            const int e0 = img * img_hw + iy * a.w + ox0 + cbase;        // first element, relative to the chunk (-1 at the earliest)
+            uint32_t xo = 16u;                                            // padding lanes fetch the chunk's first bytes (in bounds, never read)
+            if (ok) {
+                xo = 16u + 2u * (uint32_t)e0;
+                cls_n |= 1u << k;
+                if (e0 < 0) cls_n |= 256u << k;
+                if (e0 + 8 > last_chunk_elems) cls_n |= 4096u << k;
+            } else if (place) {
+                cls_n |= 16u << k;
+            }
+            park[k * NL] = xo;
+        }
+        park[MAXX * NL] = cls_n;
+    };
+    auto take_tile = [&](int item) {                // the parked set becomes the staged tile
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) {
-                            const int64_t idx = e0 + e;
-                            v[e] = (idx >= 0 && idx < a.x_elems) ? xin[idx] : (_Float16)0.0f;
-                        }
-                        *reinterpret_cast<k3_h8*>(smem + buf * xb_bytes + (wave + WAVES * k) * 1024 + lane * 16) = v;
-                    }
+        for (int k = 0; k < MAXX; ++k) xoff[k] = park[k * NL];
+        cls = park[MAXX * NL];
+        any_hole = __builtin_amdgcn_ballot_w64((cls & 0xF0u) != 0u) != 0;
+        any_edge = __builtin_amdgcn_ballot_w64((cls & 0xFF00u) != 0u) != 0;
+        fbi_s = item % a.fb;
+    };
+
+    // The loads of one step (chunk qi of the staged tile, into ring place `buf`) are WU weight instructions
+    // and up to MAXX input instructions per wavefront, plus the tile's bias values with its first chunk:
+    // nine "slots", issued one per tap of an earlier step, so that the address unit works through them
+    // while the matrix cores run.  Nothing here waits.
+    struct Step {
+        const unsigned char* wbase;
+        const unsigned char* xbase;
+        const float* bbase;
+        uint32_t ldsw, ldsx, edge_bits;
+        int64_t chunk_elem0;
+        int buf;
+        int count;                                  // load instructions this wavefront issues for the step
+        bool on;
+        bool plain;                                 // every lane of every input instruction fetches (no place outside the images, no piece outside the tensor)
+        bool bias;                                  // the tile's first chunk: the bias values come along
+    };
+    const uint32_t lane16 = (uint32_t)(lane * 16);
+    auto begin_step = [&](int qi, int buf) {
+        Step st;
+        st.on = true;
+        st.buf = buf;
+        st.wbase = k3_uniform_ptr(static_cast<const unsigned char*>(a.wpk) + ((int64_t)fbi_s * a.q + qi) * kK3WeightBytes + wave * 1024);
+        st.ldsw = lds0 + (uint32_t)(NS * xb_bytes + buf * kK3WeightBytes + wave * 1024);
+        st.chunk_elem0 = (int64_t)qi * kMfmaChunk * hw;
+        st.xbase = k3_uniform_ptr(reinterpret_cast<const unsigned char*>(xin + st.chunk_elem0) - 16);
+        st.ldsx = lds0 + (uint32_t)(buf * xb_bytes + wave * 1024);
+        st.bias = qi == 0;
+        st.bbase = k3_uniform_ptr(a.bias + fbi_s * kMfmaFilters);
+        st.plain = !(any_edge || any_hole);
+        st.edge_bits = 0u;
+        st.count = nwu + nx + (st.bias ? 1 : 0);
+        if (!st.plain) {
+            // A piece may reach a few bytes outside the tensor at its two ends (the halo column of the very
+            // first row, the columns past the very last row): those lanes assemble their piece from guarded
+            // element loads instead.  Only the first and the last chunk can have such pieces.
+            st.edge_bits = !any_edge ? 0u : ((qi == 0 ? (cls >> 8) & 15u : 0u) | (qi == a.q - 1 ? (cls >> 12) & 15u : 0u));
+            // an instruction is issued if any lane takes part in it: count them the way issue_slot decides
+            st.count = nwu + (st.bias ? 1 : 0);
+#pragma unroll
+            for (int k = 0; k < MAXX; ++k)
+                if (k < nx && __builtin_amdgcn_ballot_w64(((cls >> k) & 1u) && !((st.edge_bits >> k) & 1u)) != 0) ++st.count;
+        }
+        return st;
+    };
+    auto issue_slot = [&](const Step& st, int j) {          // j = 0 .. 8, a compile-time constant at every call
+        if (!st.on) return;
+        if (j < WU) {
+            if (wave + WAVES * j < NWU) k3_dma16(lane16, st.wbase + WAVES * j * 1024, st.ldsw + (uint32_t)(WAVES * j * 1024));
+        } else if (j - WU < MAXX) {
+            const int k = j - WU;
+            if (k < nx) {
+                if (st.plain) {
+                    // almost every tile: all 64 lanes fetch
+                    k3_dma16(xoff[k], st.xbase, st.ldsx + (uint32_t)(WAVES * k * 1024));
+                } else {
+                    // (the branch is on the wavefront's vote, so that the instruction count is what begin_step says)
+                    const bool mine = ((cls >> k) & 1u) && !((st.edge_bits >> k) & 1u);
+                    if (__builtin_amdgcn_ballot_w64(mine) != 0 && mine) k3_dma16(xoff[k], st.xbase, st.ldsx + (uint32_t)(WAVES * k * 1024));
                 }
             }
         }
-        const unsigned char* wbase = k3_uniform_ptr(static_cast<const unsigned char*>(a.wpk) + ((int64_t)fbi * a.q + qi) * kK3WeightBytes);
-        const uint32_t ldsw = lds0 + (uint32_t)(2 * xb_bytes + buf * kK3WeightBytes);
+        // the last slot also brings this wavefront's copy of the tile's 64 bias values
+        if (j == 8 && st.bias) k3_dma4(lane16 >> 2, st.bbase, lds0 + (uint32_t)(corner0 + wave * kMfmaFilters * 4));
+    };
+    auto finish_step = [&](const Step& st) {                 // the rare pieces that are not plain loads
+        if (!st.on || st.plain) return;
 #pragma unroll
-        for (int k = 0; k < WU; ++k) {
-            const int unit = wave + WAVES * k;
-            if (unit < NWU) k3_dma16((uint32_t)(unit * 1024 + lane * 16), wbase, ldsw + (uint32_t)(unit * 1024));
+        for (int k = 0; k < MAXX; ++k) {
+            if (k < nx) {
+                unsigned char* mine = smem + st.buf * xb_bytes + (wave + WAVES * k) * 1024 + lane * 16;
+                if ((st.edge_bits >> k) & 1u)
+                    k3_edge_piece(reinterpret_cast<const uint16_t*>(xin), st.chunk_elem0 + ((int64_t)(int32_t)(xoff[k] - 16u)) / 2, a.x_elems, mine);
+                // a place outside the images would keep whatever the ring place's last tile left there
+                if ((cls >> (4 + k)) & 1u) *reinterpret_cast<k3_u4*>(mine) = k3_u4(0u);
+            }
         }
     };
 
@@ -197,99 +335,221 @@ void k3_mfma(const K3Args a) {
         const int row = k3_div(ui, a.magic_nseg), seg = ui - row * a.nseg;
         baddr[nt] = (uint32_t)((8 * (blk >> 1) + jch) * a.chs + row * rowb + seg * SEGB + (p0 % SW) * 2);
     }
+    const bool wide_ok = (a.w & 1) == 0;             // rows start on 4-byte boundaries
 
     // ---- accumulators: three tap columns x two filter halves x NT column tiles ----
-    // The bias starts out in the centre column's set (lane halves hold filters 4 apart).
-    const int p = lane & 31, kb = lane >> 5;
     k3_f16 acc[3][2][NT];
-#pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const float bz = a.bias[fbi * kMfmaFilters + mt * 32 + (r >> 2) * 8 + kb * 4 + (r & 3)];
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                acc[0][mt][nt][r] = 0.0f;
-                acc[1][mt][nt][r] = bz;
-                acc[2][mt][nt][r] = 0.0f;
-            }
-        }
 
-    // ---- main loop over chunks of 16 channels ----
-    issue(0, 0);
-    for (int qi = 0; qi < a.q; ++qi) {
-        // this wavefront's loads of chunk qi have landed (and its zero fills and edge pieces are written);
-        // after the barrier everyone's have, and everyone is done reading the other buffer
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        if (qi + 1 < a.q) issue(qi + 1, (qi + 1) & 1);
-
-        const uint32_t xb = lds0 + (uint32_t)((qi & 1) * xb_bytes);
-        const unsigned char* wb = smem + 2 * xb_bytes + (qi & 1) * kK3WeightBytes + lane * 16;
+    // Steps (chunk after chunk, tile after tile) are staged NS - 1 ahead of the step being multiplied.
+    int ik = 0, iq = 0, ibuf = 0;                   // the next step to stage: tile, chunk, ring place
+    int young = 0;                                  // load instructions issued after those of the step that is waited for next
+    auto advance_issue = [&]() {
+        ibuf = ibuf + 1 == NS ? 0 : ibuf + 1;
+        if (++iq == a.q) iq = 0, ++ik;
+    };
+    setup_tile(first_item + slot);
+    take_tile(first_item + slot);
+    // fill the pipeline with the first NS - 1 steps (all of the first tile: the launcher sees to it that a
+    // tile has at least NS - 1 chunks)
 #pragma unroll
-        for (int r = 0; r < 3; ++r) {
-            k3_h8 bf[NT];
+    for (int d = 0; d < NS - 1; ++d) {
+        const Step st0 = begin_step(iq, ibuf);
+#pragma unroll
+        for (int j = 0; j < 9; ++j) issue_slot(st0, j);
+        finish_step(st0);
+        if (d > 0) young += st0.count;
+        advance_issue();
+    }
+
+    // One step: multiply the chunk in ring place sbuf, and deal out the loads of step `nxt` between the taps.
+    // FIRST: the tile's first chunk, whose MFMAs start the accumulators (the centre column's from the bias).
+    auto multiply = [&](auto first_tag, int sbuf, const Step& nxt) {
+        constexpr bool FIRST = decltype(first_tag)::value;
+        const uint32_t xb = lds0 + (uint32_t)(sbuf * xb_bytes);
+        const unsigned char* wb = smem + NS * xb_bytes + sbuf * kK3WeightBytes + lane * 16;
+        // Operand fragments are read one tap ahead into a second set of registers, so that the LDS latency
+        // of tap t + 1 hides behind the four MFMAs of tap t; the input operand changes with the tap row only.
+        k3_h8 af[2][2], bf[2][NT];
+        auto read_a = [&](int set, int t) {
+            af[set][0] = *reinterpret_cast<const k3_h8*>(wb + (t * 2 + 0) * 1024);
+            af[set][1] = *reinterpret_cast<const k3_h8*>(wb + (t * 2 + 1) * 1024);
+        };
+        auto read_b = [&](int set, int r) {
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
                 const uint32_t ad = xb + baddr[nt] + (uint32_t)(r * rowb);
                 const k3_hh4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4f16(reinterpret_cast<__attribute__((address_space(3))) k3_hh4*>(ad));
                 const k3_hh4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4f16(reinterpret_cast<__attribute__((address_space(3))) k3_hh4*>(ad + (uint32_t)(4 * a.chs)));
                 const k3_h4 l4 = __builtin_bit_cast(k3_h4, lo), h4 = __builtin_bit_cast(k3_h4, hi);
-                bf[nt] = __builtin_shufflevector(l4, h4, 0, 1, 2, 3, 4, 5, 6, 7);
+                bf[set][nt] = __builtin_shufflevector(l4, h4, 0, 1, 2, 3, 4, 5, 6, 7);
+            }
+        };
+        read_b(0, 0);
+        read_a(0, 0);
+        k3_f16 cb[2];                               // FIRST: the bias in accumulator order (an accumulator register holds one filter)
+        if constexpr (FIRST) {
+            const int kb = lane >> 5;
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const float4 b4 = *reinterpret_cast<const float4*>(bias_lds + mt * 32 + g * 8 + kb * 4);
+                    cb[mt][g * 4 + 0] = b4.x, cb[mt][g * 4 + 1] = b4.y, cb[mt][g * 4 + 2] = b4.z, cb[mt][g * 4 + 3] = b4.w;
+                }
+        }
+#pragma unroll
+        for (int t = 0; t < 9; ++t) {
+            const int r = t / 3, c = t % 3;
+            if (t + 1 < 9) {
+                read_a((t + 1) & 1, t + 1);
+                if ((t + 1) % 3 == 0) read_b(((t + 1) / 3) & 1, (t + 1) / 3);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt) {
+                    k3_f16 cin;
+                    if (FIRST && r == 0) {
+                        if (c == 1) cin = cb[mt];
+                        else
+#pragma unroll
+                            for (int e = 0; e < 16; ++e) cin[e] = 0.0f;
+                    } else {
+                        cin = acc[c][mt][nt];
+                    }
+                    acc[c][mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[t & 1][mt], bf[r & 1][nt], cin, 0, 0, 0);
+                }
+            issue_slot(nxt, t);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    int sbuf = 0;                                   // ring place of the current step
+    for (int kt = 0; kt < my_n; ++kt) {
+        const int item_c = first_item + slot + kt * gslots;
+        if (kt + 1 < my_n) setup_tile(item_c + gslots);
+        __builtin_amdgcn_sched_barrier(0);
+
+        // ---- main loop over chunks of 16 channels ----
+        for (int qi = 0; qi < a.q; ++qi) {
+            // This wavefront's loads of the current step have landed (and its zero fills and edge pieces are
+            // written); after the barrier everyone's have, and everyone is done reading the ring place that
+            // is filled next.  Loads return in order: all but the `young` most recent instructions are
+            // awaited (stores of an epilogue in between only make the wait longer than needed).
+            k3_wait_vm(young);
+            __syncthreads();
+            // the step to stage now: NS - 1 after the current one
+            Step nxt;
+            nxt.on = false;
+            if (ik < my_n) {
+                if (iq == 0) take_tile(first_item + slot + ik * gslots);   // parked at the head of tile ik - 1
+                nxt = begin_step(iq, ibuf);
+                advance_issue();
+            }
+            young = NS > 2 ? (nxt.on ? nxt.count : 0) : 0;
+            if (qi == 0) multiply(std::true_type{}, sbuf, nxt);
+            else multiply(std::false_type{}, sbuf, nxt);
+            finish_step(nxt);
+            sbuf = sbuf + 1 == NS ? 0 : sbuf + 1;
+        }
+
+        // ---- epilogue: combine the three tap columns, ReLU, binary16, store ----
+        // An accumulator register holds one filter for the 32 columns of a column tile (lanes 0-31; lanes
+        // 32-63 hold the filter four further on).  Output o of a segment sits in lane o: its own P_0, the
+        // next lane's P_1 (which carries the bias), the P_2 two lanes on.  Pairs of registers (two filters of
+        // one column) are converted together and written as two 16-bit halves into this wavefront's
+        // [32 filters][32 columns] corner of LDS; read back 16 bytes per lane, four lanes hold a filter's 32
+        // columns and one store instruction writes 64-byte runs of 16 filters.
+        // The lane's position is worked out again here, every time, instead of living in registers across
+        // the main loop (the empty asm stops the compiler from hoisting it).
+        int lane_e = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+        asm volatile("" : "+v"(lane_e));
+        const int p = lane_e & 31, kb = lane_e >> 5;
+        const int tb_w = kb * 4 * 64 + p * 2;                                 // + filter row * 64
+        const int tb_r = lane_e * 16;                                         // filter lane / 4, columns 8 (lane % 4) ..
+        int fbi, ox0, v0;
+        decode(item_c, fbi, ox0, v0);
+        const int oimg0 = v0 / a.po, oy0 = v0 - oimg0 * a.po;
+        unsigned char* ybase = static_cast<unsigned char*>(a.y);
+        const uint32_t fstride = (uint32_t)(a.h * a.w * 2);              // bytes between filters
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            // accumulator side: this lane's computed column is input column ox - 1, outside the image for
+            // ox = 0 (it would reach output 0 through P_0) and for ox = w + 1 (output w - 1 through P_2)
+            bool kill0, kill2, fix;
+            {
+                const int ui = (wave * NT + nt) * UPT + p / SW, col = p % SW;
+                const int row = k3_div(ui, a.magic_nseg), seg = ui - row * a.nseg;
+                const int ox = ox0 + seg * VALID + col;
+                kill0 = ox == 0;
+                kill2 = ox == a.w + 1;
+                fix = __builtin_amdgcn_ballot_w64(kill0 || kill2) != 0;
+            }
+            // store side: lane = 4 * filter + piece; the piece's 8 columns, how many of them are outputs
+            const int sp = lane_e & 3, sf = lane_e >> 2;
+            int nv;
+            uint32_t off;
+            {
+                const int ui = (wave * NT + nt) * UPT + (8 * sp) / SW, col = (8 * sp) % SW;
+                const int row = k3_div(ui, a.magic_nseg), seg = ui - row * a.nseg;
+                const int t = oy0 + row, di = k3_div(t, a.magic_po);
+                const int img = oimg0 + di, oy = t - di * a.po, ox = ox0 + seg * VALID + col;
+                int lim = a.w - ox;                                       // outputs left in the image row
+                if (lim > VALID - col) lim = VALID - col;                 // ... and in the segment
+                nv = (v0 + row < a.vrows && oy < a.h) ? (lim > 8 ? 8 : (lim < 0 ? 0 : lim)) : 0;
+                off = (uint32_t)(((img * a.c_out + fbi * kMfmaFilters + sf) * a.h + oy) * a.w + ox) * 2u;
             }
 #pragma unroll
-            for (int c = 0; c < 3; ++c) {
-                const k3_h8 af0 = *reinterpret_cast<const k3_h8*>(wb + ((r * 3 + c) * 2 + 0) * 1024);
-                const k3_h8 af1 = *reinterpret_cast<const k3_h8*>(wb + ((r * 3 + c) * 2 + 1) * 1024);
+            for (int mt = 0; mt < 2; ++mt) {
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    acc[c][0][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af0, bf[nt], acc[c][0][nt], 0, 0, 0);
-                    acc[c][1][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af1, bf[nt], acc[c][1][nt], 0, 0, 0);
+                for (int r = 0; r < 16; r += 2) {
+                    k3_f2 pr;
+#pragma unroll
+                    for (int i = 0; i < 2; ++i) {
+                        float p0 = acc[0][mt][nt][r + i], p1 = acc[1][mt][nt][r + i], p2 = acc[2][mt][nt][r + i];
+                        if (fix) {                 // wave-uniform and rare: kept a branch (the empty asm stops if-conversion)
+                            asm volatile("" ::: "memory");
+                            p0 = kill0 ? 0.0f : p0;
+                            p2 = kill2 ? 0.0f : p2;
+                        }
+                        pr[i] = p0 + k3_shl1(p1 + k3_shl1(p2));
+                    }
+                    k3_h2 hv = __builtin_convertvector(pr, k3_h2);                // (filter, filter + 1) of this column, rounded to nearest even
+                    if (a.relu) hv = __builtin_elementwise_max(hv, k3_h2((_Float16)0.0f));
+                    const int frow = (r >> 2) * 8 + (r & 3);                      // + kb * 4: the filter's row in the corner
+                    *reinterpret_cast<_Float16*>(tb + tb_w + frow * 64) = hv.x;
+                    *reinterpret_cast<_Float16*>(tb + tb_w + (frow + 1) * 64) = hv.y;
+                }
+                // the wavefront's own corner: LDS operations of one wavefront execute in order
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const k3_u4 w4 = *reinterpret_cast<const k3_u4*>(tb + tb_r + j * 1024);
+                    const int f = mt * 32 + j * 16 + sf;                  // filter inside the block
+                    const bool fok = fbi * kMfmaFilters + f < a.c_out;
+                    unsigned char* dst = ybase + (off + (uint32_t)(mt * 32 + j * 16) * fstride);
+                    if (fok && nv > 0) {
+                        if (wide_ok && nv == 8) {
+                            *reinterpret_cast<k3_u4*>(dst) = w4;
+                        } else if (wide_ok && nv == 6) {
+                            k3_u3 w3;
+                            w3.x = w4.x, w3.y = w4.y, w3.z = w4.z;
+                            *reinterpret_cast<k3_u3*>(dst) = w3;
+                        } else {
+                            const uint32_t ws[4] = {w4.x, w4.y, w4.z, w4.w};
+#pragma unroll
+                            for (int e = 0; e < 8; ++e)
+                                if (e < nv) *reinterpret_cast<uint16_t*>(dst + 2 * e) = (uint16_t)(ws[e >> 1] >> (16 * (e & 1)));
+                        }
+                    }
                 }
             }
         }
     }
-
-    // ---- epilogue: combine the three tap columns, ReLU, binary16, store ----
-    // An accumulator register holds one filter for the 32 columns of a column tile (lanes 0-31; lanes
-    // 32-63 hold the filter four further on).  Output o of a segment sits in lane o: its own P_0, the
-    // next lane's P_1, the P_2 two lanes on.
-    _Float16* __restrict__ yout = static_cast<_Float16*>(a.y);
-    const int64_t fstride = (int64_t)a.h * a.w * 2;              // bytes between filters
-    unsigned char* ybase = reinterpret_cast<unsigned char*>(yout);
-    const bool whole_block = (fbi + 1) * kMfmaFilters <= a.c_out;
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        const int ui = (wave * NT + nt) * UPT + p / SW, col = p % SW;
-        const int row = k3_div(ui, a.magic_nseg), seg = ui - row * a.nseg;
-        const int t = oy0 + row, di = k3_div(t, a.magic_po);
-        const int img = oimg0 + di, oy = t - di * a.po, ox = ox0 + seg * VALID + col;
-        const bool valid = col < VALID && ox < a.w && v0 + row < a.vrows && oy < a.h;
-        // this lane's computed column is input column ox - 1: outside the image for ox = 0 (it would
-        // reach output 0 through P_0) and for ox = w + 1 (output w - 1 through P_2)
-        const bool kill0 = ox == 0, kill2 = ox == a.w + 1;
-        const bool fix = __builtin_amdgcn_ballot_w64(kill0 || kill2) != 0;
-        const uint32_t off = (uint32_t)(((img * a.c_out + fbi * kMfmaFilters + kb * 4) * a.h + oy) * a.w + ox) * 2u;
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                float p0 = acc[0][mt][nt][r], p1 = acc[1][mt][nt][r], p2 = acc[2][mt][nt][r];
-                if (fix) {
-                    p0 = kill0 ? 0.0f : p0;
-                    p2 = kill2 ? 0.0f : p2;
-                }
-                float v = p0 + k3_shl1(p1 + k3_shl1(p2));
-                if (a.relu) v = v > 0.0f ? v : 0.0f;
-                const int fl = mt * 32 + (r >> 2) * 8 + (r & 3);             // the lower lanes' filter inside the block
-                if (valid && (whole_block || fbi * kMfmaFilters + fl + kb * 4 < a.c_out))
-                    *reinterpret_cast<_Float16*>(ybase + fl * fstride + off) = (_Float16)v;
-            }
-    }
 }
 
 typedef void (*k3_launch_fn)(const K3Args& a, int blocks, int lds_bytes, hipStream_t stream);
-// The instantiation for a segment width (32 or 16); nullptr otherwise.
-k3_launch_fn k3_lookup(int sw);
+// The instantiation for a segment width (32 or 16) and a workgroup size (4 or 8 wavefronts); nullptr otherwise.
+k3_launch_fn k3_lookup(int sw, int waves);
 
 }  // namespace ppc

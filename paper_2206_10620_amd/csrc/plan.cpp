@@ -599,31 +599,51 @@ pp_status_t build_mfma_layout(const pp_conv_tuning_t& t, HostPlan& hp) {
         // with the least matrix-core work (ragged last tiles) plus a quarter of the staged rows (halo).
         const int64_t vr = (int64_t)hp.n_hint * (hp.h + 1) - 1;
         int sw = ((hp.w + 29) / 30) * 32 <= ((hp.w + 13) / 14) * 16 ? 32 : 16;
-        int nseg = 0;
-        if (t.tile_cols) {
-            if (t.tile_cols % 30 == 0) sw = 32, nseg = t.tile_cols / 30;
-            else if (t.tile_cols % 14 == 0) sw = 16, nseg = t.tile_cols / 14;
-            else return false;
-        } else {
-            const int units = kK3Waves * kK3ColTiles * (32 / sw), spr = (hp.w + sw - 3) / (sw - 2);
+        // Workgroup size: eight wavefronts stage the weights once for twice the pixels (and have a compute
+        // unit's LDS to themselves), but only a layer with several such tiles per compute unit keeps the
+        // chip busy with them; four otherwise.
+        if (t.wg_waves && t.wg_waves != 4 && t.wg_waves != 8) return false;
+        if (t.tiles_per_wave && t.tiles_per_wave != kK3ColTiles) return false;
+        auto pick = [&](int waves, int& nseg_o, double& tiles_o) -> bool {
+            nseg_o = 0;
+            if (ml.q < k3_stages(waves) - 1) return false;         // the kernel's ring is filled from one tile's chunks
+            if (t.tile_cols) {
+                if (t.tile_cols % 30 == 0) sw = 32, nseg_o = t.tile_cols / 30;
+                else if (t.tile_cols % 14 == 0) sw = 16, nseg_o = t.tile_cols / 14;
+                else return false;
+            }
+            const int units = waves * kK3ColTiles * (32 / sw), spr = (hp.w + sw - 3) / (sw - 2);
             double best = 1e300;
             for (int ns = 1; ns <= units; ++ns) {
-                const K3Geom g = k3_geom(sw, ns);
+                if (t.tile_cols && ns != nseg_o) continue;
+                const K3Geom g = k3_geom(sw, ns, waves);
                 if (!g.ok || (t.tile_rows && t.tile_rows != g.tr)) continue;
                 const double tiles = (double)((spr + ns - 1) / ns) * (double)((vr + g.tr - 1) / g.tr);
                 const double cost = tiles * (g.units + 0.25 * g.trp * ns);
-                if (cost < best - 1e-9) best = cost, nseg = ns;
+                if (cost < best - 1e-9) best = cost, nseg_o = ns, tiles_o = tiles * ml.fb;
             }
+            return best < 1e299;
+        };
+        int nseg = 0, waves = 0;
+        double tiles = 0.0;
+        if (t.wg_waves) {
+            waves = t.wg_waves;
+            if (!pick(waves, nseg, tiles)) return false;
+        } else {
+            int ns8 = 0;
+            double tiles8 = 0.0;
+            if (pick(8, ns8, tiles8) && tiles8 >= 4 * 256) waves = 8, nseg = ns8, tiles = tiles8;
+            else if (pick(4, nseg, tiles)) waves = 4;
+            else return false;
         }
-        const K3Geom g = k3_geom(sw, nseg);
-        if (!g.ok || (t.tile_rows && t.tile_rows != g.tr)) return false;
-        if ((t.tiles_per_wave && t.tiles_per_wave != kK3ColTiles) || (t.wg_waves && t.wg_waves != kK3Waves)) return false;
+        const K3Geom g = k3_geom(sw, nseg, waves);
+        if (!g.ok) return false;
         ml.g3 = g;
         ml.po = hp.h + 1;
         ml.tr = g.tr;
         ml.tc = nseg * (sw - 2);
         ml.ntw = kK3ColTiles;
-        ml.waves = kK3Waves;
+        ml.waves = waves;
         ml.lds_bytes = g.lds_bytes;
         hp.chosen.wg_waves = ml.waves;
         hp.chosen.tile_rows = ml.tr;

@@ -134,13 +134,15 @@ def test_direct_ragged_shapes(shape):
     say(f"  E={rep['E']:.2e} {rep['chosen']}")
 
 
-@pytest.mark.parametrize("tile_cols", [30, 60, 120, 14, 28, 56, 112])
-def test_direct_forced_tile_geometries(tile_cols):
-    say(f"mfma direct tile_cols {tile_cols}")
-    for (n, c_in, c_out, h, w) in [(2, 32, 37, 19, 45), (3, 16, 16, 8, 8), (2, 16, 72, 11, 48), (1, 48, 20, 5, 300)]:
+@pytest.mark.parametrize("waves,tile_cols", [(4, 30), (4, 60), (4, 14), (4, 28), (4, 56), (8, 30), (8, 60), (8, 14), (8, 28), (8, 56)])
+def test_direct_forced_tile_geometries(waves, tile_cols):
+    say(f"mfma direct waves {waves} tile_cols {tile_cols}")
+    for (n, c_in, c_out, h, w) in [(2, 32, 37, 19, 45), (3, 16, 16, 8, 8), (2, 16, 72, 11, 48), (1, 48, 20, 5, 300), (2, 16, 8, 70, 33)]:
+        if waves == 8:
+            c_in = max(c_in, 32)            # eight wavefronts stage two chunks ahead: the layer needs at least two
         lay = synth.random_pruned_layer("dtile", n, c_in, c_out, h, w, "f16", synth.PSET16, 0.5, 0.3, seed=7)
-        rep, _ = check_layer(lay, tuning=TD(tile_cols=tile_cols), label=f"mfma-direct-tile{tile_cols}")
-        assert rep["chosen"]["tile_cols"] == tile_cols and rep["chosen"]["mfma_kind"] == 2
+        rep, _ = check_layer(lay, tuning=TD(tile_cols=tile_cols, wg_waves=waves), label=f"mfma-direct-tile{waves}x{tile_cols}")
+        assert rep["chosen"]["tile_cols"] == tile_cols and rep["chosen"]["mfma_kind"] == 2 and rep["chosen"]["wg_waves"] == waves
     say(f"  E={rep['E']:.2e} {rep['chosen']}")
 
 
