@@ -117,11 +117,13 @@ __device__ __attribute__((noinline)) void k3_edge_piece(const uint16_t* x, int64
     *reinterpret_cast<k3_u4*>(lds_dst) = v4;
 }
 
-// s_waitcnt vmcnt(n) for a wave-uniform n (0..10; anything else waits for everything)
+// s_waitcnt vmcnt(n) for a wave-uniform n (0..31; anything else waits for everything)
 __device__ __forceinline__ void k3_wait_vm(int n) {
     switch (n) {
 #define PPC_K3_W(N) case N: asm volatile("s_waitcnt vmcnt(" #N ")" ::: "memory"); break;
         PPC_K3_W(1) PPC_K3_W(2) PPC_K3_W(3) PPC_K3_W(4) PPC_K3_W(5) PPC_K3_W(6) PPC_K3_W(7) PPC_K3_W(8) PPC_K3_W(9) PPC_K3_W(10)
+        PPC_K3_W(11) PPC_K3_W(12) PPC_K3_W(13) PPC_K3_W(14) PPC_K3_W(15) PPC_K3_W(16) PPC_K3_W(17) PPC_K3_W(18) PPC_K3_W(19) PPC_K3_W(20)
+        PPC_K3_W(21) PPC_K3_W(22) PPC_K3_W(23) PPC_K3_W(24) PPC_K3_W(25) PPC_K3_W(26) PPC_K3_W(27) PPC_K3_W(28) PPC_K3_W(29) PPC_K3_W(30) PPC_K3_W(31)
 #undef PPC_K3_W
         default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
     }
@@ -343,6 +345,9 @@ void k3_mfma(const K3Args a) {
     // Steps (chunk after chunk, tile after tile) are staged NS - 1 ahead of the step being multiplied.
     int ik = 0, iq = 0, ibuf = 0;                   // the next step to stage: tile, chunk, ring place
     int young = 0;                                  // load instructions issued after those of the step that is waited for next
+    // An epilogue's stores are issued behind the loads of the next NS - 1 steps: the waits for those steps
+    // may leave them in flight too.  Counted is a lower bound (the full-width store instructions).
+    int stores_behind = 0, store_credit = 0;
     auto advance_issue = [&]() {
         ibuf = ibuf + 1 == NS ? 0 : ibuf + 1;
         if (++iq == a.q) iq = 0, ++ik;
@@ -436,8 +441,9 @@ void k3_mfma(const K3Args a) {
             // This wavefront's loads of the current step have landed (and its zero fills and edge pieces are
             // written); after the barrier everyone's have, and everyone is done reading the ring place that
             // is filled next.  Loads return in order: all but the `young` most recent instructions are
-            // awaited (stores of an epilogue in between only make the wait longer than needed).
-            k3_wait_vm(young);
+            // awaited.
+            k3_wait_vm(young + (store_credit > 0 ? stores_behind : 0));
+            if (store_credit > 0) --store_credit;
             __syncthreads();
             // the step to stage now: NS - 1 after the current one
             Step nxt;
@@ -473,6 +479,8 @@ void k3_mfma(const K3Args a) {
         const int oimg0 = v0 / a.po, oy0 = v0 - oimg0 * a.po;
         unsigned char* ybase = static_cast<unsigned char*>(a.y);
         const uint32_t fstride = (uint32_t)(a.h * a.w * 2);              // bytes between filters
+        stores_behind = 0;
+        store_credit = NS - 1;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             // accumulator side: this lane's computed column is input column ox - 1, outside the image for
@@ -528,6 +536,7 @@ void k3_mfma(const K3Args a) {
                     const int f = mt * 32 + j * 16 + sf;                  // filter inside the block
                     const bool fok = fbi * kMfmaFilters + f < a.c_out;
                     unsigned char* dst = ybase + (off + (uint32_t)(mt * 32 + j * 16) * fstride);
+                    if (__builtin_amdgcn_ballot_w64(fok && wide_ok && nv == 8) != 0) ++stores_behind;
                     if (fok && nv > 0) {
                         if (wide_ok && nv == 8) {
                             *reinterpret_cast<k3_u4*>(dst) = w4;
