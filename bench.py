@@ -78,7 +78,7 @@ def time_layer(lay, steps, warmup, tuning=None, autotune=False):
     y = torch.empty((lay.n, lay.c_out, lay.h, lay.w), dtype=x.dtype, device="cuda")
     stream = torch.cuda.current_stream().cuda_stream
     if autotune and tuning is None:
-        tuning, _ = pp.autotune(lay, x, y, stream)
+        tuning = pp.Tuning(autotune=1)             # the plan times its candidates itself and keeps the fastest
     plan = pp.plan_from_layer(lay, tuning=tuning)
     for _ in range(warmup):
         plan.run(x, y, stream)
@@ -218,8 +218,8 @@ def main():
                                                      "on the timed workload (0 = automatic)")
     ap.add_argument("--variant", type=int, default=0, help="force a kernel variant for the timed workload (0 = the plan's choice)")
     ap.add_argument("--autotune", action="store_true",
-                    help="pick the parameters of every timed workload by measurement (paper_2206_10620_amd.autotune) "
-                         "instead of the plan's own rules; reported under config.params and 'tuned'")
+                    help="let every plan pick its kernel and parameters by measurement (tuning.autotune = 1) "
+                         "instead of by its rules; reported under config.params and 'tuned'")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this library runs on ONE GPU (no collectives, no sharding); run with --gpus 1")

@@ -91,9 +91,13 @@ typedef struct {
     int32_t tile_cols;      /* TC: columns per workgroup tile; TR * TC <= 32 * tiles_per_wave * wg_waves */
     int32_t tiles_per_wave; /* NTW: 32-pixel MFMA column tiles per wavefront (2 or 4) */
     int32_t wg_waves;       /* wavefronts per workgroup (4 or 8), all on the same 64 filters; 8 only with NTW = 4 */
-    int32_t autotune;       /* 1: pp_conv_plan times the candidate variants and parameters on the device, on scratch
-                               buffers of n_hint images that it allocates and frees, and keeps the fastest (the
-                               "tuning-decided parameters" of section 2.3.1 decided by measurement) */
+    int32_t autotune;       /* 1: pp_conv_plan times candidate variants and parameters on the device (the rules' own
+                               choice, the other kernels that take the layer, other workgroup sizes and tile shapes;
+                               fields set in this struct are kept), on scratch buffers of n_hint images and a stream
+                               that it creates and frees, and keeps the fastest: the "tuning-decided parameters" of
+                               section 2.3.1 decided by measurement.  Takes some milliseconds per candidate and
+                               synchronises with its own stream only.  Ignored with PP_FLAG_HOST_ONLY.  The plan
+                               reports chosen.autotune = 1 */
     int32_t mfma_kind;      /* which matrix-core kernel: 0 auto; 1 the general one (tiles transposed in registers on
                                their way into LDS; any kernel size, stride, channel count, fused pool); 2 the
                                direct-load one (3x3, stride 1, c_in a multiple of 16, no fused pool: tiles copied

@@ -4,6 +4,7 @@
 
 #include <cstring>
 #include <new>
+#include <vector>
 
 #include "k1_tiled.hpp"
 #include "k2_mfma.hpp"
@@ -241,11 +242,124 @@ const char* pp_status_string(pp_status_t s) {
     return "unknown status";
 }
 
+// pp_conv_plan with tuning.autotune = 1: the execution parameters that section 2.3.1 leaves to tuning are
+// decided by measurement.  A short list of candidates (the rules' own choice first, then the alternatives
+// that have won on some layer: the other workgroup size and tile shapes of the matrix-core kernels, the
+// other kernel, rows per lane and channel splits of the vector kernel) is planned, each plan is timed on
+// scratch buffers of n_hint images on a stream of its own, and the fastest is kept.
+static pp_status_t plan_autotuned(const pp_conv_desc_t* desc, pp_conv_plan_t** out_plan) {
+    pp_conv_tuning_t base = *desc->tuning;
+    base.autotune = 0;
+    std::vector<pp_conv_tuning_t> cands;
+    cands.push_back(base);
+    auto add = [&](auto&& edit) {
+        pp_conv_tuning_t t = base;
+        edit(t);
+        cands.push_back(t);
+    };
+    const bool f16 = desc->dtype == PP_F16;
+    if (f16 && (base.variant == 0 || base.variant == 3)) {
+        if (base.mfma_kind != 1) {
+            for (int waves : {4, 8})
+                for (int cols : {0, 60, 28})
+                    if (!base.wg_waves && !base.tile_cols && !base.tile_rows)
+                        add([&](pp_conv_tuning_t& t) { t.variant = 3, t.mfma_kind = 2, t.wg_waves = waves, t.tile_cols = cols; });
+        }
+        if (base.mfma_kind == 0) add([&](pp_conv_tuning_t& t) { t.variant = 3, t.mfma_kind = 1; });
+    }
+    if (base.variant == 0 || base.variant == 2) {
+        if (f16 && base.variant == 0) add([&](pp_conv_tuning_t& t) { t.variant = 2; });
+        if (!f16 || base.variant == 2)
+            for (int r : {1, 2})
+                for (int ks : {1, 2, 4})
+                    if (!base.rows_per_lane && !base.split_c)
+                        add([&](pp_conv_tuning_t& t) { t.variant = 2, t.rows_per_lane = r, t.split_c = ks; });
+    }
+    const int n = desc->n_hint > 0 ? desc->n_hint : 1;
+    pp_conv_plan_t* best = nullptr;
+    float best_ms = 0.0f;
+    void *x = nullptr, *y = nullptr;
+    hipStream_t stream = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    pp_status_t first_err = PP_ERR_UNSUPPORTED;
+    bool device_ok = true;
+    std::vector<pp_conv_tuning_t> timed;
+    for (const pp_conv_tuning_t& t : cands) {
+        pp_conv_desc_t d = *desc;
+        d.tuning = &t;
+        pp_conv_plan_t* p = nullptr;
+        const pp_status_t st = pp_conv_plan(&d, &p);
+        if (st != PP_OK) {
+            if (&t == &cands[0]) first_err = st;
+            if (st == PP_ERR_DEVICE || st == PP_ERR_ALLOC) {      // not a matter of the candidate
+                first_err = st;
+                device_ok = false;
+                break;
+            }
+            continue;
+        }
+        bool seen = false;                                        // candidates that come to the same parameters are timed once
+        for (const pp_conv_tuning_t& c : timed) seen = seen || std::memcmp(&c, &p->hp.chosen, sizeof c) == 0;
+        if (seen) {
+            pp_conv_destroy(p);
+            continue;
+        }
+        timed.push_back(p->hp.chosen);
+        if (!x) {
+            const HostPlan& hp = p->hp;
+            const size_t eb = hp.dtype == PP_F16 ? 2 : 4;
+            const size_t xb = (size_t)n * hp.c_in * hp.h * hp.w * eb, yb = (size_t)n * hp.c_out * hp.out_h * hp.out_w * eb;
+            device_ok = hipMalloc(&x, xb) == hipSuccess && hipMalloc(&y, yb) == hipSuccess &&
+                        hipMemset(x, hp.dtype == PP_F16 ? 0x34 : 0x3c, xb) == hipSuccess &&     // finite values of moderate size in either type
+                        hipStreamCreate(&stream) == hipSuccess && hipEventCreate(&e0) == hipSuccess && hipEventCreate(&e1) == hipSuccess;
+            if (!device_ok) {
+                pp_conv_destroy(p);
+                first_err = PP_ERR_DEVICE;
+                break;
+            }
+        }
+        float ms = 1e30f;
+        bool ok = true;
+        for (int i = 0; i < 3 && ok; ++i) ok = pp_conv_run(p, x, y, n, stream) == PP_OK;
+        for (int round = 0; round < 2 && ok; ++round) {
+            ok = hipEventRecord(e0, stream) == hipSuccess;
+            for (int i = 0; i < 10 && ok; ++i) ok = pp_conv_run(p, x, y, n, stream) == PP_OK;
+            float r = 0.0f;
+            ok = ok && hipEventRecord(e1, stream) == hipSuccess && hipEventSynchronize(e1) == hipSuccess &&
+                 hipEventElapsedTime(&r, e0, e1) == hipSuccess;
+            if (ok && r < ms) ms = r;
+        }
+        if (ok && (!best || ms < best_ms)) {
+            if (best) pp_conv_destroy(best);
+            best = p;
+            best_ms = ms;
+        } else {
+            pp_conv_destroy(p);
+        }
+    }
+    if (stream) (void)hipStreamSynchronize(stream);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (stream) (void)hipStreamDestroy(stream);
+    if (x) (void)hipFree(x);
+    if (y) (void)hipFree(y);
+    (void)hipGetLastError();
+    if (!best) return first_err;
+    best->hp.chosen.autotune = 1;
+    *out_plan = best;
+    return PP_OK;
+}
+
 pp_status_t pp_conv_plan(const pp_conv_desc_t* desc, pp_conv_plan_t** out_plan) {
     if (out_plan) *out_plan = nullptr;
     if (!desc || !out_plan) return PP_ERR_NULL;
     pp_status_t st = validate(*desc);
     if (st != PP_OK) return st;
+    if (desc->tuning && desc->tuning->autotune != 0) {
+        if (desc->tuning->autotune != 1) return PP_ERR_UNSUPPORTED;
+        // a host-only plan has no device to measure on: the rules decide
+        if (!(desc->flags & PP_FLAG_HOST_ONLY)) return plan_autotuned(desc, out_plan);
+    }
     pp_conv_plan_t* p = new (std::nothrow) pp_conv_plan_t();
     if (!p) return PP_ERR_ALLOC;
     try {

@@ -309,3 +309,15 @@ def test_config5_large_image(variant):
         rep, _ = check_layer(lay, x, tuning=T(variant=variant), relu=relu, points=8192, label="cfg5")
         assert rep["chosen"]["variant"] == variant
     say(f"  E={rep['E']:.2e} {rep['chosen']}")
+
+
+@pytest.mark.parametrize("dtype,shape", [("f16", (2, 32, 64, 40, 60)), ("f32", (2, 24, 32, 28, 28)), ("f16", (1, 12, 20, 9, 17))])
+def test_plan_time_autotuning_keeps_a_plan_that_passes_parity(dtype, shape):
+    """tuning.autotune = 1: the C library times its candidates itself and reports what it kept."""
+    n, c_in, c_out, h, w = shape
+    lay = synth.random_pruned_layer("auto", n, c_in, c_out, h, w, dtype, synth.PSET8, 0.5, 0.3, seed=5)
+    rep, _ = check_layer(lay, tuning=pp.Tuning(autotune=1), label="plan-autotune")
+    assert rep["chosen"]["autotune"] == 1 and rep["chosen"]["variant"] in (2, 3)
+    # a fixed field is kept
+    rep, _ = check_layer(lay, tuning=pp.Tuning(autotune=1, variant=2), label="plan-autotune-v2")
+    assert rep["chosen"]["autotune"] == 1 and rep["chosen"]["variant"] == 2

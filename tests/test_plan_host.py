@@ -179,3 +179,13 @@ def test_binary16_weight_rounding_matches_checker():
     assert st == pp.PP_OK
     want = oracle.widen_f16(oracle.round_f16(info["wpacked"].astype(np.float64))).astype(np.float32)
     assert np.array_equal(w, want)
+
+
+def test_autotune_request_on_a_host_only_plan_falls_back_to_the_rules():
+    lay = synth.random_pruned_layer("auto-host", 1, 16, 16, 12, 12, "f16", synth.PSET8, 0.5, 0.3, seed=1)
+    plan = pp.plan_from_layer(lay, host_only=True, tuning=pp.Tuning(autotune=1))
+    chosen = plan.query()["chosen"]
+    plan.close()
+    assert chosen["autotune"] == 0 and chosen["variant"] == 3
+    with pytest.raises(pp.PPError):
+        pp.plan_from_layer(lay, host_only=True, tuning=pp.Tuning(autotune=2))
