@@ -5,7 +5,7 @@ import numpy as np
 import torch
 
 import oracle
-from oracle.compare import TOL, error_report, sample_points
+from oracle.compare import TOL, error_report, sample_points, structured_points
 import paper_2206_10620_amd as pp
 
 FULL_LIMIT = 3.0e9      # dense multiply-accumulates above which the checker is evaluated at sampled outputs only
@@ -48,6 +48,24 @@ def reference_at(lay, x_np, wd, pts, relu_flag):
     return y4.reshape(-1, 4).max(axis=1), pre4, sc4.reshape(-1, 4).max(axis=1)
 
 
+def tile_boundary_points(lay, n, chosen):
+    """Stored-output coordinates on both sides of every tile boundary of the plan that ran (row bands of
+    the batch as one tall image, column strips), on the first and last row of every image and over the
+    whole last ragged tile: the places a sampled comparison of a large layer would otherwise only hit by
+    luck.  The tile geometry is read from the plan's reported parameters."""
+    pool = 2 if getattr(lay, "pool", False) else 1
+    if chosen["variant"] == 3:
+        band, strip = max(chosen["tile_rows"] // pool, 1), max(chosen["tile_cols"] // pool, 1)
+        # rows per image of the tall image: the general kernel pads by the kernel's reach, the direct one by one row
+        rpi = lay.out_h + 1
+    elif chosen["variant"] == 2:
+        band, strip = chosen["rows_per_lane"] * max(64 // chosen["lanes_x"], 1), 4 * chosen["lanes_x"]
+        rpi = lay.out_h + 1
+    else:
+        band, strip, rpi = 1, 256, lay.out_h
+    return structured_points(n, lay.c_out, lay.out_h, lay.out_w, band, strip, rpi, seed=lay.seed)
+
+
 def check_layer(lay, x_np=None, tuning=None, relu=None, tol=None, points=4096, label="", extra_points=None):
     """Compare GPU output with the checker: every element when the layer is small, sampled outputs otherwise
     (random ones, corners and edges, plus extra_points: an int array [k, 4] of stored-output coordinates)."""
@@ -66,6 +84,7 @@ def check_layer(lay, x_np=None, tuning=None, relu=None, tol=None, points=4096, l
     else:
         wd = oracle.layer_dense_weights(lay)
         pts = sample_points(n, lay.c_out, lay.out_h, lay.out_w, points, seed=lay.seed)
+        pts = np.concatenate([pts, tile_boundary_points(lay, n, chosen)], axis=0)
         if extra_points is not None and len(extra_points):
             pts = np.concatenate([pts, np.asarray(extra_points, dtype=np.int32)], axis=0)
         ref, pre, scale = reference_at(lay, x_np, wd, pts, relu_flag)

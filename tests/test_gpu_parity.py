@@ -278,14 +278,17 @@ def test_config4_vgg_stack_per_layer(variant):
     for lay in layers:
         say(f"{lay.name} variant {variant}")
         plan = pp.plan_from_layer(lay, tuning=T(variant=variant))
-        assert plan.query()["chosen"]["variant"] == variant
+        chosen = plan.query()["chosen"]
+        assert chosen["variant"] == variant
         yd = plan.run(xd)
         torch.cuda.synchronize()
         plan.close()
         x_np, y_np = xd.cpu().numpy(), yd.cpu().numpy()
         wd = oracle.layer_dense_weights(lay)
         from oracle.compare import error_report, sample_points, TOL
-        pts = sample_points(lay.n, lay.c_out, lay.h, lay.w, 2048, seed=lay.seed)
+        from gpu_util import tile_boundary_points
+        pts = np.concatenate([sample_points(lay.n, lay.c_out, lay.h, lay.w, 2048, seed=lay.seed),
+                              tile_boundary_points(lay, lay.n, chosen)], axis=0)
         ref, pre, scale = oracle.conv_at(x_np, wd, pts, lay.bias, lay.relu)
         rep = error_report(y_np[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]], ref, pre, scale)
         say(f"  E={rep['E']:.2e} sigma={rep['sigma']:.3f}")
@@ -321,3 +324,43 @@ def test_plan_time_autotuning_keeps_a_plan_that_passes_parity(dtype, shape):
     # a fixed field is kept
     rep, _ = check_layer(lay, tuning=pp.Tuning(autotune=1, variant=2), label="plan-autotune-v2")
     assert rep["chosen"]["autotune"] == 1 and rep["chosen"]["variant"] == 2
+
+
+# ---- the gate itself: it must fail when the layer that was run is not the layer that is checked ----
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_the_comparison_fails_on_a_wrong_layer(dtype):
+    """Negative controls.  The GPU runs the layer as given; the checker is handed a copy with one small
+    mistake planted in it (on the CPU side): a kernel's pattern changed, one weight scaled by 1 + 2e-3 (fp32:
+    1 + 1e-4), two filters swapped.  Each must push E over the tolerance, and the unchanged layer must pass."""
+    import copy
+    from gpu_util import run_layer
+    from oracle.compare import error_report, TOL
+    lay = synth.random_pruned_layer("neg", 2, 16, 24, 12, 20, dtype, synth.PSET8, 0.6, 0.3, seed=11)
+    x = lay.make_input()
+    y, _ = run_layer(lay, x)
+
+    def E_against(other):
+        ref, pre, scale = oracle.layer_reference(other, x.astype(np.float64))
+        return error_report(y, ref, pre, scale)["E"]
+
+    assert E_against(lay) <= TOL[dtype]
+    kept = np.flatnonzero(lay.conn_mask.ravel())
+    # (i) one kept kernel gets another pattern
+    wrong = copy.deepcopy(lay)
+    k = int(kept[len(kept) // 2])
+    wrong.pattern_id.ravel()[k] = (int(wrong.pattern_id.ravel()[k]) + 1) % len(lay.pattern_masks)
+    assert E_against(wrong) > TOL[dtype]
+    # (ii) the weights of the kernel with the largest weight are off by a relative 25 x tolerance (0.05 for
+    # binary16 storage, 2.5e-4 for fp32): that kernel's products are a good fraction of sigma on some outputs
+    wrong = copy.deepcopy(lay)
+    big = int(kept[np.argmax(np.abs(wrong.weights[kept]).max(axis=1))])
+    wrong.weights[big] *= 1.0 + 25 * TOL[dtype]
+    assert E_against(wrong) > TOL[dtype]
+    # (iii) two output filters trade places
+    wrong = copy.deepcopy(lay)
+    for name in ("pattern_id", "conn_mask", "weights", "bias"):
+        arr = getattr(wrong, name)
+        view = arr.reshape(lay.c_out, -1)
+        view[[3, 7]] = view[[7, 3]]
+    assert E_against(wrong) > TOL[dtype]

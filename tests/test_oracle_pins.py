@@ -285,3 +285,57 @@ def test_plan_structural_invariants(seed):
         if r["kcount"][pos] == r["kcount"][pos + 1]:
             a, b = hist[pos].tolist(), hist[pos + 1].tolist()
             assert a > b or (a == b and r["perm"][pos] < r["perm"][pos + 1])
+
+
+# ---- the comparison helpers (oracle/compare.py) ------------------------------------------------
+
+def test_error_report_on_hand_made_arrays():
+    """E = max |got - ref| / max(|ref|, sigma) with sigma = RMS of the pre-activations, worked by hand."""
+    from oracle.compare import error_report
+    pre = np.array([3.0, -4.0, 0.0, 0.0])                    # sigma = sqrt((9 + 16) / 4) = 2.5
+    ref = np.maximum(pre, 0.0)                               # ReLU: [3, 0, 0, 0]
+    got = np.array([3.3, 0.05, 0.0, -0.25])
+    rep = error_report(got, ref, pre, np.array([10.0, 10.0, 1.0, 0.5]))
+    assert rep["sigma"] == pytest.approx(2.5)
+    # element errors 0.3, 0.05, 0, 0.25 over denominators max(3, 2.5), 2.5, 2.5, 2.5
+    assert rep["E"] == pytest.approx(max(0.3 / 3.0, 0.05 / 2.5, 0.25 / 2.5))
+    assert rep["max_abs"] == pytest.approx(0.3)
+    assert rep["E_scale"] == pytest.approx(0.25 / 0.5)
+    assert rep["normwise"] == pytest.approx(np.sqrt(0.3 ** 2 + 0.05 ** 2 + 0.25 ** 2) / 3.0)
+    # the floor: an output near zero is measured against sigma, not against itself
+    rep = error_report(np.array([1e-9]), np.array([0.0]), np.array([2.0]))
+    assert rep["E"] == pytest.approx(1e-9 / 2.0)
+    # above the floor it is the plain relative error
+    rep = error_report(np.array([101.0, 0.0]), np.array([100.0, 0.0]), np.array([100.0, 0.0]))
+    assert rep["E"] == pytest.approx(0.01)
+    # an empty comparison reports zero, an all-zero reference does not divide by zero
+    assert error_report(np.zeros(0), np.zeros(0), np.ones(3))["E"] == 0.0
+    assert error_report(np.array([0.5]), np.array([0.0]), np.array([0.0]))["E"] == pytest.approx(0.5)
+
+
+def test_structured_points_cover_the_tile_boundaries():
+    from oracle.compare import sample_points, structured_points
+    n, c_out, h, w, band, strip = 3, 130, 10, 50, 4, 16
+    rpi = h + 1
+    pts = structured_points(n, c_out, h, w, band, strip, rpi, seed=1)
+    assert pts.dtype == np.int32 and pts.shape[1] == 4
+    assert (pts >= 0).all() and (pts[:, 0] < n).all() and (pts[:, 1] < c_out).all() and (pts[:, 2] < h).all() and (pts[:, 3] < w).all()
+    cells = {(int(a), int(c), int(d)) for a, _, c, d in pts}
+    vrows = n * rpi - 1
+    for k in range(1, (vrows + band - 1) // band):              # both sides of every band boundary that is an image row
+        for v in (k * band - 1, k * band):
+            if v % rpi < h:
+                assert any(img == v // rpi and oy == v % rpi for img, oy, _ in cells), v
+    for k in range(1, (w + strip - 1) // strip):                # both sides of every strip boundary
+        for x in (k * strip - 1, k * strip):
+            assert any(ox == x for _, _, ox in cells), x
+    for img in range(n):                                         # first and last row of every image
+        assert any(i == img and oy == 0 for i, oy, _ in cells) and any(i == img and oy == h - 1 for i, oy, _ in cells)
+    last_v0, last_x0 = ((vrows - 1) // band) * band, ((w - 1) // strip) * strip
+    for v in range(last_v0, vrows):                              # the whole last tile
+        for x in range(last_x0, w):
+            if v % rpi < h:
+                assert (v // rpi, v % rpi, x) in cells
+    assert set(int(f) for f in pts[:, 1]) <= {0, 63, 64, 127, 128, 129}
+    rnd = sample_points(n, c_out, h, w, 100, seed=2)
+    assert rnd.shape == (100 + 36, 4) and (rnd[:, 1] < c_out).all()
