@@ -479,6 +479,7 @@ void k3_mfma(const K3Args a) {
         const int oimg0 = v0 / a.po, oy0 = v0 - oimg0 * a.po;
         unsigned char* ybase = static_cast<unsigned char*>(a.y);
         const uint32_t fstride = (uint32_t)(a.h * a.w * 2);              // bytes between filters
+        const k3_h2 floor2 = a.relu ? k3_h2((_Float16)0.0f) : k3_h2((_Float16)-65504.0f);
         stores_behind = 0;
         store_credit = NS - 1;
 #pragma unroll
@@ -524,7 +525,7 @@ void k3_mfma(const K3Args a) {
                         pr[i] = p0 + k3_shl1(p1 + k3_shl1(p2));
                     }
                     k3_h2 hv = __builtin_convertvector(pr, k3_h2);                // (filter, filter + 1) of this column, rounded to nearest even
-                    if (a.relu) hv = __builtin_elementwise_max(hv, k3_h2((_Float16)0.0f));
+                    hv = __builtin_elementwise_max(hv, floor2);                   // ReLU (or nothing: the floor is then the lowest finite value)
                     const int frow = (r >> 2) * 8 + (r & 3);                      // + kb * 4: the filter's row in the corner
                     *reinterpret_cast<_Float16*>(tb + tb_w + frow * 64) = hv.x;
                     *reinterpret_cast<_Float16*>(tb + tb_w + (frow + 1) * 64) = hv.y;
