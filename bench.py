@@ -17,11 +17,12 @@ roofline : the dominant kernel of the timed workload against the roofline that b
              256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2 (packed) x 2.4 GHz = 157.3 TFLOP/s; the library is
              built with packed-FP32 formation disabled, so `peak_unpacked` = 78.6 TFLOP/s is the reachable
              ceiling.  `achieved` counts 2 flop per effective MAC.
-           * the matrix-core kernel (variant 3, zero-filled dense weights in binary16) does 9/(4*keep) times
-             the multiply-accumulates at matrix-core rate, which leaves HBM as the binding roofline of the
-             large-image layers: `achieved` = algorithmic bytes (x once, y once, packed weights once) per
-             second against 8 TB/s.  The matrix-core fraction (dense flop against 2.5 PFLOP/s) is given
-             beside it as `frac_mfma`.
+           * the matrix-core kernels (variant 3, zero-filled dense weights in binary16) do 9/(4*keep) times
+             the multiply-accumulates at matrix-core rate.  By algorithmic counts the 1080p layer then
+             needs 66 us of HBM time (531 MB at 8 TB/s) against 61 us of matrix-core time (153 GFLOP at
+             2.5 PFLOP/s): HBM is the binding roofline, and `achieved` = algorithmic bytes (x once, y
+             once, packed weights once) per second against 8 TB/s.  The matrix-core fraction (dense flop
+             against 2.5 PFLOP/s) is given beside it as `frac_mfma`.
            Kernel time comes from events recorded on the launch stream around the timed launches.
 """
 from __future__ import annotations
@@ -46,7 +47,12 @@ PEAK_HBM_GBS = 8000.0
 # HBM-side traffic of one launch (bytes), from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by a copy
 # kernel of known size; see profiles/.  Valid only for the kernel revision it was measured on:
 # reported as null for any other.  Keyed by (workload, variant).
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    ("cfg5_enhance_1080p", 3): ("lib-2026-11-28-b", 660.58e6),
+    ("cfg4_vgg_L6", 3): ("lib-2026-11-28-b", 38.19e6),
+    ("cfg4_vgg_L9", 3): ("lib-2026-11-28-b", 53.95e6),
+    ("cfg2_vgg_mid", 2): ("lib-2026-11-28-b", 20.43e6),
+}
 
 DEFAULT_WORKLOAD = "cfg5_enhance_1080p"
 
@@ -190,7 +196,8 @@ def roofline_of(lay, t, traffic):
     variant = t["chosen"]["variant"]
     if variant == 3:
         return {"bound": "hbm", "achieved": lay.alg_bytes / sec / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                "frac": lay.alg_bytes / sec / 1e9 / PEAK_HBM_GBS, "traffic": traffic, "kernel": "k2_mfma",
+                "frac": lay.alg_bytes / sec / 1e9 / PEAK_HBM_GBS, "traffic": traffic,
+                "kernel": "k3_mfma" if t["chosen"].get("mfma_kind") == 2 else "k2_mfma",
                 "kernel_us": t["event_ms_per_step"] * 1e3,
                 "frac_mfma": 2 * dense_macs(lay) / sec / 1e12 / PEAK_MFMA_F16_TFLOPS,
                 "peak_mfma_tflops": PEAK_MFMA_F16_TFLOPS}

@@ -21,7 +21,7 @@ def test_measured_traffic_belongs_to_the_current_kernel_revision():
     profile summaries have to name the revision the library reports."""
     sys.path.insert(0, ROOT)
     import bench
-    kernel_of = {2: "k1_tiled", 3: "k2_mfma"}
+    kernel_of = {2: "k1_tiled", 3: "k3_mfma"}
     for (wl, variant), (rev, nbytes) in bench.MEASURED_TRAFFIC.items():
         assert rev == pp.KERNEL_REVISION, f"{wl}: traffic measured on {rev}, library is {pp.KERNEL_REVISION}"
         assert nbytes > 0
