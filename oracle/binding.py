@@ -10,14 +10,16 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "pp_oracle.cpp")
+_SRC_BLOCK = os.path.join(_HERE, "pp_block_oracle.cpp")
 _SO = os.path.join(_HERE, "libpp_oracle.so")
 _lib = None
 
 
 def build(force: bool = False) -> str:
     """Compile the checker (host compiler only)."""
-    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
-        subprocess.check_call(["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-pthread", "-o", _SO, _SRC])
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_BLOCK))
+    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < newest:
+        subprocess.check_call(["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-pthread", "-o", _SO, _SRC, _SRC_BLOCK])
     return _SO
 
 
@@ -51,6 +53,14 @@ def lib() -> C.CDLL:
         L.oracle_conv_k_at.restype = None
         L.oracle_brute_k.argtypes = [i32] * 8 + [vp] * 6 + [i32, vp]
         L.oracle_brute_k.restype = None
+        L.oracle_block_expand.argtypes = [i32] * 4 + [vp] * 4
+        L.oracle_block_expand.restype = i32
+        L.oracle_gemm.argtypes = [i32] * 3 + [vp] * 3 + [i32] + [vp] * 3 + [i32]
+        L.oracle_gemm.restype = None
+        L.oracle_gemm_at.argtypes = [i32] * 3 + [vp] * 3 + [i32, vp, i64] + [vp] * 3 + [i32]
+        L.oracle_gemm_at.restype = None
+        L.oracle_block_brute.argtypes = [i32] * 5 + [vp] * 5 + [i32, vp]
+        L.oracle_block_brute.restype = None
         _lib = L
     return _lib
 
@@ -274,3 +284,69 @@ def layer_reference(layer, x, relu=None, threads=None):
     if pool:
         y, sc = maxpool2(y), maxpool2(sc)
     return y, pre, sc
+
+
+# ---- block-pruned matrix product (section 2.1.2) ----
+
+def block_expand(m, k, bm, bk, row_keep, col_keep, weights) -> np.ndarray:
+    """Masked dense matrix Wd [m, k] in float64."""
+    rk, ck, w = _c(row_keep, np.uint8), _c(col_keep, np.uint8), _c(weights, np.float64)
+    blocks = ((m + bm - 1) // bm) * ((k + bk - 1) // bk)
+    assert rk.size == blocks * bm and ck.size == blocks * bk and w.shape == (m, k)
+    wd = np.empty((m, k), dtype=np.float64)
+    if lib().oracle_block_expand(m, k, bm, bk, _p(rk), _p(ck), _p(w), _p(wd)) != 0:
+        raise ValueError("bad block layer shape")
+    return wd
+
+
+def gemm(wd, x, bias=None, relu=False, want_pre=False, want_scale=False, threads=None):
+    """y = act(wd @ x + bias) by three plain loops in float64; x is [k, n]."""
+    wd, x = _c(wd, np.float64), _c(x, np.float64)
+    m, k = wd.shape
+    assert x.shape[0] == k
+    n = x.shape[1]
+    b = None if bias is None else _c(bias, np.float64)
+    y = np.empty((m, n), dtype=np.float64)
+    pre = np.empty((m, n), dtype=np.float64) if want_pre else None
+    sc = np.empty((m, n), dtype=np.float64) if want_scale else None
+    lib().oracle_gemm(m, k, n, _p(wd), _p(x), _p(b), int(relu), _p(y), _p(pre), _p(sc), threads or default_threads())
+    out = (y,)
+    if want_pre:
+        out += (pre,)
+    if want_scale:
+        out += (sc,)
+    return out if len(out) > 1 else y
+
+
+def gemm_at(wd, x, pts, bias=None, relu=False, threads=None):
+    """(y, pre, scale) at the (row, column) pairs pts [count, 2]."""
+    wd, x = _c(wd, np.float64), _c(x, np.float64)
+    m, k = wd.shape
+    n = x.shape[1]
+    pts = _c(pts, np.int32)
+    assert pts.ndim == 2 and pts.shape[1] == 2 and pts[:, 0].max(initial=0) < m and pts[:, 1].max(initial=0) < n and pts.min(initial=0) >= 0
+    b = None if bias is None else _c(bias, np.float64)
+    cnt = pts.shape[0]
+    y, pre, sc = (np.empty(cnt, dtype=np.float64) for _ in range(3))
+    lib().oracle_gemm_at(m, k, n, _p(wd), _p(x), _p(b), int(relu), _p(pts), cnt, _p(y), _p(pre), _p(sc), threads or default_threads())
+    return y, pre, sc
+
+
+def block_brute(m, k, bm, bk, row_keep, col_keep, weights, x, bias=None, relu=False) -> np.ndarray:
+    """Gather-style evaluation that never forms the masked matrix (a pin for block_expand + gemm)."""
+    rk, ck, w, x = _c(row_keep, np.uint8), _c(col_keep, np.uint8), _c(weights, np.float64), _c(x, np.float64)
+    n = x.shape[1]
+    b = None if bias is None else _c(bias, np.float64)
+    y = np.empty((m, n), dtype=np.float64)
+    lib().oracle_block_brute(m, k, n, bm, bk, _p(rk), _p(ck), _p(w), _p(x), _p(b), int(relu), _p(y))
+    return y
+
+
+def block_layer_reference(layer, x, relu=None, threads=None):
+    """(y, pre, scale) of a synth.BlockLayer on x [k, n]; weights, input and bias are taken as stored
+    (binary16-rounded first when the layer's storage type is f16)."""
+    w = layer.weights.astype(np.float64)
+    if layer.dtype == "f16":
+        w = widen_f16(round_f16(w))
+    wd = block_expand(layer.m, layer.k, layer.bm, layer.bk, layer.row_keep, layer.col_keep, w)
+    return gemm(wd, np.asarray(x, dtype=np.float64), layer.bias, layer.relu if relu is None else relu, True, True, threads)
