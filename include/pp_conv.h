@@ -102,7 +102,9 @@ typedef struct {
                                their way into LDS; any kernel size, stride, channel count, fused pool); 2 the
                                direct-load one (3x3, stride 1, c_in a multiple of 16, no fused pool: tiles copied
                                memory-to-LDS as they are and transposed by the LDS read; tile_cols is then a multiple
-                               of 30 or of 14, tile_rows = 8 * 30 / tile_cols or 16 * 14 / tile_cols) */
+                               of 30 or of 14: segments of 30 or 14 outputs, of which a workgroup of wg_waves
+                               wavefronts holds 2 * wg_waves or 4 * wg_waves; tile_rows = that count divided by
+                               the segments per row, tile_cols / 30 or tile_cols / 14) */
 } pp_conv_tuning_t;
 
 /* Layer description (section 2.1.1 for the sparsity, section 2.3.1 for what the layer-wise

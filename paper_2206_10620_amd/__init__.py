@@ -9,3 +9,5 @@ from .pp_conv import (PP_OK, PP_ERR_NULL, PP_ERR_SHAPE, PP_ERR_PATTERN, PP_ERR_U
                       pp_conv_plan_query, pp_conv_plan_unpack, pp_maxpool2x2_run, pp_status_string,
                       plan_from_layer)
 from .autotune import autotune, default_candidates
+from .pp_block_gemm import (BlockPlan, block_plan_from_layer, pp_block_gemm_plan, pp_block_gemm_run, pp_block_gemm_destroy,
+                            pp_block_gemm_query, pp_block_gemm_unpack)
