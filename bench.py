@@ -120,6 +120,79 @@ def summarize(lay, t):
                 frac_hbm=lay.alg_bytes / sec / 1e9 / PEAK_HBM_GBS, params=t["chosen"])
 
 
+BLOCK_WORKLOAD = "block_ffn_4096"
+
+
+def time_block_gemm(steps, warmup, check=True, npts=2000):
+    """The block-pruned matrix product (section 2.1.2) on a transformer-sized projection: 4096 x 4096 weights in
+    64 x 64 blocks, about one weight in six kept, 4096 columns of activations, binary16 storage.  The matrix
+    cores multiply every row of a 64-row tile against the tile's kept columns, so `executed` counts more than
+    the kept weights; the roofline of this kernel is the matrix-core one."""
+    import torch
+    import synth
+    import paper_2206_10620_amd as pp
+    lay = synth.transformer_block_layer()
+    x = torch.from_numpy(lay.make_input()).cuda()
+    y = torch.empty((lay.m, lay.n), dtype=x.dtype, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    plan = pp.block_plan_from_layer(lay)
+    q = plan.query()
+    for _ in range(warmup):
+        plan.run(x, y, stream)
+    torch.cuda.synchronize()
+    ev0, ev1 = _events()
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(steps):
+        plan.run(x, y, stream)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) / steps
+    sec = ev0.elapsed_time(ev1) * 1e-3 / steps
+    plan.close()
+    executed_flop = 2.0 * q["executed_weights"] * lay.n
+    res = dict(workload=lay.name, dtype=lay.dtype, m=lay.m, k=lay.k, n=lay.n, block=[lay.bm, lay.bk],
+               kept_weights=int(q["kept_weights"]), executed_weights=int(q["executed_weights"]), kernel="k4_block_gemm" if q["variant"] == 2 else "k4_generic",
+               eff_gmacs=lay.eff_macs / 1e9, alg_mb=lay.alg_bytes / 1e6, us_per_step=sec * 1e6, wall_us_per_step=wall * 1e6,
+               eff_gmac_per_s=lay.eff_macs / sec / 1e9, alg_gb_per_s=lay.alg_bytes / sec / 1e9,
+               executed_tflops=executed_flop / sec / 1e12, frac_mfma_executed=executed_flop / sec / 1e12 / PEAK_MFMA_F16_TFLOPS,
+               frac_mfma_effective=2.0 * lay.eff_macs / sec / 1e12 / PEAK_MFMA_F16_TFLOPS, frac_hbm=lay.alg_bytes / sec / 1e9 / PEAK_HBM_GBS)
+    if check:
+        import oracle
+        from oracle.compare import error_report
+        rs = np.random.RandomState(0)
+        pts = np.stack([rs.randint(0, lay.m, npts), rs.randint(0, lay.n, npts)], axis=1).astype(np.int32)
+        w = oracle.widen_f16(oracle.round_f16(lay.weights.astype(np.float64)))
+        wd = oracle.block_expand(lay.m, lay.k, lay.bm, lay.bk, lay.row_keep, lay.col_keep, w)
+        c0 = time.perf_counter()
+        ref, pre, scale = oracle.gemm_at(wd, x.cpu().numpy().astype(np.float64), pts, lay.bias, lay.relu)
+        res["cpu_seconds"], res["cpu_outputs"] = time.perf_counter() - c0, npts
+        res["max_rel_err"] = error_report(y.cpu().numpy()[pts[:, 0], pts[:, 1]], ref, pre, scale)["E"]
+    res["_sec"], res["_wall"], res["_lay"] = sec, wall, lay
+    return res
+
+
+def block_main(args):
+    """--workload block_ffn_4096: the JSON line for the block-pruned matrix product alone (used for its profiles)."""
+    r = time_block_gemm(args.steps, max(args.warmup, 20), check=not args.no_cpu, npts=2000000)
+    sec, wall, lay = r.pop("_sec"), r.pop("_wall"), r.pop("_lay")
+    out = {"metric": "effective GMAC/s (nonzero MACs), block-pruned matrix product", "value": lay.eff_macs / wall / 1e9, "unit": "GMAC/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall * 1e3, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+           "config": {"workload": lay.name, "m": lay.m, "k": lay.k, "n": lay.n, "block": [lay.bm, lay.bk],
+                      "kept_weights": r["kept_weights"], "executed_weights": r["executed_weights"], "fused": "bias+relu"},
+           "roofline": {"bound": "mfma", "achieved": r["executed_tflops"], "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s",
+                        "frac": r["frac_mfma_executed"], "traffic": None, "kernel": r["kernel"], "kernel_us": sec * 1e6,
+                        "frac_effective": r["frac_mfma_effective"], "frac_hbm": r["frac_hbm"]}}
+    if "max_rel_err" in r:
+        import oracle
+        frac = r["cpu_outputs"] / (lay.m * lay.n)
+        out["cpu_baseline"] = {"value": lay.eff_macs * frac / r["cpu_seconds"] / 1e9, "unit": "GMAC/s", "cores": oracle.binding.default_threads(),
+                               "kind": "oracle", "sample": f"{r['cpu_outputs']} sampled outputs ({frac:.3%} of the layer)", "seconds": r["cpu_seconds"]}
+        out["max_rel_err"] = r["max_rel_err"]
+    print(json.dumps(out))
+
+
 def time_vgg_stack(steps, warmup):
     """The 13 layers of the VGG-shaped configuration as ONE chain on one stream: every plan is built up
     front, every activation buffer is allocated up front, and a step enqueues the 13 convolutions and the 4
@@ -245,6 +318,9 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    if args.workload == BLOCK_WORKLOAD:
+        block_main(args)
+        return
     table = workloads()
     lay = table[args.workload]()
     tuning = None
@@ -324,6 +400,8 @@ def main():
             del t2
             torch.cuda.empty_cache()
         others.append(time_vgg_stack(steps=20, warmup=5))
+        blk = time_block_gemm(steps=50, warmup=10, check=not args.no_cpu)
+        others.append({k: v for k, v in blk.items() if not k.startswith("_")})
         out["others"] = others
 
     print(json.dumps(out))

@@ -16,6 +16,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <type_traits>
 
 #include "block_plan.hpp"
 
@@ -93,25 +94,27 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)k4_smem;
     const uint32_t lane16 = (uint32_t)lane * 16u;
     const bool piece_ok = col0 + lane * 8 < a.n;            // n is a multiple of 8: a 16-byte piece is inside a row or outside
-    const int64_t row_bytes = (int64_t)a.n * 2;
-    const int per_chunk = 4 + (wave < 2 ? 1 : 0);           // direct loads this wavefront issues per chunk
+    const uint32_t row_bytes = (uint32_t)a.n * 2u;          // x is smaller than 4 GB: byte offsets fit 32 bits
+    const bool wload = wave < 2;                            // wavefronts 0 and 1 also fetch the two weight operands
 
     // chunks are issued in order, so the four list entries of the next chunk to issue are fetched one
     // issue ahead (the list is padded by a chunk at its very end)
     int rows[4];
-    auto fetch_rows = [&](int c) {
+    k4_const_i32 next_rows = list + wave;
+    auto fetch_rows = [&]() {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) rows[i] = list[c * kBlockChunk + wave + 4 * i];
+        for (int i = 0; i < 4; ++i) rows[i] = next_rows[4 * i];
+        next_rows += kBlockChunk;
     };
-    auto issue = [&](int c) {
-        const uint32_t st = lds0 + (uint32_t)((c % NS) * kK4StageBytes);
+    auto issue = [&](int c, int stage) {
+        const uint32_t st = lds0 + (uint32_t)(stage * kK4StageBytes);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const unsigned char* src = xsrc + rows[i] * row_bytes;
-            if (piece_ok) k4_dma16(lane16, src, st + (uint32_t)((wave + 4 * i) * kK4RowPitch));
+            const uint32_t off = (uint32_t)rows[i] * row_bytes + lane16;
+            if (piece_ok) k4_dma16(off, xsrc, st + (uint32_t)((wave + 4 * i) * kK4RowPitch));
         }
-        if (wave < 2) k4_dma16(lane16, wsrc + (int64_t)c * 2048, st + (uint32_t)(kBlockChunk * kK4RowPitch + wave * 1024));
-        fetch_rows(c + 1);
+        if (wload) k4_dma16(lane16, wsrc + (int64_t)c * 2048, st + (uint32_t)(kBlockChunk * kK4RowPitch + wave * 1024));
+        fetch_rows();
     };
 
     // accumulators: register i of tile (mt, nt) is row mt * 32 + (i / 4) * 8 + (lane / 32) * 4 + i % 4, column nt * 32 + lane % 32
@@ -134,33 +137,63 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int blk = lane >> 4, jj = (lane & 15) >> 2, qq = lane & 3;
     const uint32_t bbase = (uint32_t)((8 * (blk >> 1) + jj) * kK4RowPitch + (wave * 128 + 16 * (blk & 1) + 4 * qq) * 2);
 
-    fetch_rows(0);
-#pragma unroll 1
-    for (int c = 0; c < NS - 1; ++c)
-        if (c < nch) issue(c);
-#pragma unroll 1
-    for (int c = 0; c < nch; ++c) {
-        int younger = nch - 1 - c;
-        younger = younger > NS - 2 ? NS - 2 : younger;
-        k4_wait_vm(younger * per_chunk);
-        __syncthreads();                       // chunk c is complete for everyone; everyone is done reading chunk c - 1
-        if (c + NS - 1 < nch) issue(c + NS - 1);
-        const uint32_t st = lds0 + (uint32_t)((c % NS) * kK4StageBytes);
-        const unsigned char* wst = k4_smem + (c % NS) * kK4StageBytes + kBlockChunk * kK4RowPitch + lane * 16;
-        k4_h8 af[2], bf[NT];
-        af[0] = *reinterpret_cast<const k4_h8*>(wst);
-        af[1] = *reinterpret_cast<const k4_h8*>(wst + 1024);
+    // Operand fragments live in two register sets: while the MFMAs of chunk c run from one, the
+    // fragments of chunk c + 1 are read into the other, behind the one barrier per chunk that says
+    // "chunk c + 1 has landed for every wavefront, and every wavefront has read chunk c out of LDS"
+    // -- which also frees chunk c's stage for chunk c + 4.
+    k4_h8 af[2][2], bf[2][NT];
+    auto read_frags = [&](int stage, int set) {
+        const uint32_t st = lds0 + (uint32_t)(stage * kK4StageBytes);
+        const unsigned char* wst = k4_smem + stage * kK4StageBytes + kBlockChunk * kK4RowPitch + lane * 16;
+        af[set][0] = *reinterpret_cast<const k4_h8*>(wst);
+        af[set][1] = *reinterpret_cast<const k4_h8*>(wst + 1024);
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             const uint32_t ad = st + bbase + (uint32_t)(nt * 64);
             const k4_hh4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4f16(reinterpret_cast<__attribute__((address_space(3))) k4_hh4*>(ad));
             const k4_hh4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4f16(reinterpret_cast<__attribute__((address_space(3))) k4_hh4*>(ad + (uint32_t)(4 * kK4RowPitch)));
-            bf[nt] = __builtin_shufflevector(__builtin_bit_cast(k4_h4, lo), __builtin_bit_cast(k4_h4, hi), 0, 1, 2, 3, 4, 5, 6, 7);
+            bf[set][nt] = __builtin_shufflevector(__builtin_bit_cast(k4_h4, lo), __builtin_bit_cast(k4_h4, hi), 0, 1, 2, 3, 4, 5, 6, 7);
+        }
+    };
+    // waits until this wavefront's direct loads of a chunk have landed, given how many younger chunks it has issued
+    auto wait_chunk = [&](int younger) {
+        if (younger >= 2) {
+            if (wload) asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        } else {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        }
+    };
+    auto step = [&](auto stage_tag, int c) {               // c % NS == S
+        constexpr int S = decltype(stage_tag)::value;
+        if (c + 1 < nch) {
+            wait_chunk(nch - 2 - c);                       // chunks c + 2 and c + 3 may still be in flight
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // this wavefront's reads of chunk c have left LDS before anyone refills its stage
+            __syncthreads();
+            if (c + NS < nch) issue(c + NS, S);
+            read_frags((S + 1) % NS, (S + 1) & 1);
         }
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt) acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[mt], bf[nt], acc[mt][nt], 0, 0, 0);
+            for (int mt = 0; mt < 2; ++mt) acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[S & 1][mt], bf[S & 1][nt], acc[mt][nt], 0, 0, 0);
+    };
+
+    fetch_rows();
+    if (nch > 0) {
+#pragma unroll
+        for (int c = 0; c < NS; ++c)
+            if (c < nch) issue(c, c);
+        k4_wait_vm((nch > NS ? NS - 1 : nch - 1) * (wload ? 5 : 4));
+        __syncthreads();
+        read_frags(0, 0);
+#pragma unroll 1
+        for (int c = 0; c < nch; c += NS) {
+            step(std::integral_constant<int, 0>{}, c);
+            if (c + 1 < nch) step(std::integral_constant<int, 1>{}, c + 1);
+            if (c + 2 < nch) step(std::integral_constant<int, 2>{}, c + 2);
+            if (c + 3 < nch) step(std::integral_constant<int, 3>{}, c + 3);
+        }
     }
     __syncthreads();                           // the ring is free: its memory becomes the wavefronts' corners
 
