@@ -121,6 +121,8 @@ def summarize(lay, t):
 
 
 BLOCK_WORKLOAD = "block_ffn_4096"
+# HBM-side bytes of one launch of the block-pruned product, measured as above (profiles/k4_block_gemm_block_ffn_4096.md)
+MEASURED_TRAFFIC_BLOCK = ("k4-2026-11-28-a", 184.45e6)
 
 
 def time_block_gemm(steps, warmup, check=True, npts=2000):
@@ -172,6 +174,12 @@ def time_block_gemm(steps, warmup, check=True, npts=2000):
     return res
 
 
+def block_traffic():
+    from paper_2206_10620_amd import pp_block_gemm as pb
+    rev, nbytes = MEASURED_TRAFFIC_BLOCK
+    return nbytes if rev == pb.BLOCK_KERNEL_REVISION else None
+
+
 def block_main(args):
     """--workload block_ffn_4096: the JSON line for the block-pruned matrix product alone (used for its profiles)."""
     r = time_block_gemm(args.steps, max(args.warmup, 20), check=not args.no_cpu, npts=2000000)
@@ -182,7 +190,7 @@ def block_main(args):
            "config": {"workload": lay.name, "m": lay.m, "k": lay.k, "n": lay.n, "block": [lay.bm, lay.bk],
                       "kept_weights": r["kept_weights"], "executed_weights": r["executed_weights"], "fused": "bias+relu"},
            "roofline": {"bound": "mfma", "achieved": r["executed_tflops"], "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s",
-                        "frac": r["frac_mfma_executed"], "traffic": None, "kernel": r["kernel"], "kernel_us": sec * 1e6,
+                        "frac": r["frac_mfma_executed"], "traffic": block_traffic(), "kernel": r["kernel"], "kernel_us": sec * 1e6,
                         "frac_effective": r["frac_mfma_effective"], "frac_hbm": r["frac_hbm"]}}
     if "max_rel_err" in r:
         import oracle

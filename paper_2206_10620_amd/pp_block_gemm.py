@@ -9,6 +9,10 @@ import numpy as np
 from .pp_conv import PP_OK, PP_F16, PP_F32, PP_FLAG_HOST_ONLY, PP_FLAG_RELU, PPError, lib as _conv_lib
 
 
+# Bumped whenever the device code of the matrix-core kernel changes (hardware-counter readings are keyed by it).
+BLOCK_KERNEL_REVISION = "k4-2026-11-28-a"
+
+
 class _Desc(C.Structure):
     _fields_ = [("m", C.c_int32), ("k", C.c_int32), ("block_m", C.c_int32), ("block_k", C.c_int32),
                 ("row_keep", C.c_void_p), ("col_keep", C.c_void_p), ("weights", C.c_void_p), ("bias", C.c_void_p),

@@ -31,6 +31,18 @@ def test_measured_traffic_belongs_to_the_current_kernel_revision():
         assert m and abs(float(m.group(1)) * 1e6 - nbytes) <= 0.02e6 + 1e-3 * nbytes
 
 
+def test_block_product_traffic_belongs_to_the_current_kernel_revision():
+    sys.path.insert(0, ROOT)
+    import bench
+    from paper_2206_10620_amd import pp_block_gemm as pb
+    rev, nbytes = bench.MEASURED_TRAFFIC_BLOCK
+    assert rev == pb.BLOCK_KERNEL_REVISION and nbytes > 0
+    text = open(os.path.join(ROOT, "profiles", "k4_block_gemm_block_ffn_4096.md")).read()
+    assert pb.BLOCK_KERNEL_REVISION in text
+    m = re.search(r"= ([0-9.]+) MB, against", text)
+    assert m and abs(float(m.group(1)) * 1e6 - nbytes) <= 0.02e6 + 1e-3 * nbytes
+
+
 def test_workload_table_covers_the_benchmark_configurations():
     sys.path.insert(0, ROOT)
     import bench
