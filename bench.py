@@ -68,7 +68,30 @@ def workloads():
         w[f"cfg3_resnet_c{c}_n1"] = (lambda i=i: synth.config3(1)[i])
     for i in range(13):
         w[f"cfg4_vgg_L{i + 1}"] = (lambda i=i: synth.config4()[i])
+    # The fp32 configurations again in binary16 storage (the paper fixes no precision): the same layers, so
+    # that the matrix-core path has a number on these shapes too.
+    w["cfg2_vgg_mid_f16"] = lambda: _as_f16(synth.config2())
+    for i, (c, hw) in enumerate(synth.RESNET_SHAPES):
+        w[f"cfg3_resnet_c{c}_n32_f16"] = (lambda i=i: _as_f16(synth.config3(32)[i]))
+    # A pattern table that is not the library's own (eight random centre-holding four-tap masks) on the shape of
+    # the VGG mid layer: fp32 falls back to the generic kernel, binary16 runs on the matrix cores like any table.
+    w["cfg2_shape_foreign_patterns_f32"] = lambda: _foreign("f32")
+    w["cfg2_shape_foreign_patterns_f16"] = lambda: _foreign("f16")
     return w
+
+
+def _as_f16(lay):
+    lay.dtype = "f16"
+    lay.name += "_f16"
+    return lay
+
+
+def _foreign(dtype):
+    import synth
+    own = set(int(m) for m in synth.PSET16)
+    masks = [m for m in synth.random_pattern_set(3, 4, 40, seed=11) if int(m) not in own][:8]
+    return synth.random_pruned_layer_k(f"cfg2_shape_foreign_patterns_{dtype}", 1, 256, 256, 56, 56, dtype, 3, np.array(masks), 0.3,
+                                       float(np.sqrt(2.0 / (4 * 0.3 * 256))), seed=5)
 
 
 def _events():

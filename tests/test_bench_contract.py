@@ -50,4 +50,5 @@ def test_workload_table_covers_the_benchmark_configurations():
     assert bench.DEFAULT_WORKLOAD == "cfg5_enhance_1080p"      # the largest single-GPU configuration
     assert {"cfg2_vgg_mid", "cfg5_enhance_1080p"} <= names
     assert sum(n.startswith("cfg4_vgg_L") for n in names) == 13
-    assert sum(n.startswith("cfg3_resnet_") for n in names) == 8
+    assert sum(n.startswith("cfg3_resnet_") and not n.endswith("_f16") for n in names) == 8
+    assert {"cfg2_vgg_mid_f16", "cfg2_shape_foreign_patterns_f32", "cfg2_shape_foreign_patterns_f16"} <= names
