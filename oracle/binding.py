@@ -11,15 +11,16 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "pp_oracle.cpp")
 _SRC_BLOCK = os.path.join(_HERE, "pp_block_oracle.cpp")
+_SRC_REUSE = os.path.join(_HERE, "pp_reuse_oracle.cpp")
 _SO = os.path.join(_HERE, "libpp_oracle.so")
 _lib = None
 
 
 def build(force: bool = False) -> str:
     """Compile the checker (host compiler only)."""
-    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_BLOCK))
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_BLOCK), os.path.getmtime(_SRC_REUSE))
     if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < newest:
-        subprocess.check_call(["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-pthread", "-o", _SO, _SRC, _SRC_BLOCK])
+        subprocess.check_call(["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-pthread", "-ffp-contract=off", "-o", _SO, _SRC, _SRC_BLOCK, _SRC_REUSE])
     return _SO
 
 
@@ -61,6 +62,12 @@ def lib() -> C.CDLL:
         L.oracle_gemm_at.restype = None
         L.oracle_block_brute.argtypes = [i32] * 5 + [vp] * 5 + [i32, vp]
         L.oracle_block_brute.restype = None
+        L.oracle_reuse_signatures.argtypes = [i32] * 4 + [vp] * 3
+        L.oracle_reuse_signatures.restype = i32
+        L.oracle_reuse_representatives.argtypes = [i32] * 3 + [vp] * 2
+        L.oracle_reuse_representatives.restype = None
+        L.oracle_reuse_apply.argtypes = [i32] * 5 + [vp] * 5 + [i32] + [vp] * 3
+        L.oracle_reuse_apply.restype = None
         _lib = L
     return _lib
 
@@ -350,3 +357,39 @@ def block_layer_reference(layer, x, relu=None, threads=None):
         w = widen_f16(round_f16(w))
     wd = block_expand(layer.m, layer.k, layer.bm, layer.bk, layer.row_keep, layer.col_keep, w)
     return gemm(wd, np.asarray(x, dtype=np.float64), layer.bias, layer.relu if relu is None else relu, True, True, threads)
+
+
+# ---- deep reuse (section 2.3.2) ----
+
+def reuse_signatures(x, hyperplanes, seg_len, hash_bits) -> np.ndarray:
+    """uint16 [n, k // seg_len]: sign-random-projection signature of every neuron vector (binary32, fixed order)."""
+    x, hp = _c(x, np.float32), _c(hyperplanes, np.float32)
+    n, k = x.shape
+    assert k % seg_len == 0 and hp.size == (k // seg_len) * hash_bits * seg_len
+    sig = np.empty((n, k // seg_len), dtype=np.uint16)
+    if lib().oracle_reuse_signatures(n, k, seg_len, hash_bits, _p(x), _p(hp), _p(sig)) != 0:
+        raise ValueError("bad deep-reuse shape")
+    return sig
+
+
+def reuse_representatives(sig, hash_bits) -> np.ndarray:
+    """int32 [S, 2**hash_bits]: lowest row index per cluster, -1 where empty."""
+    sig = _c(sig, np.uint16)
+    n, S = sig.shape
+    rep = np.empty((S, 1 << hash_bits), dtype=np.int32)
+    lib().oracle_reuse_representatives(n, S, hash_bits, _p(sig), _p(rep))
+    return rep
+
+
+def reuse_layer(x, w, hyperplanes, seg_len, hash_bits, bias=None, relu=False):
+    """(y, pre, scale, sig, rep) of the deep-reuse approximation of act(x @ w + bias); x [n, k] float32 values."""
+    sig = reuse_signatures(x, hyperplanes, seg_len, hash_bits)
+    rep = reuse_representatives(sig, hash_bits)
+    x64, w64 = _c(x, np.float64), _c(w, np.float64)
+    n, k = x64.shape
+    m = w64.shape[1]
+    assert w64.shape[0] == k
+    b = None if bias is None else _c(bias, np.float64)
+    y, pre, sc = (np.empty((n, m), dtype=np.float64) for _ in range(3))
+    lib().oracle_reuse_apply(n, k, m, seg_len, hash_bits, _p(x64), _p(w64), _p(b), _p(sig), _p(rep), int(relu), _p(y), _p(pre), _p(sc))
+    return y, pre, sc, sig, rep
