@@ -11,3 +11,4 @@ from .pp_conv import (PP_OK, PP_ERR_NULL, PP_ERR_SHAPE, PP_ERR_PATTERN, PP_ERR_U
 from .autotune import autotune, default_candidates
 from .pp_block_gemm import (BlockPlan, block_plan_from_layer, pp_block_gemm_plan, pp_block_gemm_run, pp_block_gemm_destroy,
                             pp_block_gemm_query, pp_block_gemm_unpack)
+from .pp_deep_reuse import (ReusePlan, reuse_plan_from_layer, pp_reuse_plan, pp_reuse_run, pp_reuse_read_clusters, pp_reuse_destroy)
