@@ -197,6 +197,76 @@ def time_block_gemm(steps, warmup, check=True, npts=2000):
     return res
 
 
+REUSE_WORKLOAD = "reuse_conv_64x64_56x56_n32"
+
+
+def time_deep_reuse(steps, warmup, check=True):
+    """Deep reuse (section 2.3.2) on the unfolded input of a 3x3, 64 -> 64 channel layer, 56 x 56 maps, batch 32
+    (100 352 rows of 576 values, binary32): hash + elect representatives, products once per cluster, gather-sum.
+    The rate is quoted in dense-equivalent GMAC/s (rows x k x m per second: the product it stands in for);
+    the pass is memory-bound, so the roofline is HBM on algorithmic bytes (x once, y once)."""
+    import torch
+    import synth
+    import paper_2206_10620_amd as pp
+    lay = synth.conv_shaped_reuse_layer()
+    x_np = lay.make_input()
+    x = torch.from_numpy(x_np).cuda()
+    y = torch.empty((lay.n, lay.m), dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    plan = pp.reuse_plan_from_layer(lay)
+    for _ in range(warmup):
+        plan.run(x, y, stream)
+    torch.cuda.synchronize()
+    ev0, ev1 = _events()
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(steps):
+        plan.run(x, y, stream)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) / steps
+    sec = ev0.elapsed_time(ev1) * 1e-3 / steps
+    sig, rep = plan.clusters(lay.n)
+    plan.close()
+    clusters = int((rep >= 0).sum())
+    res = dict(workload=lay.name, dtype="f32", n=lay.n, k=lay.k, m=lay.m, seg_len=lay.seg_len, hash_bits=lay.hash_bits,
+               neuron_vectors=lay.n * lay.segments, clusters=clusters, dense_gmacs=lay.dense_macs / 1e9, alg_mb=lay.alg_bytes / 1e6,
+               us_per_step=sec * 1e6, wall_us_per_step=wall * 1e6, dense_equiv_gmac_per_s=lay.dense_macs / sec / 1e9,
+               alg_gb_per_s=lay.alg_bytes / sec / 1e9, frac_hbm=lay.alg_bytes / sec / 1e9 / PEAK_HBM_GBS)
+    if check:
+        import oracle
+        from oracle.compare import error_report
+        c0 = time.perf_counter()
+        ref, pre, scale, rsig, rrep = oracle.reuse_layer(x_np, lay.weights, lay.hyperplanes, lay.seg_len, lay.hash_bits, lay.bias, lay.relu)
+        res["cpu_seconds"] = time.perf_counter() - c0
+        res["max_rel_err"] = error_report(y.cpu().numpy(), ref, pre, scale)["E"]
+        res["clusters_match_checker"] = bool(np.array_equal(sig, rsig) and np.array_equal(rep, rrep))
+        exact = np.maximum(x_np.astype(np.float64) @ lay.weights.astype(np.float64) + lay.bias.astype(np.float64), 0.0)
+        res["approximation_normwise_vs_exact_product"] = float(np.linalg.norm(ref - exact) / np.linalg.norm(exact))
+    res["_sec"], res["_wall"], res["_lay"] = sec, wall, lay
+    return res
+
+
+def reuse_main(args):
+    """--workload reuse_conv_64x64_56x56_n32: the JSON line for deep reuse alone (used for its profile)."""
+    r = time_deep_reuse(args.steps, max(args.warmup, 10), check=not args.no_cpu)
+    sec, wall, lay = r.pop("_sec"), r.pop("_wall"), r.pop("_lay")
+    out = {"metric": "dense-equivalent GMAC/s, deep reuse", "value": lay.dense_macs / wall / 1e9, "unit": "GMAC/s", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall * 1e3, "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {k: r[k] for k in ("workload", "n", "k", "m", "seg_len", "hash_bits", "neuron_vectors", "clusters")},
+           "roofline": {"bound": "hbm", "achieved": r["alg_gb_per_s"], "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": r["frac_hbm"],
+                        "traffic": None, "kernel": "reuse_hash + reuse_products + reuse_gather", "kernel_us": sec * 1e6}}
+    if "max_rel_err" in r:
+        import oracle
+        out["cpu_baseline"] = {"value": lay.dense_macs / r["cpu_seconds"] / 1e9, "unit": "GMAC/s", "cores": 1, "kind": "oracle",
+                               "sample": "the whole layer, one pass", "seconds": r["cpu_seconds"]}
+        out["max_rel_err"] = r["max_rel_err"]
+        out["clusters_match_checker"] = r["clusters_match_checker"]
+        out["approximation_normwise_vs_exact_product"] = r["approximation_normwise_vs_exact_product"]
+    print(json.dumps(out))
+
+
 def block_traffic():
     from paper_2206_10620_amd import pp_block_gemm as pb
     rev, nbytes = MEASURED_TRAFFIC_BLOCK
@@ -352,6 +422,9 @@ def main():
     if args.workload == BLOCK_WORKLOAD:
         block_main(args)
         return
+    if args.workload == REUSE_WORKLOAD:
+        reuse_main(args)
+        return
     table = workloads()
     lay = table[args.workload]()
     tuning = None
@@ -433,6 +506,10 @@ def main():
         others.append(time_vgg_stack(steps=20, warmup=5))
         blk = time_block_gemm(steps=50, warmup=10, check=not args.no_cpu)
         others.append({k: v for k, v in blk.items() if not k.startswith("_")})
+        del blk
+        torch.cuda.empty_cache()
+        reu = time_deep_reuse(steps=20, warmup=5, check=not args.no_cpu)
+        others.append({k: v for k, v in reu.items() if not k.startswith("_")})
         out["others"] = others
 
     print(json.dumps(out))

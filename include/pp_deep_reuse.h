@@ -46,9 +46,10 @@ typedef struct {
 } pp_reuse_desc_t;
 
 /* Validates (before any device call; *out_plan is NULL on error), uploads weights, bias and hyperplanes and
- * allocates the workspace: signatures [k/L][n_max] (16 bit), representatives [k/L][2^H] (32 bit) and the
+ * allocates the workspace: signatures [n_max][k/L] (16 bit), representatives [k/L][2^H] (32 bit) and the
  * cluster products [k/L][2^H][m] (binary32).  PP_ERR_SHAPE: a size out of range, k not a multiple of
- * seg_len, or n_max * max(k, m) beyond 2^31 - 1. */
+ * seg_len, or n_max * max(k, m) beyond 2^31 - 1.  PP_ERR_UNSUPPORTED: an unknown flag, or hyperplanes that do not fit
+ * 64 KB of LDS ((k/L) * (H*L + 1) * 4 bytes). */
 pp_status_t pp_reuse_plan(const pp_reuse_desc_t *desc, pp_reuse_plan_t **out_plan);
 
 /* Enqueue one pass over n rows (1 <= n <= n_max): four kernels on hip_stream (clear the representatives,

@@ -2,16 +2,15 @@
 //
 // Four launches per pass:
 //   reuse_clear     representatives <- "none"
-//   reuse_hash      one lane per row and segment: the L values go through LDS (read from memory in runs of L
-//                   consecutive floats, then one row per lane), the hyperplanes are wave-uniform scalar loads;
-//                   signature bits are signs of binary32 fused multiply-add chains; the lowest row of every
-//                   cluster is elected with integer minimum atomics, first inside the workgroup's LDS table,
-//                   then one global atomic per cluster the workgroup touched
+//   reuse_hash      one lane per neuron vector, segments fastest (a wavefront reads one contiguous stretch of x),
+//                   hyperplanes in LDS; signature bits are signs of binary32 fused multiply-add chains; the
+//                   lowest row of every cluster is elected with integer minimum atomics
 //   reuse_products  P[s][g][:] = x[rep(s,g)][segment s] . W[segment s][:]
 //   reuse_gather    y[i][:] = act(bias + sum_s P[s][sig(i,s)][:])
 // Integer work (signatures, representatives) is deterministic; the float sums run in a fixed order.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <climits>
 #include <cstdint>
 #include <new>
@@ -21,7 +20,6 @@
 
 namespace {
 
-constexpr int kRows = 256;          // rows per workgroup of reuse_hash
 constexpr int kMaxSeg = 32;
 
 typedef const __attribute__((address_space(4))) float* const_f32;
@@ -31,50 +29,51 @@ __global__ __launch_bounds__(256) void reuse_clear(int32_t* rep, int count) {
     if (e < count) rep[e] = INT_MAX;
 }
 
-template <int L>
-__device__ __forceinline__ unsigned hash_row(const float* xv, const_f32 hp, int hash_bits) {
-    unsigned g = 0;
-    for (int h = 0; h < hash_bits; ++h) {
-        float p = 0.0f;
-#pragma unroll
-        for (int l = 0; l < L; ++l) p = __builtin_fmaf(xv[l], hp[h * L + l], p);
-        g |= (p > 0.0f ? 1u : 0u) << h;
-    }
-    return g;
-}
-
-// grid (ceil(n / 256)); dynamic LDS: 256 * (L + 1) floats + 2^H ints
+// One lane per neuron vector, segments fastest: consecutive lanes read consecutive runs of L floats of x, so a
+// wavefront reads one contiguous stretch of memory (a lane per row, with the hyperplanes as wave-uniform scalar
+// operands, was measured ten times slower: its loads are a cache line apart).  The hyperplanes of all segments
+// sit in LDS, loaded once per workgroup, which then walks the neuron vectors with the stride of the grid; the
+// segment pitch is H * L + 1 floats, so lanes on different segments use different banks.  A lane's signature
+// bits are the signs of H chains of fused multiply-adds in ascending l.  The representative of a cluster is
+// the lowest row: one integer minimum atomic per lane, skipped when the table already holds a row at least as
+// low (the table only ever decreases, so a stale read can cost an atomic, never a wrong result).
 template <int L>
 __global__ __launch_bounds__(256) void reuse_hash(const float* __restrict__ x, const float* __restrict__ hyper, uint16_t* __restrict__ sig,
-                                                  int32_t* __restrict__ rep, int n, int k, int hash_bits, int n_max) {
+                                                  int32_t* __restrict__ rep, int n, int k, int hash_bits) {
     extern __shared__ __attribute__((aligned(16))) unsigned char reuse_smem[];
-    float* tile = reinterpret_cast<float*>(reuse_smem);                         // [256][L + 1]
-    int32_t* table = reinterpret_cast<int32_t*>(tile + kRows * (L + 1));        // [2^H]
-    const int t = (int)threadIdx.x, i0 = (int)blockIdx.x * kRows, i = i0 + t;
-    const int S = k / L, G = 1 << hash_bits;
-    const int rows_here = n - i0 < kRows ? n - i0 : kRows;
-    const const_f32 hp_all = (const_f32)(uintptr_t)hyper;
-    for (int s = 0; s < S; ++s) {
-        for (int g = t; g < G; g += 256) table[g] = INT_MAX;
-        for (int e = t; e < rows_here * L; e += 256) {
-            const int row = e / L, l = e - row * L;
-            tile[row * (L + 1) + l] = x[(int64_t)(i0 + row) * k + s * L + l];
-        }
-        __syncthreads();
-        if (i < n) {
-            float xv[L];
+    float* hp = reinterpret_cast<float*>(reuse_smem);
+    const int S = k / L, G = 1 << hash_bits, pitch = hash_bits * L + 1;
+    for (int e = (int)threadIdx.x; e < S * hash_bits * L; e += 256) {
+        const int s = e / (hash_bits * L);
+        hp[s * pitch + (e - s * hash_bits * L)] = hyper[e];
+    }
+    __syncthreads();
+    const uint32_t total = (uint32_t)n * (uint32_t)S;              // below 2^31: n * k is
+    for (uint32_t e = blockIdx.x * 256u + threadIdx.x; e < total; e += gridDim.x * 256u) {      // e = i * S + s
+        const int i = (int)(e / (uint32_t)S), s = (int)(e - (uint32_t)i * (uint32_t)S);
+        float xv[L];
+        const float* src = x + (int64_t)e * L;                      // row i, columns s L ..: rows are k = S L floats long
+        if constexpr (L % 4 == 0) {
 #pragma unroll
-            for (int l = 0; l < L; ++l) xv[l] = tile[t * (L + 1) + l];
-            const unsigned g = hash_row<L>(xv, hp_all + (int64_t)s * hash_bits * L, hash_bits);
-            sig[(int64_t)s * n_max + i] = (uint16_t)g;
-            atomicMin(&table[g], i);
+            for (int l = 0; l < L; l += 4) {
+                const float4 v = *reinterpret_cast<const float4*>(src + l);
+                xv[l] = v.x, xv[l + 1] = v.y, xv[l + 2] = v.z, xv[l + 3] = v.w;
+            }
+        } else {
+#pragma unroll
+            for (int l = 0; l < L; ++l) xv[l] = src[l];
         }
-        __syncthreads();
-        for (int g = t; g < G; g += 256) {
-            const int v = table[g];
-            if (v != INT_MAX) atomicMin(&rep[(int64_t)s * G + g], v);
+        const float* h0 = hp + s * pitch;
+        unsigned g = 0;
+        for (int h = 0; h < hash_bits; ++h) {
+            float p = 0.0f;
+#pragma unroll
+            for (int l = 0; l < L; ++l) p = __builtin_fmaf(xv[l], h0[h * L + l], p);
+            g |= (p > 0.0f ? 1u : 0u) << h;
         }
-        __syncthreads();
+        sig[e] = (uint16_t)g;
+        int32_t* slot = rep + (int64_t)s * G + g;
+        if (__builtin_nontemporal_load(slot) > i) atomicMin(slot, i);
     }
 }
 
@@ -85,25 +84,46 @@ __global__ __launch_bounds__(256) void reuse_products(const float* __restrict__ 
     if (e >= G * m) return;
     const int g = e / m, c = e - g * m;
     const int r = rep[(int64_t)s * G + g];
+    if (r == INT_MAX) return;                                       // an empty cluster: nobody reads its products
     float acc = 0.0f;
-    if (r != INT_MAX)
-        for (int l = 0; l < L; ++l) acc = __builtin_fmaf(x[(int64_t)r * k + s * L + l], w[(int64_t)(s * L + l) * m + c], acc);
+    for (int l = 0; l < L; ++l) acc = __builtin_fmaf(x[(int64_t)r * k + s * L + l], w[(int64_t)(s * L + l) * m + c], acc);
     P[((int64_t)s * G + g) * m + c] = acc;
 }
 
-// one lane per output element, columns fastest
+// V output columns per lane (4 when m is a multiple of 4, else 1), columns fastest
+template <int V>
 __global__ __launch_bounds__(256) void reuse_gather(const uint16_t* __restrict__ sig, const float* __restrict__ P, const float* __restrict__ bias,
-                                                    float* __restrict__ y, int n, int m, int S, int G, int n_max, int relu) {
+                                                    float* __restrict__ y, int n, int m, int S, int G, int relu) {
+    const int mv = m / V;
     const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (e >= (int64_t)n * m) return;
-    const int i = (int)(e / m), c = (int)(e - (int64_t)i * m);
-    float acc = bias[c];
-    for (int s = 0; s < S; ++s) acc += P[((int64_t)s * G + sig[(int64_t)s * n_max + i]) * m + c];
-    if (relu) acc = acc > 0.0f ? acc : 0.0f;
-    y[e] = acc;
+    if (e >= (int64_t)n * mv) return;
+    const int i = (int)(e / mv), c = (int)(e - (int64_t)i * mv) * V;
+    float acc[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) acc[v] = bias[c + v];
+    const uint16_t* srow = sig + (int64_t)i * S;
+    for (int s = 0; s < S; ++s) {
+        const float* p = P + ((int64_t)s * G + srow[s]) * m + c;
+        if constexpr (V == 4) {
+            const float4 v4 = *reinterpret_cast<const float4*>(p);
+            acc[0] += v4.x, acc[1] += v4.y, acc[2] += v4.z, acc[3] += v4.w;
+        } else {
+            acc[0] += p[0];
+        }
+    }
+#pragma unroll
+    for (int v = 0; v < V; ++v)
+        if (relu) acc[v] = acc[v] > 0.0f ? acc[v] : 0.0f;
+    if constexpr (V == 4) {
+        float4 o;
+        o.x = acc[0], o.y = acc[1], o.z = acc[2], o.w = acc[3];
+        *reinterpret_cast<float4*>(y + (int64_t)i * m + c) = o;
+    } else {
+        y[(int64_t)i * m + c] = acc[0];
+    }
 }
 
-typedef void (*hash_fn)(const float*, const float*, uint16_t*, int32_t*, int, int, int, int);
+typedef void (*hash_fn)(const float*, const float*, uint16_t*, int32_t*, int, int, int);
 template <int L> hash_fn pick_hash(int seg_len) {
     if constexpr (L == 0) return nullptr;
     else return seg_len == L ? reuse_hash<L> : pick_hash<L - 1>(seg_len);
@@ -152,6 +172,8 @@ pp_status_t pp_reuse_plan(const pp_reuse_desc_t* d, pp_reuse_plan_t** out_plan) 
         return PP_ERR_SHAPE;
     if ((int64_t)d->n_max * std::max(d->k, d->m) >= ((int64_t)1 << 31) || (int64_t)d->k * d->m >= ((int64_t)1 << 31)) return PP_ERR_SHAPE;
     if (d->flags & ~(uint32_t)(PP_FLAG_RELU | PP_FLAG_HOST_ONLY)) return PP_ERR_UNSUPPORTED;
+    // the hash kernel keeps every segment's hyperplanes in LDS (H * L + 1 floats per segment)
+    if ((int64_t)(d->k / d->seg_len) * (d->hash_bits * d->seg_len + 1) * 4 > 64 * 1024) return PP_ERR_UNSUPPORTED;
     pp_reuse_plan_t* p = new (std::nothrow) pp_reuse_plan_t();
     if (!p) return PP_ERR_ALLOC;
     p->k = d->k, p->m = d->m, p->L = d->seg_len, p->H = d->hash_bits, p->n_max = d->n_max, p->flags = d->flags;
@@ -195,13 +217,19 @@ pp_status_t pp_reuse_run(const pp_reuse_plan_t* p, const void* x_dev, void* y_de
     if (!hash) return PP_ERR_UNSUPPORTED;
     (void)hipGetLastError();
     hipLaunchKernelGGL(reuse_clear, dim3((unsigned)((S * G + 255) / 256)), dim3(256), 0, stream, p->d_rep, S * G);
-    const size_t lds = (size_t)kRows * (p->L + 1) * 4 + (size_t)G * 4;
-    hipLaunchKernelGGL(hash, dim3((unsigned)((n + kRows - 1) / kRows)), dim3(256), lds, stream, x, p->d_hyper, p->d_sig, p->d_rep, n, p->k, p->H, p->n_max);
+    const size_t lds = (size_t)S * (p->H * p->L + 1) * 4;
+    const int64_t hash_blocks = std::min<int64_t>(((int64_t)n * S + 255) / 256, 256 * 8);      // at most eight workgroups per compute unit
+    hipLaunchKernelGGL(hash, dim3((unsigned)hash_blocks), dim3(256), lds, stream, x, p->d_hyper, p->d_sig, p->d_rep, n, p->k, p->H);
     hipLaunchKernelGGL(reuse_products, dim3((unsigned)((G * p->m + 255) / 256), (unsigned)S), dim3(256), 0, stream, x, p->d_w, p->d_rep, p->d_P, p->k,
                        p->m, p->L, G);
-    const int64_t outs = (int64_t)n * p->m;
-    hipLaunchKernelGGL(reuse_gather, dim3((unsigned)((outs + 255) / 256)), dim3(256), 0, stream, p->d_sig, p->d_P, p->d_bias, y, n, p->m, S, G,
-                       p->n_max, (p->flags & PP_FLAG_RELU) ? 1 : 0);
+    const int relu = (p->flags & PP_FLAG_RELU) ? 1 : 0;
+    if (p->m % 4 == 0) {
+        const int64_t lanes = (int64_t)n * (p->m / 4);
+        hipLaunchKernelGGL(reuse_gather<4>, dim3((unsigned)((lanes + 255) / 256)), dim3(256), 0, stream, p->d_sig, p->d_P, p->d_bias, y, n, p->m, S, G, relu);
+    } else {
+        const int64_t lanes = (int64_t)n * p->m;
+        hipLaunchKernelGGL(reuse_gather<1>, dim3((unsigned)((lanes + 255) / 256)), dim3(256), 0, stream, p->d_sig, p->d_P, p->d_bias, y, n, p->m, S, G, relu);
+    }
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_DEVICE;
 }
 
@@ -213,10 +241,7 @@ pp_status_t pp_reuse_read_clusters(const pp_reuse_plan_t* p, int32_t n, uint16_t
     const int S = p->k / p->L, G = 1 << p->H;
     try {
         if (sig_out) {
-            std::vector<uint16_t> tmp((size_t)S * p->n_max);
-            if (hipMemcpy(tmp.data(), p->d_sig, tmp.size() * 2, hipMemcpyDeviceToHost) != hipSuccess) return PP_ERR_DEVICE;
-            for (int i = 0; i < n; ++i)
-                for (int s = 0; s < S; ++s) sig_out[(size_t)i * S + s] = tmp[(size_t)s * p->n_max + i];
+            if (hipMemcpy(sig_out, p->d_sig, (size_t)n * S * 2, hipMemcpyDeviceToHost) != hipSuccess) return PP_ERR_DEVICE;
         }
         if (rep_out) {
             if (hipMemcpy(rep_out, p->d_rep, (size_t)S * G * 4, hipMemcpyDeviceToHost) != hipSuccess) return PP_ERR_DEVICE;

@@ -25,6 +25,8 @@ def test_error_paths_need_no_device():
     assert pp.pp_reuse_plan(**args(hash_bits=13))[0] == pp.PP_ERR_SHAPE
     assert pp.pp_reuse_plan(**args(n_max=0))[0] == pp.PP_ERR_SHAPE
     assert pp.pp_reuse_plan(**args(flags=H | 2))[0] == pp.PP_ERR_UNSUPPORTED
+    big = synth.random_reuse_layer("big", 8, 4096, 2, 2, 12, 3)
+    assert pp.pp_reuse_plan(4096, 2, 2, 12, 8, big.weights, None, big.hyperplanes, H)[0] == pp.PP_ERR_UNSUPPORTED   # hyperplanes beyond LDS
     st, h = pp.pp_reuse_plan(**args(bias=None))
     assert st == pp.PP_OK
     try:
