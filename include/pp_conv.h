@@ -67,8 +67,8 @@ enum {
 /* Execution parameters (the part of the layer-wise representation that the paper leaves to tuning,
  * section 2.3.1).  A zero field means "let the library choose". */
 typedef struct {
-    int32_t variant;        /* 0 auto; 1 generic kernel (any layer); 2 tiled pattern-specialised kernel (3x3, stride 1,
-                               the library's sixteen masks); 3 matrix-core kernel (binary16 storage only: the pruned
+    int32_t variant;        /* 0 auto; 1 generic kernel (any layer); 2 tiled pattern-specialised kernel (3x3, stride 1, no
+                               fused pool; masks outside its sixteen run as covers of those with zero weights); 3 matrix-core kernel (binary16 storage only: the pruned
                                weights zero-filled to a dense matrix and multiplied on the MFMA units -- the measured
                                alternative to pattern-specialised vector code; any pattern table, kernel size, stride) */
     int32_t filters_per_wave; /* F: output filters whose accumulators one wavefront holds (4, 8 or 16) */

@@ -18,6 +18,59 @@ int builtin_slot(uint64_t mask) {
     return -1;
 }
 
+// The fewest built-in patterns (at most three) whose union holds every tap of `mask`; src[j] is the index,
+// among the mask's own taps in ascending order, of the weight that goes to the part's j-th tap, or -1.
+std::vector<CoverPart> cover_pattern(uint32_t mask) {
+    auto part_list = [&](const int* slots, int count) {
+        std::vector<CoverPart> parts;
+        uint32_t given = 0;
+        for (int i = 0; i < count; ++i) {
+            CoverPart c;
+            c.slot = slots[i];
+            int j = 0;
+            for (int tap = 0; tap < 9; ++tap) {
+                if (!((kBuiltinMasks[slots[i]] >> tap) & 1u)) continue;
+                const uint32_t bit = 1u << tap;
+                if ((mask & bit) && !(given & bit)) {
+                    int idx = 0;
+                    for (int t2 = 0; t2 < tap; ++t2) idx += (mask >> t2) & 1u;
+                    c.src[j] = idx;
+                    given |= bit;
+                } else {
+                    c.src[j] = -1;
+                }
+                ++j;
+            }
+            parts.push_back(c);
+        }
+        return parts;
+    };
+    if (mask == 0x1FFu) {                       // the unpruned kernel keeps the cover it has been measured with
+        const int slots[3] = {4, 7, 8};
+        return part_list(slots, 3);
+    }
+    const int own = builtin_slot(mask);
+    if (own >= 0) return part_list(&own, 1);
+    const int N = kBuiltinPatterns;
+    for (int a = 0; a < N; ++a)
+        if ((kBuiltinMasks[a] & mask) == mask) return part_list(&a, 1);
+    for (int a = 0; a < N; ++a)
+        for (int b = a + 1; b < N; ++b)
+            if (((kBuiltinMasks[a] | kBuiltinMasks[b]) & mask) == mask) {
+                const int slots[2] = {a, b};
+                return part_list(slots, 2);
+            }
+    for (int a = 0; a < N; ++a)
+        for (int b = a + 1; b < N; ++b)
+            for (int c = b + 1; c < N; ++c)
+                if (((kBuiltinMasks[a] | kBuiltinMasks[b] | kBuiltinMasks[c]) & mask) == mask) {
+                    const int slots[3] = {a, b, c};
+                    return part_list(slots, 3);
+                }
+    const int slots[3] = {4, 7, 8};             // these three hold all nine taps
+    return part_list(slots, 3);
+}
+
 }  // namespace
 
 uint16_t f32_to_f16_rne(float v) {
@@ -240,20 +293,27 @@ pp_status_t build_layouts(const pp_conv_desc_t& d, HostPlan& hp) {
 
     // can the tiled kernel express this layer?  (3x3, stride 1, no pooling, and a pattern table made of
     // the masks it has specialised code for)
-    std::vector<int> slot_of(hp.num_patterns, -1);
-    // An unpruned (nine-tap) kernel is run as three four-tap kernels on the same channel whose
-    // patterns cover the 3x3 window: {0,1,3,4}, {4,5,7,8} with a zero centre weight, and
-    // {0,2,4,6} with zero weights on taps 0 and 4 (12 multiply-accumulates for 9 weights).
+    // A pattern the kernel has no specialised code for is run as up to three of its own four-tap patterns
+    // on the same channel whose union covers the pattern's taps; every tap is given to the first of
+    // them that holds it and the other positions carry zero weights.  An unpruned (nine-tap) kernel is
+    // the extreme case: {0,1,3,4}, {4,5,7,8} with a zero centre weight, and {0,2,4,6} with zero
+    // weights on taps 0 and 4 (12 multiply-accumulates for 9 weights).  This is the plan-time side of
+    // "code for the patterns the layer has" (section 2.3.1) without generating code: a foreign table
+    // costs extra multiply-accumulates on zeros, not the loss of tiling and reuse.
     const bool dense = hp.taps == 9 && hp.ks == 3;
-    bool builtin = hp.ks == 3 && hp.stride == 1 && !hp.pool && (dense || hp.taps == 4);
-    int max_slot = dense ? 8 : -1;
-    if (builtin && !dense) {
+    bool builtin = hp.ks == 3 && hp.stride == 1 && !hp.pool;
+    int max_slot = -1;
+    bool covered = false;                                     // some pattern needs more than its own slot
+    std::vector<std::vector<CoverPart>>& cover = hp.tl.cover;
+    cover.assign(hp.num_patterns, {});
+    if (builtin) {
         std::vector<char> used(hp.num_patterns, 0);
         for (uint8_t p : hp.canon.kpat) used[p] = 1;
         for (int p = 0; p < hp.num_patterns; ++p) {
-            slot_of[p] = builtin_slot(hp.masks[p]);
-            if (used[p] && slot_of[p] < 0) builtin = false;
-            if (used[p]) max_slot = std::max(max_slot, slot_of[p]);
+            if (!used[p]) continue;
+            cover[p] = cover_pattern(dense ? 0x1FFu : (uint32_t)hp.masks[p]);
+            covered = covered || cover[p].size() != 1 || hp.taps != 4;
+            for (const CoverPart& c : cover[p]) max_slot = std::max(max_slot, c.slot);
         }
     }
     // The matrix-core kernel takes any layer whose storage is binary16.  Measured on MI355X it beats the
@@ -272,6 +332,7 @@ pp_status_t build_layouts(const pp_conv_desc_t& d, HostPlan& hp) {
     if (!hp.tiled) return PP_OK;
 
     TiledLayout& tl = hp.tl;
+    tl.covered = covered;
     const int eb = hp.dtype == PP_F16 ? 2 : 4;
     tl.np = max_slot < 8 ? 8 : 16;
     tl.entry_words = hp.dtype == PP_F16 ? 4 : 8;   // header + two words of binary16 pairs, or header + 3 spare + 4 fp32
@@ -410,7 +471,6 @@ pp_status_t build_layouts(const pp_conv_desc_t& d, HostPlan& hp) {
     hp.chosen.balance = balance ? 2 : 1;
     tl.slot_pos.assign((size_t)G * F, -1);
     tl.chan_map.assign((size_t)NFB * Q * CC, -1);
-    const int per_kernel = dense ? 3 : 1;
     std::vector<float> cost;
     std::vector<double> load, share, sums;
     std::vector<int> room, left;
@@ -440,7 +500,7 @@ pp_status_t build_layouts(const pp_conv_desc_t& d, HostPlan& hp) {
             for (int fl = 0; fl < F; ++fl) {
                 const int pos = tl.slot_pos[(size_t)(g0 + g) * F + fl];
                 if (pos < 0) continue;
-                for (int64_t e = hp.filt_off[pos]; e < hp.filt_off[pos + 1]; ++e) cost[(size_t)g * C + cn.kidx[e]] += (float)per_kernel;
+                for (int64_t e = hp.filt_off[pos]; e < hp.filt_off[pos + 1]; ++e) cost[(size_t)g * C + cn.kidx[e]] += (float)tl.cover[cn.kpat[e]].size();
             }
         share.assign(ng, 0.0);
         for (int g = 0; g < ng; ++g)
@@ -486,8 +546,6 @@ pp_status_t build_layouts(const pp_conv_desc_t& d, HostPlan& hp) {
 
     // ---- weight stream: one sequence of entries per (filter group, channel split) wavefront ----
     struct Item { int32_t ci; int32_t fl; int32_t slot; int64_t src; int32_t part; };
-    static const int kDenseSlot[3] = {4, 7, 8};                       // built-in slots of the three cover patterns
-    static const int kDenseTap[3][4] = {{0, 1, 3, 4}, {-1, 5, 7, 8}, {-1, 2, -1, 6}};   // source tap of each weight, -1: zero
     tl.stream.clear();
     const int SW = tl.sw;
     tl.wave_off.assign((size_t)G * KS * SW, 0);
@@ -517,11 +575,8 @@ pp_status_t build_layouts(const pp_conv_desc_t& d, HostPlan& hp) {
             const int pos = tl.slot_pos[(size_t)g * F + fl];
             if (pos < 0) continue;
             for (int64_t e = hp.filt_off[pos]; e < hp.filt_off[pos + 1]; ++e) {
-                if (!dense) {
-                    items.push_back(Item{cn.kidx[e], fl, slot_of[cn.kpat[e]], e, 0});
-                } else {
-                    for (int part = 0; part < 3; ++part) items.push_back(Item{cn.kidx[e], fl, kDenseSlot[part], e, part});
-                }
+                const std::vector<CoverPart>& parts = tl.cover[cn.kpat[e]];
+                for (int part = 0; part < (int)parts.size(); ++part) items.push_back(Item{cn.kidx[e], fl, parts[part].slot, e, part});
             }
         }
         std::sort(items.begin(), items.end(), [](const Item& a, const Item& b) {
@@ -544,16 +599,10 @@ pp_status_t build_layouts(const pp_conv_desc_t& d, HostPlan& hp) {
                         const Item& k = items[j];
                         const uint32_t code = (uint32_t)(k.fl * tl.np + k.slot);
                         const uint32_t chan = j == first[ci] ? (uint32_t)cl * chan_stride_bytes : kSameChannel;
-                        if (!dense) {
-                            push_entry(code, chan, &cn.wpacked[(size_t)k.src * 4]);
-                        } else {
-                            float w4[4];
-                            for (int j4 = 0; j4 < 4; ++j4) {
-                                const int tap = kDenseTap[k.part][j4];
-                                w4[j4] = tap < 0 ? 0.0f : cn.wpacked[(size_t)k.src * 9 + tap];
-                            }
-                            push_entry(code, chan, w4);
-                        }
+                        const CoverPart& part = tl.cover[cn.kpat[k.src]][k.part];
+                        float w4[4];
+                        for (int j4 = 0; j4 < 4; ++j4) w4[j4] = part.src[j4] < 0 ? 0.0f : cn.wpacked[(size_t)k.src * hp.taps + part.src[j4]];
+                        push_entry(code, chan, w4);
                     }
                 }
                 push_entry(kEndCode, kSameChannel, nullptr);
@@ -775,7 +824,7 @@ pp_status_t build_mfma_layout(const pp_conv_tuning_t& t, HostPlan& hp) {
 }
 
 pp_status_t unpack_stream(const HostPlan& hp, int32_t* kidx, uint8_t* kpat, float* w) {
-    if (!hp.tiled || hp.taps != 4) return PP_ERR_UNSUPPORTED;
+    if (!hp.tiled || hp.taps != 4 || hp.tl.covered) return PP_ERR_UNSUPPORTED;
     const TiledLayout& tl = hp.tl;
     const int EW = tl.entry_words;
     // slot -> lowest pattern id carrying that mask

@@ -20,6 +20,13 @@ struct Canonical {          // tuning-independent result of the reorder
     int64_t k_kept = 0;
 };
 
+// One built-in four-tap pattern standing in for (part of) a layer pattern: its slot, and for each of its four
+// taps (ascending) the index of the layer kernel's weight that goes there, or -1 for a zero.
+struct CoverPart {
+    int slot = 0;
+    int src[4] = {-1, -1, -1, -1};
+};
+
 struct TiledLayout {        // geometry of the tiled kernel for one plan
     int np = 0;             // pattern slots compiled in (8 or 16)
     int f = 0, r = 0, lw = 0, wf = 0, ks = 0, cc = 0;
@@ -29,6 +36,8 @@ struct TiledLayout {        // geometry of the tiled kernel for one plan
     int groups = 0;         // G = ceil(c_out / f)
     int chunks = 0;         // Q = ceil(c_in / cc)
     int entry_words = 8;    // 32-bit words per entry: 8 (code, channel, 2 spare, 4 fp32 weights) or 4 (code, 2 words of binary16 pairs, channel)
+    bool covered = false;   // some pattern runs as several built-in patterns with zero weights (no round trip of the stream)
+    std::vector<std::vector<CoverPart>> cover;   // [pattern] the built-in patterns that stand for it
     int32_t idle_off = 0;   // first entry of the run of end-of-chunk entries walked by wavefronts without a filter group
     std::vector<uint32_t> stream;      // entries
     std::vector<int32_t> wave_off;     // [G*ks*sw] first entry of each (group, split) wavefront stream in each workgroup share

@@ -210,10 +210,27 @@ def test_foreign_patterns_and_dense_layer():
     lay = synth.random_pruned_layer("foreign", 2, 6, 10, 9, 11, "f32", np.array([0x00F, 0x1E0, 0x03A, 0x145], dtype=np.uint16),
                                     0.7, 0.3, seed=1)
     rep, _ = check_layer(lay, label="foreign")
+    assert rep["chosen"]["variant"] == 2                       # runs as a cover of the kernel's own patterns
+    rep, _ = check_layer(lay, tuning=T(variant=1), label="foreign-generic")
     assert rep["chosen"]["variant"] == 1
     for dtype in ("f32", "f16"):
         lay = synth.dense_layer("dense", 2, 3, 16, 12, 20, dtype, 0.3, seed=2)
         rep, _ = check_layer(lay, label="dense")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("taps", [1, 2, 3, 4, 5, 6, 8, 9])
+def test_any_three_by_three_pattern_table_on_the_tiled_kernel(taps, dtype):
+    """Random masks with any number of taps (with or without the centre) are covered by at most three of the
+    kernel's own patterns with zero weights; several tile shapes so that the covers meet every code path."""
+    rs = np.random.RandomState(taps)
+    masks = set()
+    while len(masks) < (6 if taps not in (8, 9) else (1 if taps == 9 else 5)):
+        masks.add(int(sum(1 << t for t in rs.choice(9, taps, replace=False))))
+    lay = synth.random_pruned_layer_k(f"cover{taps}", 2, 12, 20, 13, 18, dtype, 3, np.array(sorted(masks), dtype=np.uint64), 0.6, 0.2, seed=40 + taps)
+    rep, _ = check_layer(lay, tuning=T(variant=2), label=f"cover-{taps}-{dtype}")
+    assert rep["chosen"]["variant"] == 2
+    rep, _ = check_layer(lay, tuning=T(variant=2, rows_per_lane=2, filters_per_wave=8), label=f"cover-{taps}-{dtype}-r2f8")
 
 
 def test_filter_reordering_invariance_and_determinism():

@@ -59,14 +59,21 @@ def test_stream_round_trip(dtype, tune):
     assert np.array_equal(w, want)
 
 
-def test_foreign_pattern_table_takes_generic_kernel():
+def test_foreign_pattern_table_runs_on_the_tiled_kernel_as_a_cover_of_its_own_patterns():
     lay = synth.random_pruned_layer("p", 1, 8, 8, 6, 6, "f32", np.array([0x00F, 0x1E0, 0x03A], dtype=np.uint16), 0.5, 0.1, 0)
     plan, info = check_against_reference(lay)
-    assert info["chosen"]["variant"] == 1
+    assert info["chosen"]["variant"] == 2
     st, *_ = pp.pp_conv_plan_unpack(plan.handle, info["k_kept"])
-    assert st == pp.PP_ERR_UNSUPPORTED
-    with pytest.raises(pp.PPError):
-        pp.plan_from_layer(lay, host_only=True, tuning=pp.Tuning(variant=2))
+    assert st == pp.PP_ERR_UNSUPPORTED                     # several stream entries per kernel: no round trip
+    pp.plan_from_layer(lay, host_only=True, tuning=pp.Tuning(variant=2)).close()
+    gen = pp.plan_from_layer(lay, host_only=True, tuning=pp.Tuning(variant=1))
+    assert gen.query()["chosen"]["variant"] == 1           # the generic kernel stays available by name
+    gen.close()
+    # other kernel sizes and strides still have no tiled form in fp32
+    k5 = synth.random_pruned_layer_k("k5", 1, 4, 4, 8, 8, "f32", 5, synth.random_pattern_set(5, 6, 3, 1), 0.5, 0.1, 0)
+    p5 = pp.plan_from_layer(k5, host_only=True)
+    assert p5.query()["chosen"]["variant"] == 1
+    p5.close()
 
 
 def test_error_paths():
