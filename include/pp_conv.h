@@ -105,6 +105,13 @@ typedef struct {
                                of 30 or of 14: segments of 30 or 14 outputs, of which a workgroup of wg_waves
                                wavefronts holds 2 * wg_waves or 4 * wg_waves; tile_rows = that count divided by
                                the segments per row, tile_cols / 30 or tile_cols / 14) */
+    int32_t split_k;        /* direct-load matrix-core kernel only: workgroups that share one output tile, each on its
+                               own run of channel chunks (0 auto, 1 none, 2, 4 or 8; must divide the number of
+                               16-channel chunks and leave each share at least 2).  Layers with few tiles fill the
+                               chip this way.  The shares' partial sums go to a plan-owned binary32 workspace sized
+                               for n_hint images and a second small kernel adds them in share order (no atomics:
+                               results do not depend on timing), so runs of such a plan must not overlap; a run on
+                               more than n_hint images, and pp_conv_run_static, run without the split */
 } pp_conv_tuning_t;
 
 /* Layer description (section 2.1.1 for the sparsity, section 2.3.1 for what the layer-wise

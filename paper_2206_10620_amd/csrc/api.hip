@@ -187,6 +187,8 @@ struct pp_conv_plan {
     float* d_bias_mfma = nullptr;
     k2_launch_fn launch2 = nullptr;
     k3_launch_fn launch3 = nullptr;
+    k3_launch_fn launch3_split = nullptr;     // the same kernel storing partial sums of a share of the chunks
+    float* d_ws3 = nullptr;                   // their workspace: [ksplit][n_hint][c_out][h][w] binary32
     // generic kernel
     int32_t* d_filt_off = nullptr;
     int32_t* d_kidx = nullptr;
@@ -211,7 +213,7 @@ bool upload(T** dst, const void* src, size_t bytes) {
 }
 
 void free_device(pp_conv_plan_t* p) {
-    void* bufs[] = {p->d_stream, p->d_wave_off, p->d_chan_map, p->d_ws, p->d_counters, p->d_perm_pad, p->d_bias_pad, p->d_wpk, p->d_bias_mfma, p->d_filt_off, p->d_kidx,
+    void* bufs[] = {p->d_ws3, p->d_stream, p->d_wave_off, p->d_chan_map, p->d_ws, p->d_counters, p->d_perm_pad, p->d_bias_pad, p->d_wpk, p->d_bias_mfma, p->d_filt_off, p->d_kidx,
                     p->d_kpat,   p->d_w,        p->d_tap,      p->d_perm,     p->d_bias};
     for (void* b : bufs)
         if (b) (void)hipFree(b);
@@ -265,6 +267,9 @@ static pp_status_t plan_autotuned(const pp_conv_desc_t* desc, pp_conv_plan_t** o
                     if (!base.wg_waves && !base.tile_cols && !base.tile_rows)
                         add([&](pp_conv_tuning_t& t) { t.variant = 3, t.mfma_kind = 2, t.wg_waves = waves, t.tile_cols = cols; });
         }
+        if (base.mfma_kind != 1 && !base.split_k)
+            for (int k : {1, 2, 4})
+                add([&](pp_conv_tuning_t& t) { t.variant = 3, t.mfma_kind = 2, t.split_k = k; });
         if (base.mfma_kind == 0) add([&](pp_conv_tuning_t& t) { t.variant = 3, t.mfma_kind = 1; });
     }
     if (base.variant == 0 || base.variant == 2) {
@@ -380,7 +385,10 @@ pp_status_t pp_conv_plan(const pp_conv_desc_t* desc, pp_conv_plan_t** out_plan) 
             return PP_ERR_UNSUPPORTED;
         }
     } else if (hp.mfma) {
-        if (hp.ml.direct) p->launch3 = k3_lookup(hp.ml.g3.sw, hp.ml.g3.waves);
+        if (hp.ml.direct) {
+            p->launch3 = k3_lookup(hp.ml.g3.sw, hp.ml.g3.waves, false);
+            if (hp.ml.ksplit > 1) p->launch3_split = k3_lookup(hp.ml.g3.sw, hp.ml.g3.waves, true);
+        }
         else p->launch2 = k2_lookup(hp.ks, hp.stride, hp.ml.ntw, hp.ml.waves, hp.ml.pairs);
         if (!p->launch2 && !p->launch3) {
             delete p;
@@ -416,6 +424,8 @@ pp_status_t pp_conv_plan(const pp_conv_desc_t* desc, pp_conv_plan_t** out_plan) 
     } else if (hp.mfma) {
         ok = ok && upload(&p->d_wpk, hp.ml.wpk.data(), hp.ml.wpk.size() * 2);
         ok = ok && upload(&p->d_bias_mfma, hp.ml.bias_pad.data(), hp.ml.bias_pad.size() * 4);
+        if (hp.ml.direct && hp.ml.ksplit > 1)   // the shares' partial sums, for up to n_hint images
+            ok = ok && upload(&p->d_ws3, nullptr, (size_t)hp.ml.ksplit * std::max(1, hp.n_hint) * hp.c_out * hp.h * hp.w * 4);
     } else {
         const Canonical& cn = hp.canon;
         std::vector<float> w = cn.wpacked;
@@ -536,7 +546,18 @@ static pp_status_t launch_generic(const pp_conv_plan_t* plan, const void* x_dev,
 }
 
 // One launch of the direct-load matrix-core kernel on n images.
-static pp_status_t launch_mfma_direct(const pp_conv_plan_t* plan, const void* x_dev, void* y_dev, int32_t n, hipStream_t stream) {
+// Adds the shares' partial sums in share order, then bias, activation and the rounding to binary16.
+__global__ __launch_bounds__(256) void k3_sum_shares(const float* __restrict__ ws, const float* __restrict__ bias, _Float16* __restrict__ y, int ksplit,
+                                                     int64_t slab_elems, int c_out, int hw, int relu) {
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= slab_elems) return;
+    float acc = bias[(int)((e / hw) % c_out)];
+    for (int k = 0; k < ksplit; ++k) acc += ws[(int64_t)k * slab_elems + e];
+    if (relu) acc = acc > 0.0f ? acc : 0.0f;
+    y[e] = (_Float16)acc;
+}
+
+static pp_status_t launch_mfma_direct(const pp_conv_plan_t* plan, const void* x_dev, void* y_dev, int32_t n, hipStream_t stream, bool may_split) {
     const HostPlan& hp = plan->hp;
     const MfmaLayout& ml = hp.ml;
     const K3Geom& g = ml.g3;
@@ -559,7 +580,13 @@ static pp_status_t launch_mfma_direct(const pp_conv_plan_t* plan, const void* x_
     a.tiles_v = (a.vrows + g.tr - 1) / g.tr;
     a.fb = ml.fb;
     a.q = ml.q;
-    const int64_t items = (int64_t)a.tiles_x * a.tiles_v * ml.fb;
+    // the reduction is split when the plan says so, its workspace is large enough and the caller allows it
+    const bool split = may_split && ml.ksplit > 1 && plan->launch3_split && plan->d_ws3 && n <= std::max(1, hp.n_hint);
+    a.ksplit = split ? ml.ksplit : 1;
+    a.qs = ml.q / a.ksplit;
+    a.ws = split ? plan->d_ws3 : nullptr;
+    a.slab_elems = (int64_t)n * hp.c_out * hp.h * hp.w;
+    const int64_t items = (int64_t)a.tiles_x * a.tiles_v * ml.fb * a.ksplit;
     // piece offsets are 32-bit byte offsets (+16) from a chunk's first element
     if (items >= ((int64_t)1 << 30) || (int64_t)n * hp.c_in * hp.h * hp.w >= ((int64_t)1 << 31) - 16) return PP_ERR_SHAPE;
     a.work_items = (int)items;
@@ -576,22 +603,29 @@ static pp_status_t launch_mfma_direct(const pp_conv_plan_t* plan, const void* x_
     a.magic_po = magic(ml.po);
     // the index arithmetic divides by multiplication, exact below 65536
     if (ml.po + g.trp >= 65536) return PP_ERR_SHAPE;
-    if (ml.q < k3_stages(g.waves) - 1) return PP_ERR_UNSUPPORTED;      // the kernel's pipeline fill stays inside the first tile
+    if (a.qs < k3_stages(g.waves) - 1) return PP_ERR_UNSUPPORTED;      // the kernel's pipeline fill stays inside the first work item
     a.relu = (hp.flags & PP_FLAG_RELU) ? 1 : 0;
     a.x_elems = (int64_t)n * hp.c_in * hp.h * hp.w;
     (void)hipGetLastError();
     // persistent workgroups: as many as are resident at once (16 wavefronts of this kernel per compute unit), fewer
     // if the layer has fewer tiles
     const int grid = std::min(a.blocks_per_xcd * 8, 256 * 8 / g.waves);
-    plan->launch3(a, grid, g.lds_bytes, stream);
+    if (!split) {
+        plan->launch3(a, grid, g.lds_bytes, stream);
+        return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_DEVICE;
+    }
+    plan->launch3_split(a, grid, g.lds_bytes, stream);
+    if (hipGetLastError() != hipSuccess) return PP_ERR_DEVICE;
+    hipLaunchKernelGGL(k3_sum_shares, dim3((unsigned)((a.slab_elems + 255) / 256)), dim3(256), 0, stream, plan->d_ws3, plan->d_bias_mfma,
+                       static_cast<_Float16*>(y_dev), a.ksplit, a.slab_elems, hp.c_out, hp.h * hp.w, a.relu);
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_DEVICE;
 }
 
 // One launch of the matrix-core kernel on n images.
-static pp_status_t launch_mfma(const pp_conv_plan_t* plan, const void* x_dev, void* y_dev, int32_t n, hipStream_t stream) {
+static pp_status_t launch_mfma(const pp_conv_plan_t* plan, const void* x_dev, void* y_dev, int32_t n, hipStream_t stream, bool may_split = true) {
     const HostPlan& hp = plan->hp;
     const MfmaLayout& ml = hp.ml;
-    if (ml.direct) return launch_mfma_direct(plan, x_dev, y_dev, n, stream);
+    if (ml.direct) return launch_mfma_direct(plan, x_dev, y_dev, n, stream, may_split);
     K2Args a{};
     a.x = x_dev;
     a.y = y_dev;
@@ -670,7 +704,7 @@ pp_status_t pp_conv_run_static(const pp_conv_plan_t* plan, const void* x_dev, vo
     if (chk != PP_OK) return chk;
     const HostPlan& hp = plan->hp;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    if (hp.mfma) return launch_mfma(plan, x_dev, y_dev, n, stream);
+    if (hp.mfma) return launch_mfma(plan, x_dev, y_dev, n, stream, false);      // no reduction split: that needs the plan's workspace
     if (!hp.tiled) return launch_generic(plan, x_dev, y_dev, n, stream);
     const TiledLayout& tl = hp.tl;
     if (tl.sw <= 1) return launch_tiled(plan, x_dev, y_dev, n, stream, nullptr, nullptr);

@@ -71,6 +71,11 @@ struct K3Args {
     uint32_t magic_ppcp, magic_ppr, magic_nseg, magic_po;
     int32_t relu;
     int64_t x_elems;            // n * c_in * h * w
+    // split reduction (SPLIT instantiations): each work item takes qs = q / ksplit consecutive chunks and stores
+    // its partial sums, without bias or activation, as binary32 into slab ks of the workspace ([ksplit][n][c_out][h][w])
+    int32_t ksplit, qs;
+    float* ws;
+    int64_t slab_elems;         // n * c_out * h * w
 };
 
 typedef __fp16 k3_hh4 __attribute__((__vector_size__(4 * sizeof(__fp16))));
@@ -134,7 +139,7 @@ __device__ __forceinline__ float k3_shl1(float v) {
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x130, 0xf, 0xf, true));
 }
 
-template <int SW, int WAVES>
+template <int SW, int WAVES, bool SPLIT>
 __global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void k3_mfma(const K3Args a) {
     constexpr int NT = kK3ColTiles, UPT = 32 / SW, SEGB = SW * 2, PPS = SEGB / 16, VALID = SW - 2;
@@ -193,9 +198,14 @@ void k3_mfma(const K3Args a) {
     }
 
     // tile coordinates of a work item (wave-uniform)
-    auto decode = [&](int item, int& fbi_o, int& ox0_o, int& v0_o) {
+    auto decode = [&](int item, int& fbi_o, int& ks_o, int& ox0_o, int& v0_o) {
         fbi_o = item % a.fb;
         item /= a.fb;
+        ks_o = 0;
+        if constexpr (SPLIT) {
+            ks_o = item % a.ksplit;
+            item /= a.ksplit;
+        }
         const int tx = item % a.tiles_x, tv = item / a.tiles_x;
         ox0_o = tx * a.nseg * VALID;
         v0_o = tv * a.tr;
@@ -206,13 +216,14 @@ void k3_mfma(const K3Args a) {
     uint32_t cls = 0u;                              // bit k: fetch; 4+k: zero instead (outside the images); 8+k / 12+k: the piece
                                                     // reaches below / beyond the tensor in the first / last chunk
     bool any_hole = false, any_edge = false;        // wave-uniform
-    int fbi_s = 0;                                  // filter block of the tile being staged
+    int fbi_s = 0, ks_s = 0;                        // filter block and reduction share of the tile being staged
+    const int QN = SPLIT ? a.qs : a.q;              // chunks per work item
     const int last_chunk_elems = (int)(a.x_elems - (int64_t)(a.q - 1) * kMfmaChunk * hw);   // the tensor has fewer than 2^31 elements
     // The set of the workgroup's next tile is worked out at the head of a tile, while the accumulators are
     // not yet in use, and parked in this lane's own words of LDS until the ring gets there.
     auto setup_tile = [&](int item) {
-        int ox0, v0, fbi_n;
-        decode(item, fbi_n, ox0, v0);
+        int ox0, v0, fbi_n, ks_n;
+        decode(item, fbi_n, ks_n, ox0, v0);
         const int u0 = v0 - 1;                                            // virtual input row of staged row 0
         const int img0 = (u0 + a.po) / a.po - 1, iy0 = u0 - img0 * a.po;  // u0 = -1 belongs to "image -1"
         const int img_hw = a.c_in * hw;
@@ -247,6 +258,7 @@ void k3_mfma(const K3Args a) {
         any_hole = __builtin_amdgcn_ballot_w64((cls & 0xF0u) != 0u) != 0;
         any_edge = __builtin_amdgcn_ballot_w64((cls & 0xFF00u) != 0u) != 0;
         fbi_s = item % a.fb;
+        ks_s = SPLIT ? (item / a.fb) % a.ksplit : 0;
     };
 
     // The loads of one step (chunk qi of the staged tile, into ring place `buf`) are WU weight instructions
@@ -266,16 +278,17 @@ void k3_mfma(const K3Args a) {
         bool bias;                                  // the tile's first chunk: the bias values come along
     };
     const uint32_t lane16 = (uint32_t)(lane * 16);
-    auto begin_step = [&](int qi, int buf) {
+    auto begin_step = [&](int ql, int buf) {         // ql: chunk within the work item
         Step st;
         st.on = true;
         st.buf = buf;
+        const int qi = SPLIT ? ks_s * a.qs + ql : ql; // chunk of the layer
         st.wbase = k3_uniform_ptr(static_cast<const unsigned char*>(a.wpk) + ((int64_t)fbi_s * a.q + qi) * kK3WeightBytes + wave * 1024);
         st.ldsw = lds0 + (uint32_t)(NS * xb_bytes + buf * kK3WeightBytes + wave * 1024);
         st.chunk_elem0 = (int64_t)qi * kMfmaChunk * hw;
         st.xbase = k3_uniform_ptr(reinterpret_cast<const unsigned char*>(xin + st.chunk_elem0) - 16);
         st.ldsx = lds0 + (uint32_t)(buf * xb_bytes + wave * 1024);
-        st.bias = qi == 0;
+        st.bias = !SPLIT && qi == 0;
         st.bbase = k3_uniform_ptr(a.bias + fbi_s * kMfmaFilters);
         st.plain = !(any_edge || any_hole);
         st.edge_bits = 0u;
@@ -350,7 +363,7 @@ void k3_mfma(const K3Args a) {
     int stores_behind = 0, store_credit = 0;
     auto advance_issue = [&]() {
         ibuf = ibuf + 1 == NS ? 0 : ibuf + 1;
-        if (++iq == a.q) iq = 0, ++ik;
+        if (++iq == QN) iq = 0, ++ik;
     };
     setup_tile(first_item + slot);
     take_tile(first_item + slot);
@@ -392,7 +405,7 @@ void k3_mfma(const K3Args a) {
         read_b(0, 0);
         read_a(0, 0);
         k3_f16 cb[2];                               // FIRST: the bias in accumulator order (an accumulator register holds one filter)
-        if constexpr (FIRST) {
+        if constexpr (FIRST && !SPLIT) {
             const int kb = lane >> 5;
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt)
@@ -416,7 +429,7 @@ void k3_mfma(const K3Args a) {
                 for (int mt = 0; mt < 2; ++mt) {
                     k3_f16 cin;
                     if (FIRST && r == 0) {
-                        if (c == 1) cin = cb[mt];
+                        if (c == 1 && !SPLIT) cin = cb[mt];
                         else
 #pragma unroll
                             for (int e = 0; e < 16; ++e) cin[e] = 0.0f;
@@ -437,7 +450,7 @@ void k3_mfma(const K3Args a) {
         __builtin_amdgcn_sched_barrier(0);
 
         // ---- main loop over chunks of 16 channels ----
-        for (int qi = 0; qi < a.q; ++qi) {
+        for (int qi = 0; qi < QN; ++qi) {
             // This wavefront's loads of the current step have landed (and its zero fills and edge pieces are
             // written); after the barrier everyone's have, and everyone is done reading the ring place that
             // is filled next.  Loads return in order: all but the `young` most recent instructions are
@@ -474,9 +487,49 @@ void k3_mfma(const K3Args a) {
         const int p = lane_e & 31, kb = lane_e >> 5;
         const int tb_w = kb * 4 * 64 + p * 2;                                 // + filter row * 64
         const int tb_r = lane_e * 16;                                         // filter lane / 4, columns 8 (lane % 4) ..
-        int fbi, ox0, v0;
-        decode(item_c, fbi, ox0, v0);
+        int fbi, ks_c, ox0, v0;
+        decode(item_c, fbi, ks_c, ox0, v0);
         const int oimg0 = v0 / a.po, oy0 = v0 - oimg0 * a.po;
+        if constexpr (SPLIT) {
+            // Partial sums of this item's chunks: the three tap columns combined as below, stored as binary32 into
+            // the item's slab of the workspace, no bias, no activation (a second kernel adds the slabs up in
+            // slab order).  A register holds one filter for 32 columns: lanes 0-31 write a 128-byte run of one
+            // filter's row, lanes 32-63 the same columns of the filter four further on.
+            float* wsb = k3_uniform_ptr(a.ws + (int64_t)ks_c * a.slab_elems);
+            stores_behind = 0;
+            store_credit = NS - 1;
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                const int ui = (wave * NT + nt) * UPT + p / SW, col = p % SW;
+                const int row = k3_div(ui, a.magic_nseg), seg = ui - row * a.nseg;
+                const int ox = ox0 + seg * VALID + col;
+                const bool kill0 = ox == 0, kill2 = ox == a.w + 1;
+                const bool fix = __builtin_amdgcn_ballot_w64(kill0 || kill2) != 0;
+                const int t = oy0 + row, di = k3_div(t, a.magic_po);
+                const int img = oimg0 + di, oy = t - di * a.po;
+                const bool ok = col < VALID && ox < a.w && v0 + row < a.vrows && oy < a.h;
+                const int off = ((img * a.c_out + fbi * kMfmaFilters + kb * 4) * a.h + oy) * a.w + ox;   // + (filter - 4 kb) * h * w
+                // a whole block of 64 filters inside the layer (wave-uniform): then every store instruction below has
+                // an active lane as soon as one column of this tile is an output, and all 32 are counted
+                const bool full = (fbi + 1) * kMfmaFilters <= a.c_out;
+                if (full && __builtin_amdgcn_ballot_w64(ok) != 0) stores_behind += 32;
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        float p0 = acc[0][mt][nt][r], p1 = acc[1][mt][nt][r], p2 = acc[2][mt][nt][r];
+                        if (fix) {
+                            asm volatile("" ::: "memory");
+                            p0 = kill0 ? 0.0f : p0;
+                            p2 = kill2 ? 0.0f : p2;
+                        }
+                        const float v = p0 + k3_shl1(p1 + k3_shl1(p2));
+                        const int f = mt * 32 + (r >> 2) * 8 + (r & 3);               // + 4 kb: the register's filter inside the block
+                        if (ok && (full || fbi * kMfmaFilters + f + kb * 4 < a.c_out)) wsb[off + f * hw] = v;
+                    }
+            }
+            continue;
+        }
         unsigned char* ybase = static_cast<unsigned char*>(a.y);
         const uint32_t fstride = (uint32_t)(a.h * a.w * 2);              // bytes between filters
         const k3_h2 floor2 = a.relu ? k3_h2((_Float16)0.0f) : k3_h2((_Float16)-65504.0f);
@@ -560,6 +613,7 @@ void k3_mfma(const K3Args a) {
 
 typedef void (*k3_launch_fn)(const K3Args& a, int blocks, int lds_bytes, hipStream_t stream);
 // The instantiation for a segment width (32 or 16) and a workgroup size (4 or 8 wavefronts); nullptr otherwise.
-k3_launch_fn k3_lookup(int sw, int waves);
+k3_launch_fn k3_lookup(int sw, int waves, bool split);
+k3_launch_fn k3_lookup_split(int sw, int waves);
 
 }  // namespace ppc

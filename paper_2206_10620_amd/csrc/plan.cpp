@@ -328,6 +328,7 @@ pp_status_t build_layouts(const pp_conv_desc_t& d, HostPlan& hp) {
     hp.mfma = variant == 3;
     hp.chosen = pp_conv_tuning_t{};
     hp.chosen.variant = variant;
+    if (t.split_k < 0 || (t.split_k > 1 && variant != 3)) return PP_ERR_UNSUPPORTED;
     if (variant == 3) return build_mfma_layout(t, hp);
     if (!hp.tiled) return PP_OK;
 
@@ -700,10 +701,30 @@ pp_status_t build_mfma_layout(const pp_conv_tuning_t& t, HostPlan& hp) {
         hp.chosen.tile_cols = ml.tc;
         hp.chosen.tiles_per_wave = ml.ntw;
         hp.chosen.mfma_kind = 2;
+        // Reduction split: a layer with fewer work items than the chip has places for workgroups lets several
+        // of them share a tile, each on its own run of chunks.
+        const int stages = k3_stages(waves);
+        auto split_ok = [&](int k) { return k == 1 || (ml.q % k == 0 && ml.q / k >= std::max(2, stages - 1)); };
+        if (t.split_k < 0 || (t.split_k > 1 && t.split_k != 2 && t.split_k != 4 && t.split_k != 8)) return false;
+        int ks = 1;
+        if (t.split_k) {
+            if (!split_ok(t.split_k)) return false;
+            ks = t.split_k;
+        } else if (tiles <= 128.0 && (ml.q >= 32 || (ml.q >= 16 && tiles <= 64.0))) {
+            // Measured on MI355X (512- and 256-channel layers with 56 to 128 work items): a four-way split takes
+            // 512-channel layers from 49-51 us to 28-32 us and a 256-channel layer with 56 items from 28 to 23 us;
+            // with 120 or more items of 16 chunks, or any layer that fills one round of workgroups, the partial
+            // sums cost more than the split gains.
+            if (split_ok(4)) ks = 4;
+            else if (split_ok(2)) ks = 2;
+        }
+        ml.ksplit = ks;
+        hp.chosen.split_k = ks;
         return true;
     };
     ml.direct = direct_ok && t.mfma_kind != 1 && direct_layout();
     if (t.mfma_kind == 2 && !ml.direct) return PP_ERR_UNSUPPORTED;
+    if (t.split_k > 1 && !ml.direct) return PP_ERR_UNSUPPORTED;      // only the direct-load kernel splits the reduction
     // The batch is one tall virtual image: image n's output row oy is virtual row n*po + oy, and the
     // matching input rows start at virtual input row n*po*S, so that a tile may straddle images; the
     // rows between images read as zeros (they are the padding) and their outputs are not stored.

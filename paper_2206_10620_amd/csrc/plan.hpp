@@ -54,6 +54,7 @@ struct MfmaLayout {
     int waves = 4;                    // wavefronts per workgroup (4 or 8)
     bool direct = false;              // the direct-load kernel (3x3, stride 1, whole chunks of 16 channels) runs this plan
     K3Geom g3;                        // ... with this geometry
+    int ksplit = 1;                   // ... and this many workgroups sharing a tile's reduction (partial sums to a workspace)
     bool pairs = true;                // even image width: input staged as aligned 32-bit pixel pairs
     int po = 0;                       // rows per image in the tall virtual output image (ho + separator rows)
     int trp = 0, twpa = 0;            // staged input rows per tile: (tr-1)*stride + K; staged columns: (tc-1)*stride + K + 2, rounded down to even

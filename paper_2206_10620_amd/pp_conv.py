@@ -13,7 +13,7 @@ PP_FLAG_RELU, PP_FLAG_DENSE, PP_FLAG_HOST_ONLY, PP_FLAG_POOL2 = 1, 2, 4, 8
 
 # Bumped whenever the device code of the tiled kernel changes (measurements that are tied to a
 # kernel build, such as hardware-counter readings, are keyed by it).
-KERNEL_REVISION = "lib-2026-11-28-b"
+KERNEL_REVISION = "lib-2026-11-28-c"
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libpp_conv.so")
@@ -30,7 +30,7 @@ class Tuning(C.Structure):
                 ("lanes_x", C.c_int32), ("waves_f", C.c_int32), ("split_c", C.c_int32), ("chunk_c", C.c_int32),
                 ("staging", C.c_int32), ("split_wg", C.c_int32), ("balance", C.c_int32),
                 ("tile_rows", C.c_int32), ("tile_cols", C.c_int32), ("tiles_per_wave", C.c_int32),
-                ("wg_waves", C.c_int32), ("autotune", C.c_int32), ("mfma_kind", C.c_int32)]
+                ("wg_waves", C.c_int32), ("autotune", C.c_int32), ("mfma_kind", C.c_int32), ("split_k", C.c_int32)]
 
     def as_dict(self):
         return {k: getattr(self, k) for k, _ in self._fields_}

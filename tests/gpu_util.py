@@ -66,13 +66,13 @@ def tile_boundary_points(lay, n, chosen):
     return structured_points(n, lay.c_out, lay.out_h, lay.out_w, band, strip, rpi, seed=lay.seed)
 
 
-def check_layer(lay, x_np=None, tuning=None, relu=None, tol=None, points=4096, label="", extra_points=None):
+def check_layer(lay, x_np=None, tuning=None, relu=None, tol=None, points=4096, label="", extra_points=None, n_hint=None):
     """Compare GPU output with the checker: every element when the layer is small, sampled outputs otherwise
     (random ones, corners and edges, plus extra_points: an int array [k, 4] of stored-output coordinates)."""
     if x_np is None:
         x_np = lay.make_input()
     relu_flag = lay.relu if relu is None else relu
-    y, chosen = run_layer(lay, x_np, tuning, relu)
+    y, chosen = run_layer(lay, x_np, tuning, relu, n_hint)
     assert not np.isnan(y.astype(np.float32)).any(), f"{label}: output has unwritten (NaN) elements"
     n = x_np.shape[0]
     ksize = getattr(lay, "ksize", 3)

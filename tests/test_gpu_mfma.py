@@ -180,3 +180,47 @@ def test_direct_runs_are_bit_identical():
     y1, _ = run_layer(lay, x, tuning=TD())
     y2, _ = run_layer(lay, x, tuning=TD())
     assert np.array_equal(y1, y2)
+
+
+# ---- reduction split of the direct-load kernel (tuning.split_k): several workgroups share a tile ----
+
+@pytest.mark.parametrize("waves,split", [(4, 2), (4, 4), (4, 8), (8, 2), (8, 4)])
+def test_direct_split_reduction(waves, split):
+    say(f"mfma direct split_k {split} waves {waves}")
+    # c_in gives 16 or 32 chunks; shapes with several tiles, ragged rows and columns, several filter blocks, a ragged last block
+    for (n, c_in, c_out, h, w) in [(2, 256, 40, 9, 13), (3, 512, 130, 14, 14), (1, 256, 64, 5, 61), (2, 256, 8, 17, 3)]:
+        lay = synth.random_pruned_layer("dsplit", n, c_in, c_out, h, w, "f16", synth.PSET16, 0.3, 0.1, seed=split + waves)
+        for relu in (True, False):
+            rep, _ = check_layer(lay, tuning=TD(split_k=split, wg_waves=waves), relu=relu, label=f"mfma-direct-split{split}-w{waves}")
+            assert rep["chosen"]["split_k"] == split and rep["chosen"]["mfma_kind"] == 2 and rep["chosen"]["wg_waves"] == waves
+    say(f"  E={rep['E']:.2e} {rep['chosen']}")
+
+
+def test_direct_split_rule_refusals_determinism_and_larger_batches():
+    from gpu_util import run_layer
+    # few tiles, many chunks: the plan splits by itself
+    lay = synth.random_pruned_layer("dsauto", 8, 512, 512, 14, 14, "f16", synth.PSET8, 0.28, 0.03, seed=3)
+    rep, y = check_layer(lay, label="mfma-direct-split-auto")
+    assert rep["chosen"]["mfma_kind"] == 2 and rep["chosen"]["split_k"] >= 2
+    # split off by request gives the same result up to the rounding of a different summation order
+    y1, c1 = run_layer(lay, lay.make_input(), tuning=TD(split_k=1))
+    assert c1["split_k"] == 1
+    assert np.max(np.abs(y.astype(np.float32) - y1.astype(np.float32))) <= 2e-3 * max(1.0, float(np.abs(y1).max()))
+    # no atomics: two runs agree bit for bit
+    y2, _ = run_layer(lay, lay.make_input())
+    assert np.array_equal(y, y2)
+    # a plan for 2 images given 5: more than its workspace holds, so it runs unsplit; same gate
+    small = synth.random_pruned_layer("dsbig", 5, 256, 64, 7, 7, "f16", synth.PSET8, 0.4, 0.05, seed=4)
+    rep, _ = check_layer(small, tuning=TD(split_k=4), n_hint=2, label="mfma-direct-split-beyond-hint")
+    assert rep["chosen"]["split_k"] == 4
+    # refusals: a share must be whole chunks and at least two of them; only the direct-load kernel splits
+    with pytest.raises(pp.PPError):
+        pp.plan_from_layer(synth.random_pruned_layer("r1", 1, 48, 8, 8, 8, "f16", synth.PSET8, 0.5, 0.1, seed=1), tuning=TD(split_k=2))
+    with pytest.raises(pp.PPError):
+        pp.plan_from_layer(synth.random_pruned_layer("r2", 1, 64, 8, 8, 8, "f16", synth.PSET8, 0.5, 0.1, seed=1), tuning=TD(split_k=4))
+    with pytest.raises(pp.PPError):
+        pp.plan_from_layer(synth.random_pruned_layer("r3", 1, 64, 8, 8, 8, "f16", synth.PSET8, 0.5, 0.1, seed=1), tuning=TD(split_k=3))
+    with pytest.raises(pp.PPError):
+        pp.plan_from_layer(synth.random_pruned_layer("r4", 1, 64, 8, 8, 8, "f16", synth.PSET8, 0.5, 0.1, seed=1), tuning=pp.Tuning(variant=3, mfma_kind=1, split_k=2))
+    with pytest.raises(pp.PPError):
+        pp.plan_from_layer(synth.random_pruned_layer("r5", 1, 64, 8, 8, 8, "f32", synth.PSET8, 0.5, 0.1, seed=1), tuning=pp.Tuning(variant=2, split_k=2))

@@ -60,3 +60,19 @@ def test_static_scratch_run_without_a_split_and_beyond_the_limit():
         assert "scratch" in pp.pp_status_string(st)
     finally:
         plan.close()
+
+
+def test_static_run_of_a_plan_that_splits_its_reduction_runs_unsplit():
+    """A matrix-core plan with tuning.split_k > 1 keeps its partial sums in a plan-owned workspace; the entry
+    point that allocates nothing does not use it (it runs the same kernel without the split), so its result
+    agrees with the allocating run to the rounding of a different summation order, and with the checker."""
+    lay = synth.random_pruned_layer("noalloc3", 2, 256, 64, 9, 9, "f16", synth.PSET8, 0.4, 0.05, seed=8)
+    plan = pp.plan_from_layer(lay, tuning=pp.Tuning(variant=3, mfma_kind=2, split_k=4), n_hint=2)
+    try:
+        assert plan.query()["chosen"]["split_k"] == 4
+        x, y0, y1 = _run_pair(plan, lay, 2)
+        ref, pre, scale = oracle.layer_reference(lay, x.astype(np.float64))
+        for y in (y0, y1):
+            assert error_report(y, ref, pre, scale)["E"] <= TOL["f16"]
+    finally:
+        plan.close()
