@@ -666,7 +666,7 @@ pp_status_t build_mfma_layout(const pp_conv_tuning_t& t, HostPlan& hp) {
             double best = 1e300;
             for (int ns = 1; ns <= units; ++ns) {
                 if (t.tile_cols && ns != nseg_o) continue;
-                if (!t.tile_cols && !t.tile_rows && sw == 16 && spr >= 2 && ns < 2) continue;   // measured: 32-byte rows stage poorly; two narrow segments side by side
+                if (!t.tile_cols && !t.tile_rows && spr >= 2 && ns < 2) continue;   // measured: short staged rows (32 or 64 bytes) load poorly; at least two segments side by side (1080p layer: 8 x 60 tiles 225 us, 16 x 30 tiles 236 us)
                 const K3Geom g = k3_geom(sw, ns, waves);
                 if (!g.ok || (t.tile_rows && t.tile_rows != g.tr)) continue;
                 const double tiles = (double)((spr + ns - 1) / ns) * (double)((vr + g.tr - 1) / g.tr);
