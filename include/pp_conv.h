@@ -100,7 +100,9 @@ typedef struct {
                                reports chosen.autotune = 1 */
     int32_t mfma_kind;      /* which matrix-core kernel: 0 auto; 1 the general one (tiles transposed in registers on
                                their way into LDS; any kernel size, stride, channel count, fused pool); 2 the
-                               direct-load one (3x3, stride 1, c_in a multiple of 16, no fused pool: tiles copied
+                               direct-load one (3x3, stride 1, no fused pool; when c_in is not a multiple of 16 the input is
+                               first copied into a plan-owned buffer with zero channels appended, n_hint images at a
+                               time, so runs of such a plan must not overlap: tiles copied
                                memory-to-LDS as they are and transposed by the LDS read; tile_cols is then a multiple
                                of 30 or of 14: segments of 30 or 14 outputs, of which a workgroup of wg_waves
                                wavefronts holds 2 * wg_waves or 4 * wg_waves; tile_rows = that count divided by

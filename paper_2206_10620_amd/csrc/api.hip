@@ -189,6 +189,7 @@ struct pp_conv_plan {
     k3_launch_fn launch3 = nullptr;
     k3_launch_fn launch3_split = nullptr;     // the same kernel storing partial sums of a share of the chunks
     float* d_ws3 = nullptr;                   // their workspace: [ksplit][n_hint][c_out][h][w] binary32
+    _Float16* d_xpad = nullptr;               // x with zero channels appended up to whole chunks of 16: [n_hint][cpad][h][w]
     // generic kernel
     int32_t* d_filt_off = nullptr;
     int32_t* d_kidx = nullptr;
@@ -213,7 +214,7 @@ bool upload(T** dst, const void* src, size_t bytes) {
 }
 
 void free_device(pp_conv_plan_t* p) {
-    void* bufs[] = {p->d_ws3, p->d_stream, p->d_wave_off, p->d_chan_map, p->d_ws, p->d_counters, p->d_perm_pad, p->d_bias_pad, p->d_wpk, p->d_bias_mfma, p->d_filt_off, p->d_kidx,
+    void* bufs[] = {p->d_xpad, p->d_ws3, p->d_stream, p->d_wave_off, p->d_chan_map, p->d_ws, p->d_counters, p->d_perm_pad, p->d_bias_pad, p->d_wpk, p->d_bias_mfma, p->d_filt_off, p->d_kidx,
                     p->d_kpat,   p->d_w,        p->d_tap,      p->d_perm,     p->d_bias};
     for (void* b : bufs)
         if (b) (void)hipFree(b);
@@ -424,6 +425,9 @@ pp_status_t pp_conv_plan(const pp_conv_desc_t* desc, pp_conv_plan_t** out_plan) 
     } else if (hp.mfma) {
         ok = ok && upload(&p->d_wpk, hp.ml.wpk.data(), hp.ml.wpk.size() * 2);
         ok = ok && upload(&p->d_bias_mfma, hp.ml.bias_pad.data(), hp.ml.bias_pad.size() * 4);
+        if (hp.ml.direct && hp.ml.cpad != hp.c_in)   // zero-padded copy of x (the padding is zeroed here, once)
+            ok = ok && upload(&p->d_xpad, nullptr, (size_t)std::max(1, hp.n_hint) * hp.ml.cpad * hp.h * hp.w * 2) &&
+                 hipMemset(p->d_xpad, 0, (size_t)std::max(1, hp.n_hint) * hp.ml.cpad * hp.h * hp.w * 2) == hipSuccess;
         if (hp.ml.direct && hp.ml.ksplit > 1)   // the shares' partial sums, for up to n_hint images
             ok = ok && upload(&p->d_ws3, nullptr, (size_t)hp.ml.ksplit * std::max(1, hp.n_hint) * hp.c_out * hp.h * hp.w * 4);
     } else {
@@ -557,17 +561,49 @@ __global__ __launch_bounds__(256) void k3_sum_shares(const float* __restrict__ w
     y[e] = (_Float16)acc;
 }
 
+// Copies the c_in channels of every image into the first c_in of cpad channels (the others were zeroed when the
+// plan was made and are never written): 16 bytes per lane when an image plane is a multiple of 8 elements.
+__global__ __launch_bounds__(256) void k3_pad_channels(const _Float16* __restrict__ x, _Float16* __restrict__ xp, int64_t total, int chw, int cpad_hw, int v) {
+    const int64_t e = ((int64_t)blockIdx.x * 256 + threadIdx.x) * v;       // element of x; v = 8 or 1 elements per lane
+    if (e >= total) return;
+    const int64_t img = e / chw;
+    const int64_t o = img * cpad_hw + (e - img * chw);
+    if (v == 8) *reinterpret_cast<uint4*>(xp + o) = *reinterpret_cast<const uint4*>(x + e);
+    else xp[o] = x[e];
+}
+
 static pp_status_t launch_mfma_direct(const pp_conv_plan_t* plan, const void* x_dev, void* y_dev, int32_t n, hipStream_t stream, bool may_split) {
     const HostPlan& hp = plan->hp;
     const MfmaLayout& ml = hp.ml;
     const K3Geom& g = ml.g3;
+    const int cpad = ml.cpad;
+    if (cpad != hp.c_in) {
+        // the padded copy holds n_hint images: larger batches go through it a group at a time
+        const int group = std::max(1, hp.n_hint);
+        if (n > group) {
+            for (int n0 = 0; n0 < n; n0 += group) {
+                const pp_status_t st = launch_mfma_direct(plan, static_cast<const _Float16*>(x_dev) + (int64_t)n0 * hp.c_in * hp.h * hp.w,
+                                                          static_cast<_Float16*>(y_dev) + (int64_t)n0 * hp.c_out * hp.h * hp.w, std::min(group, n - n0), stream, may_split);
+                if (st != PP_OK) return st;
+            }
+            return PP_OK;
+        }
+        const int hw = hp.h * hp.w;
+        const int64_t total = (int64_t)n * hp.c_in * hw;
+        (void)hipGetLastError();
+        const int v = hw % 8 == 0 ? 8 : 1;
+        hipLaunchKernelGGL(k3_pad_channels, dim3((unsigned)((total / v + 255) / 256)), dim3(256), 0, stream, static_cast<const _Float16*>(x_dev), plan->d_xpad, total,
+                           hp.c_in * hw, cpad * hw, v);
+        if (hipGetLastError() != hipSuccess) return PP_ERR_DEVICE;
+        x_dev = plan->d_xpad;
+    }
     K3Args a{};
     a.x = x_dev;
     a.y = y_dev;
     a.wpk = plan->d_wpk;
     a.bias = plan->d_bias_mfma;
     a.n = n;
-    a.c_in = hp.c_in;
+    a.c_in = cpad;
     a.c_out = hp.c_out;
     a.h = hp.h;
     a.w = hp.w;
@@ -588,7 +624,7 @@ static pp_status_t launch_mfma_direct(const pp_conv_plan_t* plan, const void* x_
     a.slab_elems = (int64_t)n * hp.c_out * hp.h * hp.w;
     const int64_t items = (int64_t)a.tiles_x * a.tiles_v * ml.fb * a.ksplit;
     // piece offsets are 32-bit byte offsets (+16) from a chunk's first element
-    if (items >= ((int64_t)1 << 30) || (int64_t)n * hp.c_in * hp.h * hp.w >= ((int64_t)1 << 31) - 16) return PP_ERR_SHAPE;
+    if (items >= ((int64_t)1 << 30) || (int64_t)n * cpad * hp.h * hp.w >= ((int64_t)1 << 31) - 16) return PP_ERR_SHAPE;
     a.work_items = (int)items;
     a.blocks_per_xcd = (int)((items + 7) / 8);
     a.chs = g.chs;
@@ -605,7 +641,7 @@ static pp_status_t launch_mfma_direct(const pp_conv_plan_t* plan, const void* x_
     if (ml.po + g.trp >= 65536) return PP_ERR_SHAPE;
     if (a.qs < k3_stages(g.waves) - 1) return PP_ERR_UNSUPPORTED;      // the kernel's pipeline fill stays inside the first work item
     a.relu = (hp.flags & PP_FLAG_RELU) ? 1 : 0;
-    a.x_elems = (int64_t)n * hp.c_in * hp.h * hp.w;
+    a.x_elems = (int64_t)n * cpad * hp.h * hp.w;
     (void)hipGetLastError();
     // persistent workgroups: as many as are resident at once (16 wavefronts of this kernel per compute unit), fewer
     // if the layer has fewer tiles

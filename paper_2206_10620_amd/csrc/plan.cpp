@@ -637,9 +637,10 @@ pp_status_t build_mfma_layout(const pp_conv_tuning_t& t, HostPlan& hp) {
     ml.q = (hp.c_in + kMfmaChunk - 1) / kMfmaChunk;
     ml.upq = KS <= 3 ? 1 : KS;
     ml.wbuf_bytes = (KK / ml.upq) * 2 * 1024;
-    // The direct-load kernel takes 3x3, stride-1 layers without a fused pool whose channels fill whole
-    // chunks of 16; measured on MI355X it is the faster of the two wherever it applies.
-    const bool direct_ok = KS == 3 && S == 1 && !hp.pool && hp.c_in % kMfmaChunk == 0 && hp.h + 1 + 66 < 65536;
+    // The direct-load kernel takes 3x3, stride-1 layers without a fused pool; measured on MI355X it is the faster
+    // of the two wherever it applies.
+    // (a channel count that does not fill whole chunks is padded with zero channels into a plan-owned copy of x)
+    const bool direct_ok = KS == 3 && S == 1 && !hp.pool && hp.h + 1 + 66 < 65536;
     if (t.mfma_kind < 0 || t.mfma_kind > 2 || (t.mfma_kind == 2 && !direct_ok)) return PP_ERR_UNSUPPORTED;
     // A request for a tile the direct kernel has no geometry for goes to the general kernel, unless the
     // direct one was asked for by name.
@@ -720,6 +721,7 @@ pp_status_t build_mfma_layout(const pp_conv_tuning_t& t, HostPlan& hp) {
         }
         ml.ksplit = ks;
         hp.chosen.split_k = ks;
+        ml.cpad = ml.q * kMfmaChunk;
         return true;
     };
     ml.direct = direct_ok && t.mfma_kind != 1 && direct_layout();

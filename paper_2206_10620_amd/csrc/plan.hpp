@@ -54,6 +54,7 @@ struct MfmaLayout {
     int waves = 4;                    // wavefronts per workgroup (4 or 8)
     bool direct = false;              // the direct-load kernel (3x3, stride 1, whole chunks of 16 channels) runs this plan
     K3Geom g3;                        // ... with this geometry
+    int cpad = 0;                     // ... on this many input channels: c_in rounded up to whole chunks (a larger value than c_in means x is copied into a zero-padded buffer first)
     int ksplit = 1;                   // ... and this many workgroups sharing a tile's reduction (partial sums to a workspace)
     bool pairs = true;                // even image width: input staged as aligned 32-bit pixel pairs
     int po = 0;                       // rows per image in the tall virtual output image (ho + separator rows)

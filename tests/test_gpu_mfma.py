@@ -118,7 +118,8 @@ def TD(**kw):
     return pp.Tuning(variant=3, mfma_kind=2, **kw)
 
 
-DIRECT_SHAPES = [(1, 16, 5, 1, 1), (2, 16, 9, 1, 7), (3, 32, 64, 9, 1), (2, 16, 13, 7, 7), (3, 48, 10, 14, 14), (1, 16, 6, 5, 30),
+DIRECT_SHAPES = [(2, 3, 64, 20, 24), (1, 12, 8, 9, 9), (3, 19, 33, 7, 15), (2, 40, 70, 17, 24),      # channel counts padded to whole chunks
+                 (1, 16, 5, 1, 1), (2, 16, 9, 1, 7), (3, 32, 64, 9, 1), (2, 16, 13, 7, 7), (3, 48, 10, 14, 14), (1, 16, 6, 5, 30),
                  (2, 32, 17, 11, 31), (1, 16, 8, 28, 28), (5, 16, 24, 3, 56), (1, 16, 70, 20, 130), (2, 32, 40, 6, 61),
                  (2, 64, 129, 17, 29), (1, 16, 64, 16, 60), (3, 16, 8, 9, 15), (1, 64, 64, 40, 72), (2, 16, 4, 33, 2)]
 
@@ -156,8 +157,8 @@ def test_direct_is_the_default_where_it_applies_and_matches_the_general_kernel()
     assert chosen1["mfma_kind"] == 1
     # same products, summed in a different order: equal to within binary16 output rounding
     assert np.max(np.abs(y.astype(np.float32) - y1.astype(np.float32))) <= 2e-3 * max(1.0, float(np.abs(y1).max()))
-    # layers it does not take fall to the general kernel; asking for it by name is refused
-    lay2 = synth.random_pruned_layer("dno", 1, 12, 8, 9, 9, "f16", synth.PSET8, 0.5, 0.3, seed=2)
+    # layers it does not take (another kernel size, a stride, a fused pool) fall to the general kernel; asking for it by name is refused
+    lay2 = synth.random_pruned_layer_k("dno", 1, 16, 8, 10, 10, "f16", 3, synth.PSET8, 0.5, 0.3, seed=2, stride=2)
     rep2, _ = check_layer(lay2, tuning=pp.Tuning(variant=3), label="mfma-general-auto")
     assert rep2["chosen"]["mfma_kind"] == 1
     with pytest.raises(pp.PPError):
@@ -224,3 +225,14 @@ def test_direct_split_rule_refusals_determinism_and_larger_batches():
         pp.plan_from_layer(synth.random_pruned_layer("r4", 1, 64, 8, 8, 8, "f16", synth.PSET8, 0.5, 0.1, seed=1), tuning=pp.Tuning(variant=3, mfma_kind=1, split_k=2))
     with pytest.raises(pp.PPError):
         pp.plan_from_layer(synth.random_pruned_layer("r5", 1, 64, 8, 8, 8, "f32", synth.PSET8, 0.5, 0.1, seed=1), tuning=pp.Tuning(variant=2, split_k=2))
+
+
+def test_direct_padded_channels_beyond_the_batch_hint_and_dense_first_layer():
+    # a plan sized for 2 images given 5: the zero-padded copy of x holds 2, so the batch goes through it in groups
+    lay = synth.random_pruned_layer("dpad", 5, 3, 20, 11, 16, "f16", synth.PSET8, 1.0, 0.3, seed=6)
+    rep, _ = check_layer(lay, tuning=TD(), n_hint=2, label="mfma-direct-pad-groups")
+    assert rep["chosen"]["mfma_kind"] == 2
+    # an unpruned three-channel first layer (nine taps) takes the same path by default
+    dense = synth.dense_layer("dfirst", 2, 3, 64, 24, 40, "f16", 0.3, seed=2)
+    rep, _ = check_layer(dense, label="mfma-direct-dense-first")
+    assert rep["chosen"]["variant"] == 3 and rep["chosen"]["mfma_kind"] == 2
