@@ -94,6 +94,24 @@ def _foreign(dtype):
                                        float(np.sqrt(2.0 / (4 * 0.3 * 256))), seed=5)
 
 
+WARM_SECONDS = 0.1     # the clock of this chip settles some tens of milliseconds into a sustained load (the first launches
+                       # of the 1080p layer take 222 us, the next few dozen up to 290 us, the sustained ones 210 us): every
+                       # timed region is preceded by at least this much untimed work, whatever --warmup says
+
+
+def _warm(step, warmup):
+    """At least `warmup` untimed steps and at least WARM_SECONDS of them."""
+    import torch
+    t0 = time.perf_counter()
+    done = 0
+    while done < warmup or time.perf_counter() - t0 < WARM_SECONDS:
+        for _ in range(16 if done >= warmup else min(16, warmup - done)):
+            step()
+            done += 1
+        torch.cuda.synchronize()
+    return done
+
+
 def _events():
     import torch
     return torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -109,9 +127,7 @@ def time_layer(lay, steps, warmup, tuning=None, autotune=False):
     if autotune and tuning is None:
         tuning = pp.Tuning(autotune=1)             # the plan times its candidates itself and keeps the fastest
     plan = pp.plan_from_layer(lay, tuning=tuning)
-    for _ in range(warmup):
-        plan.run(x, y, stream)
-    torch.cuda.synchronize()
+    _warm(lambda: plan.run(x, y, stream), warmup)
     ev0, ev1 = _events()
     t0 = time.perf_counter()
     ev0.record()
@@ -162,9 +178,7 @@ def time_block_gemm(steps, warmup, check=True, npts=2000):
     stream = torch.cuda.current_stream().cuda_stream
     plan = pp.block_plan_from_layer(lay)
     q = plan.query()
-    for _ in range(warmup):
-        plan.run(x, y, stream)
-    torch.cuda.synchronize()
+    _warm(lambda: plan.run(x, y, stream), warmup)
     ev0, ev1 = _events()
     t0 = time.perf_counter()
     ev0.record()
@@ -214,9 +228,7 @@ def time_deep_reuse(steps, warmup, check=True):
     y = torch.empty((lay.n, lay.m), dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream().cuda_stream
     plan = pp.reuse_plan_from_layer(lay)
-    for _ in range(warmup):
-        plan.run(x, y, stream)
-    torch.cuda.synchronize()
+    _warm(lambda: plan.run(x, y, stream), warmup)
     ev0, ev1 = _events()
     t0 = time.perf_counter()
     ev0.record()
@@ -327,9 +339,7 @@ def time_vgg_stack(steps, warmup):
                 pool(i)
                 cur = pools[i]
 
-    for _ in range(warmup):
-        step()
-    torch.cuda.synchronize()
+    _warm(step, warmup)
     ev0, ev1 = _events()
     t0 = time.perf_counter()
     ev0.record()
@@ -436,7 +446,6 @@ def main():
         tuning = pp.Tuning(variant=3, tile_rows=tr, tile_cols=tc, tiles_per_wave=ntw, wg_waves=waves)
     elif args.variant:
         tuning = pp.Tuning(variant=args.variant)
-    # the warm-up also settles clocks: at least 50 ms of it, whatever --warmup says
     t = time_layer(lay, args.steps, max(args.warmup, 20), tuning, args.autotune)
     s = summarize(lay, t)
     sec_wall = t["wall_ms_per_step"] * 1e-3
