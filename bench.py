@@ -308,65 +308,84 @@ def block_main(args):
 
 def time_vgg_stack(steps, warmup):
     """The 13 layers of the VGG-shaped configuration as ONE chain on one stream: every plan is built up
-    front, every activation buffer is allocated up front, and a step enqueues the 13 convolutions and the 4
-    max-pools back to back with no host synchronisation in between.  Each layer reads what the previous one
-    wrote.  The pools are also timed on their own, on the same buffers."""
+    front, every activation buffer is allocated up front, and a step enqueues the 13 convolutions back to
+    back with no host synchronisation in between; each layer reads what the previous one wrote.  The four
+    2x2 max-pools are folded into the layers in front of them (PP_FLAG_POOL2).  The same chain with the pools
+    as separate kernels is timed too (`unfused_us_per_step`), and those pool kernels on their own."""
+    import copy
     import torch
     import synth
     import paper_2206_10620_amd as pp
     layers = synth.config4()
     stream = torch.cuda.current_stream().cuda_stream
-    plans = [pp.plan_from_layer(l) for l in layers]
     x0 = torch.from_numpy(layers[0].make_input()).cuda()
-    bufs, pools = [], []
-    for l in layers:
-        y = torch.empty((l.n, l.c_out, l.h, l.w), dtype=torch.float16, device="cuda")
-        p = torch.empty((l.n, l.c_out, l.h // 2, l.w // 2), dtype=torch.float16, device="cuda") if l.meta["pool_after"] else None
-        bufs.append(y)
-        pools.append(p)
 
-    def pool(i):
+    def build(fused):
+        plans, bufs, pools, used = [], [], [], []
+        for l in layers:
+            pooled = l.meta["pool_after"]
+            lf = l
+            if pooled and fused:
+                lf = copy.copy(l)
+                lf.pool = True
+            plans.append(pp.plan_from_layer(lf))
+            used.append(lf)
+            oh, ow = (l.h // 2, l.w // 2) if (pooled and fused) else (l.h, l.w)
+            bufs.append(torch.empty((l.n, l.c_out, oh, ow), dtype=torch.float16, device="cuda"))
+            pools.append(torch.empty((l.n, l.c_out, l.h // 2, l.w // 2), dtype=torch.float16, device="cuda") if (pooled and not fused) else None)
+        return plans, bufs, pools, used
+
+    def pool(i, bufs, pools):
         l = layers[i]
         st = pp.pp_maxpool2x2_run(bufs[i].data_ptr(), pools[i].data_ptr(), l.n, l.c_out, l.h, l.w, pp.PP_F16, stream)
         assert st == pp.PP_OK
 
-    def step():
-        cur = x0
-        for i, (l, plan) in enumerate(zip(layers, plans)):
-            plan.run(cur, bufs[i], stream)
-            cur = bufs[i]
-            if pools[i] is not None:
-                pool(i)
-                cur = pools[i]
+    def make_step(plans, bufs, pools):
+        def step():
+            cur = x0
+            for i, plan in enumerate(plans):
+                plan.run(cur, bufs[i], stream)
+                cur = bufs[i]
+                if pools[i] is not None:
+                    pool(i, bufs, pools)
+                    cur = pools[i]
+        return step
 
-    _warm(step, warmup)
-    ev0, ev1 = _events()
-    t0 = time.perf_counter()
-    ev0.record()
-    for _ in range(steps):
-        step()
-    ev1.record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    chain_ms = ev0.elapsed_time(ev1) / steps
-    ev0, ev1 = _events()
-    ev0.record()
-    for _ in range(steps):
-        for i in range(len(layers)):
-            if pools[i] is not None:
-                pool(i)
-    ev1.record()
-    torch.cuda.synchronize()
-    pools_ms = ev0.elapsed_time(ev1) / steps
-    eff = sum(l.eff_macs for l in layers)
-    alg = sum(l.alg_bytes for l in layers)
-    variants = [p.query()["chosen"]["variant"] for p in plans]
+    def timed(step):
+        _warm(step, warmup)
+        ev0, ev1 = _events()
+        t0 = time.perf_counter()
+        ev0.record()
+        for _ in range(steps):
+            step()
+        ev1.record()
+        torch.cuda.synchronize()
+        return ev0.elapsed_time(ev1) / steps, (time.perf_counter() - t0) / steps
+
+    plans, bufs, pools, used = build(True)
+    chain_ms, wall = timed(make_step(plans, bufs, pools))
+    chosen = [p.query()["chosen"] for p in plans]
+    variants = [c["variant"] for c in chosen]
     for p in plans:
         p.close()
+    del bufs
+    plans_u, bufs_u, pools_u, _ = build(False)
+    unfused_ms, _ = timed(make_step(plans_u, bufs_u, pools_u))
+
+    def pools_only():
+        for i in range(len(layers)):
+            if pools_u[i] is not None:
+                pool(i, bufs_u, pools_u)
+    pools_ms, _ = timed(pools_only)
+    for p in plans_u:
+        p.close()
+    wall = wall * steps
+    eff = sum(l.eff_macs for l in layers)
+    alg = sum(l.alg_bytes for l in used)          # pooled layers write a quarter of their outputs
     sec = chain_ms * 1e-3
     return dict(workload="cfg4_vgg_stack_chained", dtype="f16", n=layers[0].n, layers=len(layers), pools=4,
                 eff_gmacs=eff / 1e9, alg_mb=alg / 1e6, us_per_step=chain_ms * 1e3, wall_us_per_step=wall * 1e6 / steps,
-                pools_us_per_step=pools_ms * 1e3, eff_gmac_per_s=eff / sec / 1e9, alg_gb_per_s=alg / sec / 1e9,
+                pools_us_per_step=pools_ms * 1e3, unfused_us_per_step=unfused_ms * 1e3, fused_pools=True, eff_gmac_per_s=eff / sec / 1e9, alg_gb_per_s=alg / sec / 1e9,
                 frac_fp32_valu=2 * eff / sec / 1e12 / PEAK_FP32_TFLOPS,
                 frac_fp32_valu_unpacked=2 * eff / sec / 1e12 / PEAK_FP32_UNPACKED_TFLOPS,
                 frac_hbm=alg / sec / 1e9 / PEAK_HBM_GBS, variants=variants,

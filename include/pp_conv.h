@@ -100,7 +100,7 @@ typedef struct {
                                reports chosen.autotune = 1 */
     int32_t mfma_kind;      /* which matrix-core kernel: 0 auto; 1 the general one (tiles transposed in registers on
                                their way into LDS; any kernel size, stride, channel count, fused pool); 2 the
-                               direct-load one (3x3, stride 1, no fused pool; when c_in is not a multiple of 16 the input is
+                               direct-load one (3x3, stride 1; a fused pool needs even image sizes; when c_in is not a multiple of 16 the input is
                                first copied into a plan-owned buffer with zero channels appended, n_hint images at a
                                time, so runs of such a plan must not overlap: tiles copied
                                memory-to-LDS as they are and transposed by the LDS read; tile_cols is then a multiple

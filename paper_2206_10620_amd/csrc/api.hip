@@ -387,8 +387,8 @@ pp_status_t pp_conv_plan(const pp_conv_desc_t* desc, pp_conv_plan_t** out_plan) 
         }
     } else if (hp.mfma) {
         if (hp.ml.direct) {
-            p->launch3 = k3_lookup(hp.ml.g3.sw, hp.ml.g3.waves, false);
-            if (hp.ml.ksplit > 1) p->launch3_split = k3_lookup(hp.ml.g3.sw, hp.ml.g3.waves, true);
+            p->launch3 = k3_lookup(hp.ml.g3.sw, hp.ml.g3.waves, false, hp.pool);
+            if (hp.ml.ksplit > 1) p->launch3_split = k3_lookup(hp.ml.g3.sw, hp.ml.g3.waves, true, false);
         }
         else p->launch2 = k2_lookup(hp.ks, hp.stride, hp.ml.ntw, hp.ml.waves, hp.ml.pairs);
         if (!p->launch2 && !p->launch3) {
@@ -583,7 +583,7 @@ static pp_status_t launch_mfma_direct(const pp_conv_plan_t* plan, const void* x_
         if (n > group) {
             for (int n0 = 0; n0 < n; n0 += group) {
                 const pp_status_t st = launch_mfma_direct(plan, static_cast<const _Float16*>(x_dev) + (int64_t)n0 * hp.c_in * hp.h * hp.w,
-                                                          static_cast<_Float16*>(y_dev) + (int64_t)n0 * hp.c_out * hp.h * hp.w, std::min(group, n - n0), stream, may_split);
+                                                          static_cast<_Float16*>(y_dev) + (int64_t)n0 * hp.c_out * hp.out_h * hp.out_w, std::min(group, n - n0), stream, may_split);
                 if (st != PP_OK) return st;
             }
             return PP_OK;
@@ -608,7 +608,9 @@ static pp_status_t launch_mfma_direct(const pp_conv_plan_t* plan, const void* x_
     a.h = hp.h;
     a.w = hp.w;
     a.po = ml.po;
-    a.vrows = n * ml.po - 1;
+    a.vrows = (n - 1) * ml.po + hp.h;
+    a.out_h = hp.out_h;
+    a.out_w = hp.out_w;
     a.tr = g.tr;
     a.nseg = g.nseg;
     const int valid = g.sw - 2;

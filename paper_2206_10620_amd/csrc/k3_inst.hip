@@ -7,15 +7,17 @@ namespace {
 template <int SW, int WAVES>
 void launch(const K3Args& a, int blocks, int lds_bytes, hipStream_t stream) {
     // the kernel may use more than the default 64 KB of dynamic LDS; set once per instantiation
-    static const hipError_t lds_attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&k3_mfma<SW, WAVES, false>),
+    static const hipError_t lds_attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&k3_mfma<SW, WAVES, false, false>),
                                                            hipFuncAttributeMaxDynamicSharedMemorySize, kMfmaMaxDynamicLds);
     (void)lds_attr;
-    hipLaunchKernelGGL((k3_mfma<SW, WAVES, false>), dim3(blocks), dim3(64 * WAVES), lds_bytes, stream, a);
+    hipLaunchKernelGGL((k3_mfma<SW, WAVES, false, false>), dim3(blocks), dim3(64 * WAVES), lds_bytes, stream, a);
 }
 
 }  // namespace
 
-k3_launch_fn k3_lookup(int sw, int waves, bool split) {
+k3_launch_fn k3_lookup(int sw, int waves, bool split, bool pool) {
+    if (split && pool) return nullptr;
+    if (pool) return k3_lookup_pool(sw, waves);
     if (split) return k3_lookup_split(sw, waves);
     if (sw == 32 && waves == 4) return launch<32, 4>;
     if (sw == 16 && waves == 4) return launch<16, 4>;

@@ -8,10 +8,10 @@ namespace {
 template <int SW, int WAVES>
 void launch(const K3Args& a, int blocks, int lds_bytes, hipStream_t stream) {
     // the kernel may use more than the default 64 KB of dynamic LDS; set once per instantiation
-    static const hipError_t lds_attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&k3_mfma<SW, WAVES, true>),
+    static const hipError_t lds_attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&k3_mfma<SW, WAVES, true, false>),
                                                            hipFuncAttributeMaxDynamicSharedMemorySize, kMfmaMaxDynamicLds);
     (void)lds_attr;
-    hipLaunchKernelGGL((k3_mfma<SW, WAVES, true>), dim3(blocks), dim3(64 * WAVES), lds_bytes, stream, a);
+    hipLaunchKernelGGL((k3_mfma<SW, WAVES, true, false>), dim3(blocks), dim3(64 * WAVES), lds_bytes, stream, a);
 }
 
 }  // namespace

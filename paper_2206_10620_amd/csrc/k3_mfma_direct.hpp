@@ -61,7 +61,7 @@ struct K3Args {
     const float* bias;          // [fb*64]
     int32_t n, c_in, c_out, h, w;
     int32_t po;                 // rows per image of the tall virtual image: h + 1
-    int32_t vrows;              // n * po - 1
+    int32_t vrows;              // (n - 1) * po + h
     int32_t tr, nseg;           // tile: rows x segments
     int32_t tiles_x, tiles_v, fb, q;
     int32_t work_items, blocks_per_xcd;
@@ -73,6 +73,7 @@ struct K3Args {
     int64_t x_elems;            // n * c_in * h * w
     // split reduction (SPLIT instantiations): each work item takes qs = q / ksplit consecutive chunks and stores
     // its partial sums, without bias or activation, as binary32 into slab ks of the workspace ([ksplit][n][c_out][h][w])
+    int32_t out_h, out_w;       // size of y per image and filter (h / 2 x w / 2 with the fused pool, else h x w)
     int32_t ksplit, qs;
     float* ws;
     int64_t slab_elems;         // n * c_out * h * w
@@ -139,7 +140,7 @@ __device__ __forceinline__ float k3_shl1(float v) {
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x130, 0xf, 0xf, true));
 }
 
-template <int SW, int WAVES, bool SPLIT>
+template <int SW, int WAVES, bool SPLIT, bool POOL>
 __global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void k3_mfma(const K3Args a) {
     constexpr int NT = kK3ColTiles, UPT = 32 / SW, SEGB = SW * 2, PPS = SEGB / 16, VALID = SW - 2;
@@ -490,6 +491,52 @@ void k3_mfma(const K3Args a) {
         int fbi, ks_c, ox0, v0;
         decode(item_c, fbi, ks_c, ox0, v0);
         const int oimg0 = v0 / a.po, oy0 = v0 - oimg0 * a.po;
+        if constexpr (POOL) {
+            // Fused 2x2 max-pool (stride 2).  The plan lays the tile out so that a wavefront's two column tiles are an
+            // even row of the tall image and the row below it, same segments, same columns (segments per tile row =
+            // segments per column tile), and gives every image an even number of rows in the tall image: the vertical
+            // maximum is between a lane's own two accumulators, the horizontal one with the next lane.  Even lanes
+            // of a segment then hold the pooled outputs, seven (or fifteen) consecutive binary16 values per segment.
+            static_assert(!SPLIT && NT == 2, "the pooled epilogue pairs the two column tiles of a wavefront");
+            _Float16* yb = static_cast<_Float16*>(a.y);
+            const int ohw = a.out_h * a.out_w;
+            const int ui = wave * NT * UPT + p / SW, col = p % SW;
+            const int row = k3_div(ui, a.magic_nseg), seg = ui - row * a.nseg;
+            const int ox = ox0 + seg * VALID + col;
+            const bool kill0 = ox == 0, kill2 = ox == a.w + 1;
+            const bool fix = __builtin_amdgcn_ballot_w64(kill0 || kill2) != 0;
+            const int t = oy0 + row, di = k3_div(t, a.magic_po);
+            const int img = oimg0 + di, oy = t - di * a.po;
+            const bool ok = col < VALID && (col & 1) == 0 && ox < a.w && v0 + row < a.vrows && oy < a.h;
+            const int off = ((img * a.c_out + fbi * kMfmaFilters + kb * 4) * a.out_h + (oy >> 1)) * a.out_w + (ox >> 1);
+            const bool full = (fbi + 1) * kMfmaFilters <= a.c_out;
+            stores_behind = 0;
+            store_credit = NS - 1;
+            if (full && __builtin_amdgcn_ballot_w64(ok) != 0) stores_behind += 32;
+            const float floor1 = a.relu ? 0.0f : -65504.0f;
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    float v[2];
+#pragma unroll
+                    for (int nt = 0; nt < 2; ++nt) {
+                        float p0 = acc[0][mt][nt][r], p1 = acc[1][mt][nt][r], p2 = acc[2][mt][nt][r];
+                        if (fix) {
+                            asm volatile("" ::: "memory");
+                            p0 = kill0 ? 0.0f : p0;
+                            p2 = kill2 ? 0.0f : p2;
+                        }
+                        v[nt] = p0 + k3_shl1(p1 + k3_shl1(p2));
+                    }
+                    float m = __builtin_fmaxf(v[0], v[1]);
+                    m = __builtin_fmaxf(m, k3_shl1(m));
+                    m = __builtin_fmaxf(m, floor1);
+                    const int f = mt * 32 + (r >> 2) * 8 + (r & 3);
+                    if (ok && (full || fbi * kMfmaFilters + f + kb * 4 < a.c_out)) yb[off + f * ohw] = (_Float16)m;
+                }
+            continue;
+        }
         if constexpr (SPLIT) {
             // Partial sums of this item's chunks: the three tap columns combined as below, stored as binary32 into
             // the item's slab of the workspace, no bias, no activation (a second kernel adds the slabs up in
@@ -613,7 +660,8 @@ void k3_mfma(const K3Args a) {
 
 typedef void (*k3_launch_fn)(const K3Args& a, int blocks, int lds_bytes, hipStream_t stream);
 // The instantiation for a segment width (32 or 16) and a workgroup size (4 or 8 wavefronts); nullptr otherwise.
-k3_launch_fn k3_lookup(int sw, int waves, bool split);
+k3_launch_fn k3_lookup(int sw, int waves, bool split, bool pool);
 k3_launch_fn k3_lookup_split(int sw, int waves);
+k3_launch_fn k3_lookup_pool(int sw, int waves);
 
 }  // namespace ppc

@@ -637,10 +637,11 @@ pp_status_t build_mfma_layout(const pp_conv_tuning_t& t, HostPlan& hp) {
     ml.q = (hp.c_in + kMfmaChunk - 1) / kMfmaChunk;
     ml.upq = KS <= 3 ? 1 : KS;
     ml.wbuf_bytes = (KK / ml.upq) * 2 * 1024;
-    // The direct-load kernel takes 3x3, stride-1 layers without a fused pool; measured on MI355X it is the faster
-    // of the two wherever it applies.
+    // The direct-load kernel takes 3x3, stride-1 layers; measured on MI355X it is the faster of the two wherever it
+    // applies.
     // (a channel count that does not fill whole chunks is padded with zero channels into a plan-owned copy of x)
-    const bool direct_ok = KS == 3 && S == 1 && !hp.pool && hp.h + 1 + 66 < 65536;
+    // (a fused 2x2 max-pool needs even image sizes and a tile whose wavefronts each hold an even row and the row below it)
+    const bool direct_ok = KS == 3 && S == 1 && hp.h + 2 + 66 < 65536 && (!hp.pool || (hp.h % 2 == 0 && hp.w % 2 == 0));
     if (t.mfma_kind < 0 || t.mfma_kind > 2 || (t.mfma_kind == 2 && !direct_ok)) return PP_ERR_UNSUPPORTED;
     // A request for a tile the direct kernel has no geometry for goes to the general kernel, unless the
     // direct one was asked for by name.
@@ -648,7 +649,8 @@ pp_status_t build_mfma_layout(const pp_conv_tuning_t& t, HostPlan& hp) {
         // Segment width: the one that computes the fewest columns per image row (a segment of sw computed
         // columns yields sw - 2 outputs).  Segments per tile row: the divisor of the workgroup's units
         // with the least matrix-core work (ragged last tiles) plus a quarter of the staged rows (halo).
-        const int64_t vr = (int64_t)hp.n_hint * (hp.h + 1) - 1;
+        const int po = hp.h + (hp.pool ? 2 : 1);     // rows per image of the tall image: an even number when rows are pooled in pairs
+        const int64_t vr = (int64_t)(hp.n_hint - 1) * po + hp.h;
         int sw = ((hp.w + 29) / 30) * 32 < ((hp.w + 13) / 14) * 16 ? 32 : 16;      // a tie goes to the narrow segments (measured: 3-7 % faster on 56-, 112- and 224-wide layers)
         // Workgroup size: eight wavefronts stage the weights once for twice the pixels (and have a compute
         // unit's LDS to themselves), but only a layer with several such tiles per compute unit keeps the
@@ -667,7 +669,8 @@ pp_status_t build_mfma_layout(const pp_conv_tuning_t& t, HostPlan& hp) {
             double best = 1e300;
             for (int ns = 1; ns <= units; ++ns) {
                 if (t.tile_cols && ns != nseg_o) continue;
-                if (!t.tile_cols && !t.tile_rows && spr >= 2 && ns < 2) continue;   // measured: short staged rows (32 or 64 bytes) load poorly; at least two segments side by side (1080p layer: 8 x 60 tiles 225 us, 16 x 30 tiles 236 us)
+                if (hp.pool && ns != 32 / sw) continue;      // pooled: a wavefront's two column tiles are two rows of the same segments
+                if (!hp.pool && !t.tile_cols && !t.tile_rows && spr >= 2 && ns < 2) continue;   // measured: short staged rows (32 or 64 bytes) load poorly; at least two segments side by side (1080p layer: 8 x 60 tiles 225 us, 16 x 30 tiles 236 us)
                 const K3Geom g = k3_geom(sw, ns, waves);
                 if (!g.ok || (t.tile_rows && t.tile_rows != g.tr)) continue;
                 const double tiles = (double)((spr + ns - 1) / ns) * (double)((vr + g.tr - 1) / g.tr);
@@ -691,7 +694,7 @@ pp_status_t build_mfma_layout(const pp_conv_tuning_t& t, HostPlan& hp) {
         const K3Geom g = k3_geom(sw, nseg, waves);
         if (!g.ok) return false;
         ml.g3 = g;
-        ml.po = hp.h + 1;
+        ml.po = po;
         ml.tr = g.tr;
         ml.tc = nseg * (sw - 2);
         ml.ntw = kK3ColTiles;
@@ -708,7 +711,9 @@ pp_status_t build_mfma_layout(const pp_conv_tuning_t& t, HostPlan& hp) {
         auto split_ok = [&](int k) { return k == 1 || (ml.q % k == 0 && ml.q / k >= std::max(2, stages - 1)); };
         if (t.split_k < 0 || (t.split_k > 1 && t.split_k != 2 && t.split_k != 4 && t.split_k != 8)) return false;
         int ks = 1;
-        if (t.split_k) {
+        if (hp.pool) {
+            if (t.split_k > 1) return false;           // the pooled epilogue stores final values only
+        } else if (t.split_k) {
             if (!split_ok(t.split_k)) return false;
             ks = t.split_k;
         } else if (tiles <= 128.0 && (ml.q >= 32 || (ml.q >= 16 && tiles <= 64.0))) {

@@ -236,3 +236,31 @@ def test_direct_padded_channels_beyond_the_batch_hint_and_dense_first_layer():
     dense = synth.dense_layer("dfirst", 2, 3, 64, 24, 40, "f16", 0.3, seed=2)
     rep, _ = check_layer(dense, label="mfma-direct-dense-first")
     assert rep["chosen"]["variant"] == 3 and rep["chosen"]["mfma_kind"] == 2
+
+
+# ---- fused 2x2 max-pool on the direct-load kernel ----
+
+@pytest.mark.parametrize("waves", [4, 8])
+def test_direct_fused_pool(waves):
+    say(f"mfma direct fused pool waves {waves}")
+    # even sizes; widths that take 14- and 30-column segments, ragged last segments and tiles, several images and filter blocks,
+    # padded channel counts, a ragged last filter block
+    for (n, c_in, c_out, h, w) in [(2, 32, 40, 8, 28), (3, 64, 130, 14, 14), (1, 48, 64, 6, 60), (2, 32, 8, 18, 4), (5, 3, 64, 12, 36), (2, 64, 64, 30, 90)]:
+        if waves == 8:
+            c_in = max(c_in, 32)
+        lay = synth.random_pruned_layer_k("dpool", n, c_in, c_out, h, w, "f16", 3, synth.PSET16, 0.5, 0.2, seed=waves + w, pool=True)
+        for relu in (True, False):
+            rep, _ = check_layer(lay, tuning=TD(wg_waves=waves), relu=relu, label=f"mfma-direct-pool-w{waves}")
+            assert rep["chosen"]["mfma_kind"] == 2 and rep["chosen"]["wg_waves"] == waves
+    say(f"  E={rep['E']:.2e} {rep['chosen']}")
+
+
+def test_direct_fused_pool_default_and_refusals():
+    lay = synth.random_pruned_layer_k("dpool-auto", 8, 64, 64, 56, 56, "f16", 3, synth.PSET8, 0.28, 0.05, seed=2, pool=True)
+    rep, _ = check_layer(lay, label="mfma-direct-pool-auto")
+    assert rep["chosen"]["variant"] == 3 and rep["chosen"]["mfma_kind"] == 2
+    with pytest.raises(pp.PPError):
+        pp.plan_from_layer(lay, host_only=True, tuning=TD(split_k=2))          # partial sums cannot be pooled
+    odd = synth.random_pruned_layer_k("dpool-odd", 1, 16, 8, 10, 10, "f16", 3, synth.PSET8, 0.5, 0.1, seed=2, stride=2, pool=False)
+    with pytest.raises(pp.PPError):
+        pp.plan_from_layer(odd, host_only=True, tuning=TD())
