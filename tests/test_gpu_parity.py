@@ -320,6 +320,24 @@ def test_config4_vgg_stack_per_layer(variant):
     assert tuple(xd.shape) == (8, 512, 14, 14)
 
 
+def test_config4_vgg_stack_with_fused_pools():
+    """The chain the benchmark times: the four pools folded into the layers in front of them, every layer gated on
+    its own at full size (sampled outputs, points on every tile boundary), the checker fed the GPU's input to it."""
+    import copy
+    layers = synth.config4()
+    x_np = layers[0].make_input()
+    for lay in layers:
+        if lay.meta["pool_after"]:
+            lay = copy.copy(lay)
+            lay.pool = True
+        say(f"{lay.name} pool={getattr(lay, 'pool', False)}")
+        rep, y = check_layer(lay, x_np, points=2048, label=f"cfg4-fused-{lay.name}")
+        assert rep["chosen"]["variant"] == 3 and rep["chosen"]["mfma_kind"] == 2, rep["chosen"]
+        say(f"  E={rep['E']:.2e} split_k={rep['chosen']['split_k']}")
+        x_np = y
+    assert tuple(x_np.shape) == (8, 512, 14, 14)
+
+
 @pytest.mark.parametrize("variant", [2, 3])
 def test_config5_large_image(variant):
     lay = synth.config5()
