@@ -75,6 +75,11 @@ def workloads():
         w[f"cfg3_resnet_c{c}_n32_f16"] = (lambda i=i: _as_f16(synth.config3(32)[i]))
     # A pattern table that is not the library's own (eight random centre-holding four-tap masks) on the shape of
     # the VGG mid layer: fp32 falls back to the generic kernel, binary16 runs on the matrix cores like any table.
+    # The other layer kinds of a ResNet-50-shaped bottleneck stage (section 3's mobile-DSP table): connectivity-pruned
+    # 1x1 layers and a pattern-pruned 3x3 layer with stride 2, binary16, batch 32 (general matrix-core kernel).
+    w["resnet_1x1_256_64_56_n32"] = lambda: _resnet_kind("resnet_1x1_256_64_56x56_n32", 256, 64, 56, 1, 1)
+    w["resnet_1x1_64_256_56_n32"] = lambda: _resnet_kind("resnet_1x1_64_256_56x56_n32", 64, 256, 56, 1, 1)
+    w["resnet_3x3s2_128_128_56_n32"] = lambda: _resnet_kind("resnet_3x3s2_128_128_56x56_n32", 128, 128, 56, 3, 2)
     w["cfg2_shape_foreign_patterns_f32"] = lambda: _foreign("f32")
     w["cfg2_shape_foreign_patterns_f16"] = lambda: _foreign("f16")
     return w
@@ -84,6 +89,14 @@ def _as_f16(lay):
     lay.dtype = "f16"
     lay.name += "_f16"
     return lay
+
+
+def _resnet_kind(name, c_in, c_out, hw, ksize, stride):
+    import synth
+    pset = np.array([1], dtype=np.uint16) if ksize == 1 else synth.PSET8
+    taps = 1 if ksize == 1 else 4
+    return synth.random_pruned_layer_k(name, 32, c_in, c_out, hw, hw, "f16", ksize, pset, 0.5, float(np.sqrt(2.0 / (taps * 0.5 * c_in))), seed=9,
+                                       stride=stride, x_dist="relu_n")
 
 
 def _foreign(dtype):
@@ -122,7 +135,7 @@ def time_layer(lay, steps, warmup, tuning=None, autotune=False):
     import torch
     import paper_2206_10620_amd as pp
     x = torch.from_numpy(lay.make_input()).cuda()
-    y = torch.empty((lay.n, lay.c_out, lay.h, lay.w), dtype=x.dtype, device="cuda")
+    y = torch.empty((lay.n, lay.c_out, lay.out_h, lay.out_w), dtype=x.dtype, device="cuda")
     stream = torch.cuda.current_stream().cuda_stream
     if autotune and tuning is None:
         tuning = pp.Tuning(autotune=1)             # the plan times its candidates itself and keeps the fastest
@@ -144,7 +157,8 @@ def time_layer(lay, steps, warmup, tuning=None, autotune=False):
 
 
 def dense_macs(lay):
-    return 9.0 * lay.n * lay.h * lay.w * lay.c_in * lay.c_out
+    k = getattr(lay, "ksize", 3)
+    return float(k * k) * lay.n * lay.conv_h * lay.conv_w * lay.c_in * lay.c_out
 
 
 def summarize(lay, t):
