@@ -414,7 +414,7 @@ def roofline_of(lay, t, traffic):
     if variant == 3:
         return {"bound": "hbm", "achieved": lay.alg_bytes / sec / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": lay.alg_bytes / sec / 1e9 / PEAK_HBM_GBS, "traffic": traffic,
-                "kernel": "k3_mfma" if t["chosen"].get("mfma_kind") == 2 else "k2_mfma",
+                "kernel": {2: "k3_mfma", 3: "k4_block_gemm"}.get(t["chosen"].get("mfma_kind"), "k2_mfma"),
                 "kernel_us": t["event_ms_per_step"] * 1e3,
                 "frac_mfma": 2 * dense_macs(lay) / sec / 1e12 / PEAK_MFMA_F16_TFLOPS,
                 "peak_mfma_tflops": PEAK_MFMA_F16_TFLOPS}

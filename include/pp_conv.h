@@ -98,7 +98,9 @@ typedef struct {
                                section 2.3.1 decided by measurement.  Takes some milliseconds per candidate and
                                synchronises with its own stream only.  Ignored with PP_FLAG_HOST_ONLY.  The plan
                                reports chosen.autotune = 1 */
-    int32_t mfma_kind;      /* which matrix-core kernel: 0 auto; 1 the general one (tiles transposed in registers on
+    int32_t mfma_kind;      /* which matrix-core kernel: 0 auto; 3 the product kernel of pp_block_gemm.h for 1x1 layers
+                               (stride 1, no pool, h * w a multiple of 8: one matrix product per image, connectivity
+                               pruning as its column pruning); 1 the general one (tiles transposed in registers on
                                their way into LDS; any kernel size, stride, channel count, fused pool); 2 the
                                direct-load one (3x3, stride 1; a fused pool needs even image sizes; when c_in is not a multiple of 16 the input is
                                first copied into a plan-owned buffer with zero channels appended, n_hint images at a

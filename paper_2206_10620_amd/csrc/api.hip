@@ -9,7 +9,9 @@
 #include "k1_tiled.hpp"
 #include "k2_mfma.hpp"
 #include "k3_mfma_direct.hpp"
+#include "block_plan.hpp"
 #include "plan.hpp"
+#include "pp_block_gemm.h"
 #include "pp_conv.h"
 
 namespace ppc {
@@ -189,6 +191,7 @@ struct pp_conv_plan {
     k3_launch_fn launch3 = nullptr;
     k3_launch_fn launch3_split = nullptr;     // the same kernel storing partial sums of a share of the chunks
     float* d_ws3 = nullptr;                   // their workspace: [ksplit][n_hint][c_out][h][w] binary32
+    pp_block_gemm_plan_t* pointwise = nullptr; // a 1x1 stride-1 layer in binary16 runs as a batch of matrix products (one per image)
     _Float16* d_xpad = nullptr;               // x with zero channels appended up to whole chunks of 16: [n_hint][cpad][h][w]
     // generic kernel
     int32_t* d_filt_off = nullptr;
@@ -398,6 +401,34 @@ pp_status_t pp_conv_plan(const pp_conv_desc_t* desc, pp_conv_plan_t** out_plan) 
     } else if (hp.c_out > 65535) {
         delete p;
         return PP_ERR_UNSUPPORTED;
+    }
+    // A 1x1, stride-1 layer is y_n = W x_n per image, with x_n = [c_in][h*w] as it lies in memory: the matrix-core
+    // kernel of the block-pruned product runs it, connectivity pruning being its column pruning with 1 x 1 blocks.
+    const int want_kind = desc->tuning ? desc->tuning->mfma_kind : 0;
+    const bool pointwise_ok = hp.mfma && hp.ks == 1 && hp.stride == 1 && !hp.pool && hp.taps == 1 && (hp.h * hp.w) % 8 == 0 && !(desc->tuning && desc->tuning->split_k > 1);
+    if (want_kind == 3 && !pointwise_ok) {
+        delete p;
+        return PP_ERR_UNSUPPORTED;
+    }
+    if (pointwise_ok && (want_kind == 0 || want_kind == 3)) {
+        pp_block_gemm_desc_t bd{};
+        bd.m = hp.c_out, bd.k = hp.c_in, bd.block_m = 1, bd.block_k = 1;
+        bd.row_keep = nullptr;
+        bd.col_keep = desc->conn_mask;          // [c_out][c_in]: block (co, ci) keeps its one column or not
+        bd.weights = desc->weights;             // one weight per kernel: [c_out][c_in]
+        bd.bias = desc->bias;
+        bd.flags = desc->flags & (PP_FLAG_RELU | PP_FLAG_HOST_ONLY);
+        bd.dtype = PP_F16;
+        bd.variant = 2;
+        const pp_status_t bst = pp_block_gemm_plan(&bd, &p->pointwise);
+        if (bst != PP_OK) {
+            delete p;
+            return bst;
+        }
+        hp.chosen.mfma_kind = 3;
+        hp.chosen.tile_rows = hp.chosen.tile_cols = hp.chosen.tiles_per_wave = 0;
+        hp.chosen.wg_waves = 4;
+        hp.chosen.split_k = 0;
     }
     if (desc->flags & PP_FLAG_HOST_ONLY) {
         *out_plan = p;
@@ -663,6 +694,8 @@ static pp_status_t launch_mfma_direct(const pp_conv_plan_t* plan, const void* x_
 static pp_status_t launch_mfma(const pp_conv_plan_t* plan, const void* x_dev, void* y_dev, int32_t n, hipStream_t stream, bool may_split = true) {
     const HostPlan& hp = plan->hp;
     const MfmaLayout& ml = hp.ml;
+    if (plan->pointwise)
+        return pp_block_gemm_launch_batched(plan->pointwise, x_dev, y_dev, hp.h * hp.w, n, (int64_t)hp.c_in * hp.h * hp.w, (int64_t)hp.c_out * hp.h * hp.w, stream);
     if (ml.direct) return launch_mfma_direct(plan, x_dev, y_dev, n, stream, may_split);
     K2Args a{};
     a.x = x_dev;
@@ -771,6 +804,7 @@ pp_status_t pp_conv_run_static(const pp_conv_plan_t* plan, const void* x_dev, vo
 
 pp_status_t pp_conv_destroy(pp_conv_plan_t* plan) {
     if (!plan) return PP_OK;
+    if (plan->pointwise) (void)pp_block_gemm_destroy(plan->pointwise);
     free_device(plan);
     delete plan;
     return PP_OK;

@@ -40,6 +40,30 @@ void release(pp_block_gemm_plan_t* p) {
 
 }  // namespace
 
+pp_status_t pp_block_gemm_launch_batched(const pp_block_gemm_plan_t* plan, const void* x_dev, void* y_dev, int32_t n, int32_t batch, int64_t x_stride,
+                                         int64_t y_stride, void* hip_stream) {
+    if (!plan || !x_dev || !y_dev) return PP_ERR_NULL;
+    const BlockHostPlan& hp = plan->hp;
+    if (n < 1 || batch < 1 || (n % 8) != 0 || hp.dtype != PP_F16 || !plan->on_device) return PP_ERR_UNSUPPORTED;
+    if ((int64_t)hp.k * n >= ((int64_t)1 << 31) || (int64_t)hp.m * n >= ((int64_t)1 << 31)) return PP_ERR_SHAPE;
+    K4Args a;
+    a.x = x_dev, a.y = y_dev, a.apk = plan->d_apk, a.bias = plan->d_bias;
+    a.tile_off = plan->d_tile_off, a.tile_cols = plan->d_tile_cols;
+    a.m = hp.m, a.n = n, a.row_tiles = hp.row_tiles;
+    a.col_tiles = (n + kBlockColTile - 1) / kBlockColTile;
+    const int64_t items = (int64_t)a.row_tiles * a.col_tiles * batch;
+    if (items >= ((int64_t)1 << 28)) return PP_ERR_SHAPE;
+    a.items = (int)items;
+    a.per_xcd = (a.items + 7) / 8;
+    a.relu = (hp.flags & PP_FLAG_RELU) ? 1 : 0;
+    a.x_stride = x_stride, a.y_stride = y_stride;
+    static const hipError_t lds_attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&k4_block_gemm), hipFuncAttributeMaxDynamicSharedMemorySize, kK4LdsBytes);
+    (void)lds_attr;
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(k4_block_gemm, dim3((unsigned)(a.per_xcd * 8)), dim3(256), kK4LdsBytes, static_cast<hipStream_t>(hip_stream), a);
+    return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_DEVICE;
+}
+
 extern "C" {
 
 pp_status_t pp_block_gemm_plan(const pp_block_gemm_desc_t* desc, pp_block_gemm_plan_t** out_plan) {
@@ -95,22 +119,8 @@ pp_status_t pp_block_gemm_run(const pp_block_gemm_plan_t* plan, const void* x_de
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const int relu = (hp.flags & PP_FLAG_RELU) ? 1 : 0;
     (void)hipGetLastError();
-    if (variant == 2) {
-        K4Args a;
-        a.x = x_dev, a.y = y_dev, a.apk = plan->d_apk, a.bias = plan->d_bias;
-        a.tile_off = plan->d_tile_off, a.tile_cols = plan->d_tile_cols;
-        a.m = hp.m, a.n = n, a.row_tiles = hp.row_tiles;
-        a.col_tiles = (n + kBlockColTile - 1) / kBlockColTile;
-        const int64_t items = (int64_t)a.row_tiles * a.col_tiles;
-        if (items >= ((int64_t)1 << 28)) return PP_ERR_SHAPE;
-        a.items = (int)items;
-        a.per_xcd = (a.items + 7) / 8;
-        a.relu = relu;
-        static const hipError_t lds_attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&k4_block_gemm),
-                                                               hipFuncAttributeMaxDynamicSharedMemorySize, kK4LdsBytes);
-        (void)lds_attr;
-        hipLaunchKernelGGL(k4_block_gemm, dim3((unsigned)(a.per_xcd * 8)), dim3(256), kK4LdsBytes, stream, a);
-    } else {
+    if (variant == 2) return pp_block_gemm_launch_batched(plan, x_dev, y_dev, n, 1, 0, 0, hip_stream);
+    {
         const dim3 grid((unsigned)((n + 63) / 64), (unsigned)hp.row_tiles), block(64, 4);
         if (hp.row_tiles > 65535) return PP_ERR_SHAPE;
         if (hp.dtype == PP_F16)

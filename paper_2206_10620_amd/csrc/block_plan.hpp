@@ -38,3 +38,9 @@ pp_status_t build_block_plan(const pp_block_gemm_desc_t& d, BlockHostPlan& out);
 pp_status_t unpack_block_tile(const BlockHostPlan& p, int tile, float* w_out);
 
 }  // namespace ppc
+
+
+// Enqueues `batch` products with the plan's weights: matrix b of x ([k][n]) starts x_stride elements after matrix b - 1,
+// likewise y ([m][n]).  Matrix-core kernel only (binary16, n a multiple of 8); used by the convolution library for 1x1 layers.
+pp_status_t pp_block_gemm_launch_batched(const pp_block_gemm_plan_t* plan, const void* x_dev, void* y_dev, int32_t n, int32_t batch, int64_t x_stride,
+                                         int64_t y_stride, void* hip_stream);

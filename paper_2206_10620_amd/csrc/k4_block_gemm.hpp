@@ -30,6 +30,8 @@ struct K4Args {
     const int32_t* tile_off;    // [row_tiles + 1], multiples of 16
     const int32_t* tile_cols;   // compact lists
     int32_t m, n, row_tiles, col_tiles, items, per_xcd, relu;
+    // a batch of products with the same weights (the images of a 1x1 convolution): item = (image, column tile, row tile)
+    int64_t x_stride, y_stride;  // elements between the x (y) matrices of consecutive images
 };
 
 constexpr int kK4Stages = 4;
@@ -81,7 +83,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     // work items, ordered column tile first, so that the workgroups sharing an L2 read the same columns of x.
     const int item = (int)(blockIdx.x & 7u) * a.per_xcd + (int)(blockIdx.x >> 3);
     if (item >= a.items) return;
-    const int ct = item / a.row_tiles, rt = item - ct * a.row_tiles;
+    const int per_image = a.row_tiles * a.col_tiles;
+    const int img = item / per_image, in_image = item - img * per_image;
+    const int ct = in_image / a.row_tiles, rt = in_image - ct * a.row_tiles;
     const int col0 = ct * kBlockColTile;
     const int e0 = __builtin_amdgcn_readfirstlane(a.tile_off[rt]), e1 = __builtin_amdgcn_readfirstlane(a.tile_off[rt + 1]);
     const int nch = (e1 - e0) / kBlockChunk;
@@ -90,7 +94,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     typedef const __attribute__((address_space(4))) int32_t* k4_const_i32;
     const k4_const_i32 list = (k4_const_i32)(uintptr_t)k4_uniform_ptr(a.tile_cols + e0);
     const unsigned char* wsrc = k4_uniform_ptr(static_cast<const unsigned char*>(a.apk) + (int64_t)(e0 / kBlockChunk) * 2048 + wave * 1024);
-    const unsigned char* xsrc = k4_uniform_ptr(static_cast<const unsigned char*>(a.x) + (int64_t)col0 * 2);
+    const unsigned char* xsrc = k4_uniform_ptr(static_cast<const unsigned char*>(a.x) + ((int64_t)img * a.x_stride + col0) * 2);
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)k4_smem;
     const uint32_t lane16 = (uint32_t)lane * 16u;
     const bool piece_ok = col0 + lane * 8 < a.n;            // n is a multiple of 8: a 16-byte piece is inside a row or outside
@@ -204,7 +208,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int srow = lane >> 4, scol = (lane & 15) * 8;                  // store side: 16 lanes hold one row's 128 columns
     const int ycol = col0 + wave * 128 + scol;
     const bool col_ok = ycol < a.n;
-    unsigned char* ybase = static_cast<unsigned char*>(a.y);
+    unsigned char* ybase = static_cast<unsigned char*>(a.y) + (int64_t)img * a.y_stride * 2;
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) {
 #pragma unroll

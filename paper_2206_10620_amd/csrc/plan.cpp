@@ -642,7 +642,8 @@ pp_status_t build_mfma_layout(const pp_conv_tuning_t& t, HostPlan& hp) {
     // (a channel count that does not fill whole chunks is padded with zero channels into a plan-owned copy of x)
     // (a fused 2x2 max-pool needs even image sizes and a tile whose wavefronts each hold an even row and the row below it)
     const bool direct_ok = KS == 3 && S == 1 && hp.h + 2 + 66 < 65536 && (!hp.pool || (hp.h % 2 == 0 && hp.w % 2 == 0));
-    if (t.mfma_kind < 0 || t.mfma_kind > 2 || (t.mfma_kind == 2 && !direct_ok)) return PP_ERR_UNSUPPORTED;
+    // (mfma_kind 3, the product kernel for 1x1 layers, is decided by the caller of this function: the layout built here is then the fallback)
+    if (t.mfma_kind < 0 || t.mfma_kind > 3 || (t.mfma_kind == 2 && !direct_ok)) return PP_ERR_UNSUPPORTED;
     // A request for a tile the direct kernel has no geometry for goes to the general kernel, unless the
     // direct one was asked for by name.
     auto direct_layout = [&]() -> bool {
@@ -729,7 +730,7 @@ pp_status_t build_mfma_layout(const pp_conv_tuning_t& t, HostPlan& hp) {
         ml.cpad = ml.q * kMfmaChunk;
         return true;
     };
-    ml.direct = direct_ok && t.mfma_kind != 1 && direct_layout();
+    ml.direct = direct_ok && t.mfma_kind != 1 && t.mfma_kind != 3 && direct_layout();
     if (t.mfma_kind == 2 && !ml.direct) return PP_ERR_UNSUPPORTED;
     if (t.split_k > 1 && !ml.direct) return PP_ERR_UNSUPPORTED;      // only the direct-load kernel splits the reduction
     // The batch is one tall virtual image: image n's output row oy is virtual row n*po + oy, and the

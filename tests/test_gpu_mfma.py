@@ -264,3 +264,34 @@ def test_direct_fused_pool_default_and_refusals():
     odd = synth.random_pruned_layer_k("dpool-odd", 1, 16, 8, 10, 10, "f16", 3, synth.PSET8, 0.5, 0.1, seed=2, stride=2, pool=False)
     with pytest.raises(pp.PPError):
         pp.plan_from_layer(odd, host_only=True, tuning=TD())
+
+
+# ---- 1x1 layers as a batch of matrix products on the block-product kernel (mfma_kind 3) ----
+
+def test_pointwise_layers_run_on_the_product_kernel():
+    from gpu_util import run_layer
+    one = np.array([1], dtype=np.uint16)
+    for (n, c_in, c_out, h, w, keep) in [(2, 64, 256, 8, 8, 0.5), (3, 40, 70, 4, 6, 0.6), (1, 256, 64, 56, 56, 0.5), (2, 16, 16, 2, 4, 1.0),
+                                          (5, 100, 130, 12, 10, 0.3), (2, 32, 64, 16, 40, 0.0)]:
+        lay = synth.random_pruned_layer_k("pw", n, c_in, c_out, h, w, "f16", 1, one, keep, 0.2, seed=n + c_in)
+        say(f"pointwise {lay.n}x{c_in}->{c_out} {h}x{w} keep {keep}")
+        for relu in (True, False):
+            rep, y = check_layer(lay, relu=relu, label="pointwise")
+            assert rep["chosen"]["variant"] == 3 and rep["chosen"]["mfma_kind"] == 3, rep["chosen"]
+        y1, c1 = run_layer(lay, lay.make_input(), tuning=pp.Tuning(variant=3, mfma_kind=1), relu=False)
+        assert c1["mfma_kind"] == 1
+        assert np.max(np.abs(y.astype(np.float32) - y1.astype(np.float32))) <= 2e-3 * max(1.0, float(np.abs(y1).max()))
+    import copy
+    nb = copy.copy(lay)
+    nb.bias = None
+    nb.conn_mask = np.ones_like(lay.conn_mask)
+    check_layer(nb, label="pointwise-no-bias")
+    # an image plane that is not a multiple of 8 elements goes to the general kernel; asking for the product kernel there is refused
+    odd = synth.random_pruned_layer_k("pw-odd", 2, 32, 32, 7, 7, "f16", 1, one, 0.5, 0.2, seed=3)
+    rep, _ = check_layer(odd, label="pointwise-odd")
+    assert rep["chosen"]["mfma_kind"] == 1
+    with pytest.raises(pp.PPError):
+        pp.plan_from_layer(odd, host_only=True, tuning=pp.Tuning(variant=3, mfma_kind=3))
+    with pytest.raises(pp.PPError):
+        pp.plan_from_layer(synth.random_pruned_layer("pw-3x3", 1, 16, 16, 8, 8, "f16", synth.PSET8, 0.5, 0.2, seed=3), host_only=True,
+                           tuning=pp.Tuning(variant=3, mfma_kind=3))
