@@ -48,32 +48,54 @@ __global__ __launch_bounds__(256) void reuse_hash(const float* __restrict__ x, c
         hp[s * pitch + (e - s * hash_bits * L)] = hyper[e];
     }
     __syncthreads();
-    const uint32_t total = (uint32_t)n * (uint32_t)S;              // below 2^31: n * k is
-    for (uint32_t e = blockIdx.x * 256u + threadIdx.x; e < total; e += gridDim.x * 256u) {      // e = i * S + s
-        const int i = (int)(e / (uint32_t)S), s = (int)(e - (uint32_t)i * (uint32_t)S);
-        float xv[L];
-        const float* src = x + (int64_t)e * L;                      // row i, columns s L ..: rows are k = S L floats long
-        if constexpr (L % 4 == 0) {
+    // a lane takes the same segment of RPL consecutive rows, so that every hyperplane value it reads from LDS serves RPL
+    // neuron vectors; consecutive lanes take consecutive segments, so each of its loads is part of one contiguous row
+    constexpr int RPL = 4;
+    const uint32_t groups = (uint32_t)((n + RPL - 1) / RPL), total = groups * (uint32_t)S;      // below 2^31: n * k is
+    for (uint32_t e = blockIdx.x * 256u + threadIdx.x; e < total; e += gridDim.x * 256u) {      // e = (i / RPL) * S + s
+        const int i0 = (int)(e / (uint32_t)S) * RPL, s = (int)(e % (uint32_t)S);
+        float xv[RPL][L];
 #pragma unroll
-            for (int l = 0; l < L; l += 4) {
-                const float4 v = *reinterpret_cast<const float4*>(src + l);
-                xv[l] = v.x, xv[l + 1] = v.y, xv[l + 2] = v.z, xv[l + 3] = v.w;
+        for (int j = 0; j < RPL; ++j) {
+            const int i = i0 + j < n ? i0 + j : n - 1;                  // rows past the end repeat the last one (not stored)
+            const float* src = x + (int64_t)i * k + s * L;
+            if constexpr (L % 4 == 0) {
+#pragma unroll
+                for (int l = 0; l < L; l += 4) {
+                    const float4 v = *reinterpret_cast<const float4*>(src + l);
+                    xv[j][l] = v.x, xv[j][l + 1] = v.y, xv[j][l + 2] = v.z, xv[j][l + 3] = v.w;
+                }
+            } else {
+#pragma unroll
+                for (int l = 0; l < L; ++l) xv[j][l] = src[l];
             }
-        } else {
-#pragma unroll
-            for (int l = 0; l < L; ++l) xv[l] = src[l];
         }
         const float* h0 = hp + s * pitch;
-        unsigned g = 0;
-        for (int h = 0; h < hash_bits; ++h) {
-            float p = 0.0f;
+        unsigned g[RPL];
 #pragma unroll
-            for (int l = 0; l < L; ++l) p = __builtin_fmaf(xv[l], h0[h * L + l], p);
-            g |= (p > 0.0f ? 1u : 0u) << h;
+        for (int j = 0; j < RPL; ++j) g[j] = 0;
+        for (int h = 0; h < hash_bits; ++h) {
+            float p[RPL];
+#pragma unroll
+            for (int j = 0; j < RPL; ++j) p[j] = 0.0f;
+#pragma unroll
+            for (int l = 0; l < L; ++l) {
+                const float hv = h0[h * L + l];
+#pragma unroll
+                for (int j = 0; j < RPL; ++j) p[j] = __builtin_fmaf(xv[j][l], hv, p[j]);
+            }
+#pragma unroll
+            for (int j = 0; j < RPL; ++j) g[j] |= (p[j] > 0.0f ? 1u : 0u) << h;
         }
-        sig[e] = (uint16_t)g;
-        int32_t* slot = rep + (int64_t)s * G + g;
-        if (__builtin_nontemporal_load(slot) > i) atomicMin(slot, i);
+#pragma unroll
+        for (int j = 0; j < RPL; ++j) {
+            const int i = i0 + j;
+            if (i < n) {
+                sig[(int64_t)i * S + s] = (uint16_t)g[j];
+                int32_t* slot = rep + (int64_t)s * G + g[j];
+                if (__builtin_nontemporal_load(slot) > i) atomicMin(slot, i);
+            }
+        }
     }
 }
 
@@ -218,7 +240,7 @@ pp_status_t pp_reuse_run(const pp_reuse_plan_t* p, const void* x_dev, void* y_de
     (void)hipGetLastError();
     hipLaunchKernelGGL(reuse_clear, dim3((unsigned)((S * G + 255) / 256)), dim3(256), 0, stream, p->d_rep, S * G);
     const size_t lds = (size_t)S * (p->H * p->L + 1) * 4;
-    const int64_t hash_blocks = std::min<int64_t>(((int64_t)n * S + 255) / 256, 256 * 8);      // at most eight workgroups per compute unit
+    const int64_t hash_blocks = std::min<int64_t>(((int64_t)((n + 3) / 4) * S + 255) / 256, 256 * 8);      // at most eight workgroups per compute unit
     hipLaunchKernelGGL(hash, dim3((unsigned)hash_blocks), dim3(256), lds, stream, x, p->d_hyper, p->d_sig, p->d_rep, n, p->k, p->H);
     hipLaunchKernelGGL(reuse_products, dim3((unsigned)((G * p->m + 255) / 256), (unsigned)S), dim3(256), 0, stream, x, p->d_w, p->d_rep, p->d_P, p->k,
                        p->m, p->L, G);
