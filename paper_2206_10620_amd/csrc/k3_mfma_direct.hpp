@@ -355,6 +355,21 @@ void k3_mfma(const K3Args a) {
 
     // ---- accumulators: three tap columns x two filter halves x NT column tiles ----
     k3_f16 acc[3][2][NT];
+    // A computed column outside the image (input column -1 or w) must not reach an output: its P_0 (for
+    // output 0) or P_2 (for output w - 1) is cleared before the columns are combined.  Rare and
+    // wave-uniform, so a branch around in-place selects (the empty asm keeps it a branch).
+    auto clear_outside = [&](int nt, bool fix, bool kill0, bool kill2) {
+        if (fix) {
+            asm volatile("" ::: "memory");
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    acc[0][mt][nt][r] = kill0 ? 0.0f : acc[0][mt][nt][r];
+                    acc[2][mt][nt][r] = kill2 ? 0.0f : acc[2][mt][nt][r];
+                }
+        }
+    };
 
     // Steps (chunk after chunk, tile after tile) are staged NS - 1 ahead of the step being multiplied.
     int ik = 0, iq = 0, ibuf = 0;                   // the next step to stage: tile, chunk, ring place
@@ -514,21 +529,16 @@ void k3_mfma(const K3Args a) {
             store_credit = NS - 1;
             if (full && __builtin_amdgcn_ballot_w64(ok) != 0) stores_behind += 32;
             const float floor1 = a.relu ? 0.0f : -65504.0f;
+            clear_outside(0, fix, kill0, kill2);
+            clear_outside(1, fix, kill0, kill2);
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     float v[2];
 #pragma unroll
-                    for (int nt = 0; nt < 2; ++nt) {
-                        float p0 = acc[0][mt][nt][r], p1 = acc[1][mt][nt][r], p2 = acc[2][mt][nt][r];
-                        if (fix) {
-                            asm volatile("" ::: "memory");
-                            p0 = kill0 ? 0.0f : p0;
-                            p2 = kill2 ? 0.0f : p2;
-                        }
-                        v[nt] = p0 + k3_shl1(p1 + k3_shl1(p2));
-                    }
+                    for (int nt = 0; nt < 2; ++nt)
+                        v[nt] = acc[0][mt][nt][r] + k3_shl1(acc[1][mt][nt][r] + k3_shl1(acc[2][mt][nt][r]));
                     float m = __builtin_fmaxf(v[0], v[1]);
                     m = __builtin_fmaxf(m, k3_shl1(m));
                     m = __builtin_fmaxf(m, floor1);
@@ -560,17 +570,12 @@ void k3_mfma(const K3Args a) {
                 // an active lane as soon as one column of this tile is an output, and all 32 are counted
                 const bool full = (fbi + 1) * kMfmaFilters <= a.c_out;
                 if (full && __builtin_amdgcn_ballot_w64(ok) != 0) stores_behind += 32;
+                clear_outside(nt, fix, kill0, kill2);
 #pragma unroll
                 for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
-                        float p0 = acc[0][mt][nt][r], p1 = acc[1][mt][nt][r], p2 = acc[2][mt][nt][r];
-                        if (fix) {
-                            asm volatile("" ::: "memory");
-                            p0 = kill0 ? 0.0f : p0;
-                            p2 = kill2 ? 0.0f : p2;
-                        }
-                        const float v = p0 + k3_shl1(p1 + k3_shl1(p2));
+                        const float v = acc[0][mt][nt][r] + k3_shl1(acc[1][mt][nt][r] + k3_shl1(acc[2][mt][nt][r]));
                         const int f = mt * 32 + (r >> 2) * 8 + (r & 3);               // + 4 kb: the register's filter inside the block
                         if (ok && (full || fbi * kMfmaFilters + f + kb * 4 < a.c_out)) wsb[off + f * hw] = v;
                     }
@@ -595,6 +600,7 @@ void k3_mfma(const K3Args a) {
                 kill2 = ox == a.w + 1;
                 fix = __builtin_amdgcn_ballot_w64(kill0 || kill2) != 0;
             }
+            clear_outside(nt, fix, kill0, kill2);
             // store side: lane = 4 * filter + piece; the piece's 8 columns, how many of them are outputs
             const int sp = lane_e & 3, sf = lane_e >> 2;
             int nv;
@@ -615,15 +621,8 @@ void k3_mfma(const K3Args a) {
                 for (int r = 0; r < 16; r += 2) {
                     k3_f2 pr;
 #pragma unroll
-                    for (int i = 0; i < 2; ++i) {
-                        float p0 = acc[0][mt][nt][r + i], p1 = acc[1][mt][nt][r + i], p2 = acc[2][mt][nt][r + i];
-                        if (fix) {                 // wave-uniform and rare: kept a branch (the empty asm stops if-conversion)
-                            asm volatile("" ::: "memory");
-                            p0 = kill0 ? 0.0f : p0;
-                            p2 = kill2 ? 0.0f : p2;
-                        }
-                        pr[i] = p0 + k3_shl1(p1 + k3_shl1(p2));
-                    }
+                    for (int i = 0; i < 2; ++i)
+                        pr[i] = acc[0][mt][nt][r + i] + k3_shl1(acc[1][mt][nt][r + i] + k3_shl1(acc[2][mt][nt][r + i]));
                     k3_h2 hv = __builtin_convertvector(pr, k3_h2);                // (filter, filter + 1) of this column, rounded to nearest even
                     hv = __builtin_elementwise_max(hv, floor2);                   // ReLU (or nothing: the floor is then the lowest finite value)
                     const int frow = (r >> 2) * 8 + (r & 3);                      // + kb * 4: the filter's row in the corner
