@@ -24,6 +24,10 @@ roofline : the dominant kernel of the timed workload against the roofline that b
              once, packed weights once) per second against 8 TB/s.  The matrix-core fraction (dense flop
              against 2.5 PFLOP/s) is given beside it as `frac_mfma`.
            Kernel time comes from events recorded on the launch stream around the timed launches.
+timing   : every timed region follows at least 100 ms of untimed launches of the same work (the chip's clock
+           settles some tens of milliseconds into a sustained load).
+copy_reference : a plain device copy moving the same activation bytes, timed the same way: what the memory
+           system of the box gives the simplest kernel; context for `roofline`, whose peak stays 8 TB/s.
 """
 from __future__ import annotations
 
@@ -154,6 +158,28 @@ def time_layer(lay, steps, warmup, tuning=None, autotune=False):
                x=x, y=y)
     plan.close()
     return res
+
+
+def time_copy_reference(x, y, layer_us):
+    """A plain device-to-device copy that reads as many bytes as the layer's input holds and writes as many as its
+    output holds (torch's copy kernel, same warm-up and event timing as the layer): what this machine's memory system
+    delivers to the simplest kernel moving the same activation bytes.  Context for `roofline`, not a peak."""
+    import torch
+    nbytes = (x.numel() * x.element_size() + y.numel() * y.element_size()) // 2
+    src = torch.empty(nbytes // 4, dtype=torch.float32, device="cuda").normal_()
+    dst = torch.empty_like(src)
+    _warm(lambda: dst.copy_(src), 20)
+    ev0, ev1 = _events()
+    steps = 50
+    ev0.record()
+    for _ in range(steps):
+        dst.copy_(src)
+    ev1.record()
+    torch.cuda.synchronize()
+    us = ev0.elapsed_time(ev1) * 1e3 / steps
+    return {"what": "torch device copy reading and writing as many bytes as the layer's input and output hold",
+            "bytes_moved": 2 * (nbytes // 4) * 4, "us": us, "gb_per_s": 2 * (nbytes // 4) * 4 / us / 1e3,
+            "layer_us_over_copy_us": layer_us / us}
 
 
 def dense_macs(lay):
@@ -501,6 +527,8 @@ def main():
         "frac_fp32_valu": s["frac_fp32_valu"], "frac_fp32_valu_unpacked": s["frac_fp32_valu_unpacked"],
         "roofline": roofline_of(lay, t, traffic),
     }
+
+    out["copy_reference"] = time_copy_reference(t["x"], t["y"], t["event_ms_per_step"] * 1e3)
 
     if not args.no_cpu:
         import oracle
