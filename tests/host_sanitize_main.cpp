@@ -9,11 +9,21 @@
 #include <cstring>
 #include <vector>
 
+#include "block_plan.hpp"
 #include "plan.hpp"
 
 extern "C" {
 int oracle_expand_weights(int c_in, int c_out, int num_patterns, const uint16_t* masks, const int32_t* pattern_id,
                           const uint8_t* conn, const double* w, int taps_per_kernel, double* Wd);
+int oracle_block_expand(int m, int k, int bm, int bk, const uint8_t* row_keep, const uint8_t* col_keep, const double* w, double* wd);
+void oracle_gemm(int m, int k, int n, const double* wd, const double* x, const double* bias, int relu, double* y, double* pre, double* scale,
+                 int threads);
+void oracle_block_brute(int m, int k, int n, int bm, int bk, const uint8_t* row_keep, const uint8_t* col_keep, const double* w, const double* x,
+                        const double* bias, int relu, double* y);
+int oracle_reuse_signatures(int n, int k, int seg_len, int hash_bits, const float* x, const float* hp, uint16_t* sig);
+void oracle_reuse_representatives(int n, int S, int hash_bits, const uint16_t* sig, int32_t* rep);
+void oracle_reuse_apply(int n, int k, int m, int seg_len, int hash_bits, const double* x, const double* w, const double* bias, const uint16_t* sig,
+                        const int32_t* rep, int relu, double* y, double* pre, double* scale);
 int64_t oracle_plan_ref(int c_in, int c_out, int num_patterns, const int32_t* pattern_id, const uint8_t* conn,
                         int32_t* perm, int32_t* kcount, int32_t* pat_off, int32_t* kidx, uint8_t* kpat, int64_t* wsel);
 }
@@ -145,6 +155,83 @@ int main() {
             bad.pattern_masks = mb.data();
             if (validate(bad) == PP_OK) return fail("nine-bit mask accepted", c);
         }
+    }
+    // block-pruned product: the plan's packed tiles decode back to the masked matrix the checker builds, for both
+    // packings, over ragged block and matrix sizes; invalid descriptions come back as a status
+    for (int c = 0; c < 40; ++c) {
+        Rng r{(uint64_t)c * 104729u + 17u};
+        const int m = 1 + r.below(150), k = 1 + r.below(150), bm = 1 + r.below(40), bk = 1 + r.below(40), n = 1 + r.below(9);
+        const int blocks_m = (m + bm - 1) / bm, blocks_k = (k + bk - 1) / bk;
+        std::vector<uint8_t> rk((size_t)blocks_m * blocks_k * bm), ck((size_t)blocks_m * blocks_k * bk);
+        for (auto& v : rk) v = r.below(100) < 55;
+        for (auto& v : ck) v = r.below(100) < 55;
+        std::vector<float> w((size_t)m * k), bias(m);
+        for (auto& v : w) v = r.unit();
+        for (auto& v : bias) v = r.unit();
+        pp_block_gemm_desc_t d{};
+        d.m = m, d.k = k, d.block_m = bm, d.block_k = bk;
+        d.row_keep = (c % 5 == 4) ? nullptr : rk.data();
+        d.col_keep = (c % 7 == 6) ? nullptr : ck.data();
+        d.weights = w.data();
+        d.bias = (c & 1) ? bias.data() : nullptr;
+        d.flags = PP_FLAG_HOST_ONLY | ((c & 2) ? PP_FLAG_RELU : 0u);
+        d.dtype = (c % 3 == 0) ? PP_F32 : PP_F16;
+        d.variant = d.dtype == PP_F16 ? 2 - (c & 1) : 1;
+        ppc::BlockHostPlan bp;
+        if (ppc::build_block_plan(d, bp) != PP_OK) return fail("block plan refused", c);
+        std::vector<uint8_t> ones_r(rk.size(), 1), ones_c(ck.size(), 1);
+        std::vector<double> w64(w.begin(), w.end()), wd((size_t)m * k);
+        if (d.dtype == PP_F16)
+            for (auto& v : w64) v = (double)f16_to_f32(f32_to_f16_rne((float)v));
+        if (oracle_block_expand(m, k, bm, bk, d.row_keep ? rk.data() : ones_r.data(), d.col_keep ? ck.data() : ones_c.data(), w64.data(), wd.data()) != 0)
+            return fail("checker refused the block layer", c);
+        std::vector<float> tile((size_t)ppc::kBlockRowTile * k);
+        for (int t = 0; t < bp.row_tiles; ++t) {
+            if (ppc::unpack_block_tile(bp, t, tile.data()) != PP_OK) return fail("block tile did not unpack", c);
+            for (int rr = 0; rr < ppc::kBlockRowTile && t * ppc::kBlockRowTile + rr < m; ++rr)
+                for (int cc = 0; cc < k; ++cc)
+                    if ((double)tile[(size_t)rr * k + cc] != wd[(size_t)(t * ppc::kBlockRowTile + rr) * k + cc]) return fail("block tile differs from the masked matrix", c);
+        }
+        if (ppc::unpack_block_tile(bp, bp.row_tiles, tile.data()) == PP_OK) return fail("tile index past the end accepted", c);
+        std::vector<double> x((size_t)k * n), y((size_t)m * n), yb((size_t)m * n), b64(bias.begin(), bias.end());
+        for (auto& v : x) v = r.unit();
+        oracle_gemm(m, k, n, wd.data(), x.data(), d.bias ? b64.data() : nullptr, (c & 2) != 0, y.data(), nullptr, nullptr, 2);
+        oracle_block_brute(m, k, n, bm, bk, d.row_keep ? rk.data() : ones_r.data(), d.col_keep ? ck.data() : ones_c.data(), w64.data(), x.data(),
+                           d.bias ? b64.data() : nullptr, (c & 2) != 0, yb.data());
+        for (size_t i = 0; i < y.size(); ++i)
+            if (std::abs(y[i] - yb[i]) > 1e-9) return fail("the checker's two evaluations differ", c);
+        pp_block_gemm_desc_t bad = d;
+        bad.block_m = 0;
+        if (ppc::build_block_plan(bad, bp) == PP_OK) return fail("block_m = 0 accepted", c);
+        bad = d;
+        bad.weights = nullptr;
+        if (ppc::build_block_plan(bad, bp) == PP_OK) return fail("null block weights accepted", c);
+        bad = d;
+        bad.dtype = PP_F32, bad.variant = 2;
+        if (ppc::build_block_plan(bad, bp) == PP_OK) return fail("matrix-core kernel with fp32 accepted", c);
+        ++cases;
+    }
+    // deep reuse checker: signatures, representatives and the approximated layer on ragged sizes
+    for (int c = 0; c < 20; ++c) {
+        Rng r{(uint64_t)c * 7919u + 5u};
+        const int L = 1 + r.below(8), S = 1 + r.below(6), k = L * S, n = 1 + r.below(70), m = 1 + r.below(10), H = 1 + r.below(10);
+        std::vector<float> x((size_t)n * k), hp((size_t)S * H * L);
+        for (auto& v : x) v = r.unit();
+        for (auto& v : hp) v = r.unit();
+        std::vector<uint16_t> sig((size_t)n * S);
+        if (oracle_reuse_signatures(n, k, L, H, x.data(), hp.data(), sig.data()) != 0) return fail("signatures refused", c);
+        std::vector<int32_t> rep((size_t)S << H);
+        oracle_reuse_representatives(n, S, H, sig.data(), rep.data());
+        for (int i = 0; i < n; ++i)
+            for (int sgm = 0; sgm < S; ++sgm) {
+                const int32_t rp = rep[((size_t)sgm << H) + sig[(size_t)i * S + sgm]];
+                if (rp < 0 || rp > i || sig[(size_t)rp * S + sgm] != sig[(size_t)i * S + sgm]) return fail("representative is not the cluster's first row", c);
+            }
+        std::vector<double> x64(x.begin(), x.end()), w((size_t)k * m), bias(m), y((size_t)n * m), pre((size_t)n * m), sc((size_t)n * m);
+        for (auto& v : w) v = r.unit();
+        for (auto& v : bias) v = r.unit();
+        oracle_reuse_apply(n, k, m, L, H, x64.data(), w.data(), (c & 1) ? bias.data() : nullptr, sig.data(), rep.data(), c & 2, y.data(), pre.data(), sc.data());
+        ++cases;
     }
     // binary16 conversion on every bit pattern and around every rounding boundary
     for (uint32_t b = 0; b < 65536; ++b) {
