@@ -120,3 +120,38 @@ def test_transformer_sized_layer_at_sampled_outputs():
     ref, pre, sc = oracle.gemm_at(wd, x.astype(np.float64), pts, lay.bias, lay.relu)
     rep = error_report(got[pts[:, 0], pts[:, 1]], ref, pre, sc)
     assert rep["E"] <= TOL["f16"], rep
+
+
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+def test_the_comparison_fails_on_a_wrong_layer(dtype):
+    """Negative controls.  The GPU runs the layer as given; the checker is handed a copy with one mistake planted
+    in it on the CPU side: a pruned block row kept, a kept block column pruned, one kept weight off by 25 x the
+    tolerance, the row and column flags of the blocks read the other way round.  Each must push E over the
+    tolerance, and the unchanged layer must pass."""
+    import copy
+    lay = synth.random_block_layer("neg", 128, 128, 64, 32, 32, dtype, 0.5, 0.5, 71, poison=False)
+    x = lay.make_input()
+    got, _ = run(lay, x)
+
+    def E_against(other):
+        ref, pre, sc = oracle.block_layer_reference(other, x.astype(np.float64))
+        return error_report(got, ref, pre, sc)["E"]
+
+    assert E_against(lay) <= TOL[dtype]
+    keep = lay.keep_matrix()
+    # a block with kept and pruned rows and columns
+    bi, bj = next((i, j) for i in range(lay.blocks_m) for j in range(lay.blocks_k)
+                  if 0 < lay.row_keep[i, j].sum() < lay.bm and 0 < lay.col_keep[i, j].sum() < lay.bk)
+    wrong = copy.deepcopy(lay)
+    wrong.row_keep[bi, bj, int(np.flatnonzero(lay.row_keep[bi, bj] == 0)[0])] = 1
+    assert E_against(wrong) > TOL[dtype]
+    wrong = copy.deepcopy(lay)
+    wrong.col_keep[bi, bj, int(np.flatnonzero(lay.col_keep[bi, bj])[0])] = 0
+    assert E_against(wrong) > TOL[dtype]
+    wrong = copy.deepcopy(lay)
+    r, c = np.unravel_index(int(np.argmax(np.where(keep, np.abs(lay.weights), 0.0))), keep.shape)
+    wrong.weights[r, c] *= 1.0 + 25 * TOL[dtype]
+    assert E_against(wrong) > TOL[dtype]
+    wrong = copy.deepcopy(lay)
+    wrong.row_keep, wrong.col_keep = lay.col_keep.copy(), lay.row_keep.copy()       # square blocks: same shapes
+    assert E_against(wrong) > TOL[dtype]

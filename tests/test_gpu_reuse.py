@@ -101,3 +101,32 @@ def test_benchmark_layer_full_size():
     lay = synth.conv_shaped_reuse_layer()
     rep = check(lay)
     print("clusters used", int((rep >= 0).sum()), "of", lay.n * lay.segments, "neuron vectors", flush=True)
+
+
+def test_the_comparison_fails_on_a_wrong_layer():
+    """Negative controls.  The GPU runs the layer as given; the checker is handed a copy with one mistake planted
+    in it on the CPU side: one hyperplane negated (signatures must differ), the election of the highest row instead
+    of the lowest (representatives must differ), one weight off by 25 x the tolerance (E must exceed it)."""
+    lay = synth.random_reuse_layer("neg", 1500, 64, 16, 8, 6, seed=9, prototypes=12, noise=0.05)
+    x = lay.make_input()
+    plan = pp.reuse_plan_from_layer(lay)
+    try:
+        got = plan.run(torch.from_numpy(x).cuda()).cpu().numpy()
+        torch.cuda.synchronize()
+        sig, rep = plan.clusters(lay.n)
+    finally:
+        plan.close()
+    ref, pre, sc, rsig, rrep = oracle.reuse_layer(x, lay.weights, lay.hyperplanes, lay.seg_len, lay.hash_bits, lay.bias, lay.relu)
+    assert np.array_equal(sig, rsig) and np.array_equal(rep, rrep) and error_report(got, ref, pre, sc)["E"] <= TOL["f32"]
+    hp = lay.hyperplanes.copy()
+    hp.reshape(-1, lay.seg_len)[3] *= -1.0
+    assert not np.array_equal(sig, oracle.reuse_signatures(x, hp, lay.seg_len, lay.hash_bits))
+    # the last row of every cluster instead of the first: the checker's election run on the rows in reverse
+    last = oracle.reuse_representatives(np.ascontiguousarray(rsig[::-1]), lay.hash_bits)
+    last = np.where(last >= 0, lay.n - 1 - last, -1)
+    assert not np.array_equal(rep, last)
+    w = lay.weights.copy()
+    r, c = np.unravel_index(int(np.argmax(np.abs(w))), w.shape)
+    w[r, c] *= 1.0 + 25 * TOL["f32"]
+    wref, wpre, wsc, _, _ = oracle.reuse_layer(x, w, lay.hyperplanes, lay.seg_len, lay.hash_bits, lay.bias, lay.relu)
+    assert error_report(got, wref, wpre, wsc)["E"] > TOL["f32"]
