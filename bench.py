@@ -201,7 +201,7 @@ def summarize(lay, t):
 
 BLOCK_WORKLOAD = "block_ffn_4096"
 # HBM-side bytes of one launch of the block-pruned product, measured as above (profiles/k4_block_gemm_block_ffn_4096.md)
-MEASURED_TRAFFIC_BLOCK = ("k4-2026-11-28-a", 184.45e6)
+MEASURED_TRAFFIC_BLOCK = ("k4-2026-11-28-b", 184.45e6)
 
 
 def time_block_gemm(steps, warmup, check=True, npts=2000):

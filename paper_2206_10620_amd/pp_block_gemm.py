@@ -10,7 +10,7 @@ from .pp_conv import PP_OK, PP_F16, PP_F32, PP_FLAG_HOST_ONLY, PP_FLAG_RELU, PPE
 
 
 # Bumped whenever the device code of the matrix-core kernel changes (hardware-counter readings are keyed by it).
-BLOCK_KERNEL_REVISION = "k4-2026-11-28-a"
+BLOCK_KERNEL_REVISION = "k4-2026-11-28-b"
 
 
 class _Desc(C.Structure):
