@@ -395,10 +395,27 @@ void k3_mfma(const K3Args a) {
         advance_issue();
     }
 
-    // One step: multiply the chunk in ring place sbuf, and deal out the loads of step `nxt` between the taps.
+    // The step to stage during a multiplication: NS - 1 after the one being multiplied.
+    auto next_step = [&]() -> Step {
+        Step st;
+        st.on = false;
+        if (ik < my_n) {
+            if (iq == 0) take_tile(first_item + slot + ik * gslots);   // parked at the head of tile ik - 1
+            st = begin_step(iq, ibuf);
+            advance_issue();
+        }
+        young = NS > 2 ? (st.on ? st.count : 0) : 0;
+        return st;
+    };
+
+    // One step: multiply the chunk in ring place sbuf, and deal out the loads of the step to stage between the taps.
+    // That step's description (a hundred-odd scalar instructions of address arithmetic) is worked out behind the
+    // first tap's MFMAs rather than ahead of them: the matrix cores start right after the barrier.
     // FIRST: the tile's first chunk, whose MFMAs start the accumulators (the centre column's from the bias).
-    auto multiply = [&](auto first_tag, int sbuf, const Step& nxt) {
+    auto multiply = [&](auto first_tag, int sbuf, int setup_item) -> Step {
         constexpr bool FIRST = decltype(first_tag)::value;
+        Step nxt;
+        nxt.on = false;
         const uint32_t xb = lds0 + (uint32_t)(sbuf * xb_bytes);
         const unsigned char* wb = smem + NS * xb_bytes + sbuf * kK3WeightBytes + lane * 16;
         // Operand fragments are read one tap ahead into a second set of registers, so that the LDS latency
@@ -454,15 +471,25 @@ void k3_mfma(const K3Args a) {
                     }
                     acc[c][mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[t & 1][mt], bf[r & 1][nt], cin, 0, 0, 0);
                 }
+            if (t == 0) nxt = next_step();
+            if constexpr (WAVES == 8) {
+                if (t == 1 && setup_item >= 0) setup_tile(setup_item);
+            }
             issue_slot(nxt, t);
             __builtin_amdgcn_sched_barrier(0);
         }
+        return nxt;
     };
 
     int sbuf = 0;                                   // ring place of the current step
     for (int kt = 0; kt < my_n; ++kt) {
         const int item_c = first_item + slot + kt * gslots;
-        if (kt + 1 < my_n) setup_tile(item_c + gslots);
+        // The staging set of the next tile is worked out and parked in LDS before the ring gets there, which is during
+        // chunk QN - (NS - 1) of this tile: behind the MFMAs of the second chunk when that is early enough (eight-wavefront
+        // workgroups only: measured, it gains 2-3 % there and loses as much with four), else here, at the head of the tile.
+        const bool setup_late = WAVES == 8 && QN - (NS - 1) >= 2;
+        const int setup_next = kt + 1 < my_n ? item_c + gslots : -1;
+        if (!setup_late && setup_next >= 0) setup_tile(setup_next);
         __builtin_amdgcn_sched_barrier(0);
 
         // ---- main loop over chunks of 16 channels ----
@@ -474,17 +501,7 @@ void k3_mfma(const K3Args a) {
             k3_wait_vm(young + (store_credit > 0 ? stores_behind : 0));
             if (store_credit > 0) --store_credit;
             __syncthreads();
-            // the step to stage now: NS - 1 after the current one
-            Step nxt;
-            nxt.on = false;
-            if (ik < my_n) {
-                if (iq == 0) take_tile(first_item + slot + ik * gslots);   // parked at the head of tile ik - 1
-                nxt = begin_step(iq, ibuf);
-                advance_issue();
-            }
-            young = NS > 2 ? (nxt.on ? nxt.count : 0) : 0;
-            if (qi == 0) multiply(std::true_type{}, sbuf, nxt);
-            else multiply(std::false_type{}, sbuf, nxt);
+            const Step nxt = qi == 0 ? multiply(std::true_type{}, sbuf, -1) : multiply(std::false_type{}, sbuf, qi == 1 && setup_late ? setup_next : -1);
             finish_step(nxt);
             sbuf = sbuf + 1 == NS ? 0 : sbuf + 1;
         }
