@@ -88,6 +88,7 @@ typedef float k3_f16 __attribute__((ext_vector_type(16)));
 typedef uint32_t k3_u3 __attribute__((ext_vector_type(3)));
 typedef uint32_t k3_u4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) unsigned char* k3_lds_ptr;
+typedef uint32_t __attribute__((may_alias)) k3_u32_alias;
 
 // n / d for n < 65536 and 1 <= d < 65536 with magic = floor(2^32 / d) + 1 (0 stands for d = 1)
 __device__ __forceinline__ int k3_div(int n, uint32_t magic) { return magic ? (int)__umulhi((uint32_t)n, magic) : n; }
@@ -618,15 +619,21 @@ void k3_mfma(const K3Args a) {
                 fix = __builtin_amdgcn_ballot_w64(kill0 || kill2) != 0;
             }
             clear_outside(nt, fix, kill0, kill2);
-            // store side: lane = 4 * filter + piece; the piece's 8 columns, how many of them are outputs
+            // store side: lane = 4 * filter + piece; the piece's 8 columns, how many of them are outputs.  The last
+            // piece of a segment would hold 6 outputs and 2 halo columns: where the whole segment lies inside the image
+            // it is moved back by those 2 columns and writes 8 outputs, 2 of them a second time with the same values,
+            // so that one full-width store instruction serves every lane instead of a wide and a narrow one.
             const int sp = lane_e & 3, sf = lane_e >> 2;
-            int nv;
+            int nv, back;
             uint32_t off;
             {
-                const int ui = (wave * NT + nt) * UPT + (8 * sp) / SW, col = (8 * sp) % SW;
+                const int ui = (wave * NT + nt) * UPT + (8 * sp) / SW, col0 = (8 * sp) % SW;
                 const int row = k3_div(ui, a.magic_nseg), seg = ui - row * a.nseg;
                 const int t = oy0 + row, di = k3_div(t, a.magic_po);
-                const int img = oimg0 + di, oy = t - di * a.po, ox = ox0 + seg * VALID + col;
+                const int ox_seg = ox0 + seg * VALID;                     // the segment's first output column
+                back = (col0 + 8 > VALID && a.w - ox_seg >= VALID) ? col0 + 8 - VALID : 0;
+                const int col = col0 - back;
+                const int img = oimg0 + di, oy = t - di * a.po, ox = ox_seg + col;
                 int lim = a.w - ox;                                       // outputs left in the image row
                 if (lim > VALID - col) lim = VALID - col;                 // ... and in the segment
                 nv = (v0 + row < a.vrows && oy < a.h) ? (lim > 8 ? 8 : (lim < 0 ? 0 : lim)) : 0;
@@ -649,7 +656,10 @@ void k3_mfma(const K3Args a) {
                 // the wavefront's own corner: LDS operations of one wavefront execute in order
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
-                    const k3_u4 w4 = *reinterpret_cast<const k3_u4*>(tb + tb_r + j * 1024);
+                    // (4-byte aligned; the type may alias the binary16 values written above)
+                    const k3_u32_alias* src = reinterpret_cast<const k3_u32_alias*>(tb + tb_r + j * 1024 - 2 * back);
+                    k3_u4 w4;
+                    w4.x = src[0], w4.y = src[1], w4.z = src[2], w4.w = src[3];
                     const int f = mt * 32 + j * 16 + sf;                  // filter inside the block
                     const bool fok = fbi * kMfmaFilters + f < a.c_out;
                     unsigned char* dst = ybase + (off + (uint32_t)(mt * 32 + j * 16) * fstride);
