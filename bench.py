@@ -52,10 +52,10 @@ PEAK_HBM_GBS = 8000.0
 # kernel of known size; see profiles/.  Valid only for the kernel revision it was measured on:
 # reported as null for any other.  Keyed by (workload, variant).
 MEASURED_TRAFFIC = {
-    ("cfg5_enhance_1080p", 3): ("lib-2026-11-28-h", 607.80e6),
-    ("cfg4_vgg_L6", 3): ("lib-2026-11-28-h", 38.16e6),
-    ("cfg4_vgg_L9", 3): ("lib-2026-11-28-h", 53.92e6),
-    ("cfg2_vgg_mid", 2): ("lib-2026-11-28-h", 20.43e6),
+    ("cfg5_enhance_1080p", 3): ("lib-2026-11-28-i", 606.92e6),
+    ("cfg4_vgg_L6", 3): ("lib-2026-11-28-i", 38.16e6),
+    ("cfg4_vgg_L9", 3): ("lib-2026-11-28-i", 53.92e6),
+    ("cfg2_vgg_mid", 2): ("lib-2026-11-28-i", 20.43e6),
 }
 
 DEFAULT_WORKLOAD = "cfg5_enhance_1080p"

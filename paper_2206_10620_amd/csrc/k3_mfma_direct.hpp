@@ -530,6 +530,9 @@ void k3_mfma(const K3Args a) {
             // segments per column tile), and gives every image an even number of rows in the tall image: the vertical
             // maximum is between a lane's own two accumulators, the horizontal one with the next lane.  Even lanes
             // of a segment then hold the pooled outputs, seven (or fifteen) consecutive binary16 values per segment.
+            // A store instruction costs about the same however few lanes take part, so two filters share one: the even
+            // lanes store the filter of register r, the odd lanes (handed the value by their even neighbour) the filter
+            // of register r + 1 at the same pooled column.
             static_assert(!SPLIT && NT == 2, "the pooled epilogue pairs the two column tiles of a wavefront");
             _Float16* yb = static_cast<_Float16*>(a.y);
             const int ohw = a.out_h * a.out_w;
@@ -540,28 +543,36 @@ void k3_mfma(const K3Args a) {
             const bool fix = __builtin_amdgcn_ballot_w64(kill0 || kill2) != 0;
             const int t = oy0 + row, di = k3_div(t, a.magic_po);
             const int img = oimg0 + di, oy = t - di * a.po;
-            const bool ok = col < VALID && (col & 1) == 0 && ox < a.w && v0 + row < a.vrows && oy < a.h;
-            const int off = ((img * a.c_out + fbi * kMfmaFilters + kb * 4) * a.out_h + (oy >> 1)) * a.out_w + (ox >> 1);
+            const int odd = col & 1;                                      // VALID and w are even: an even column and the next one are outputs together
+            const bool ok = col - odd < VALID && ox - odd < a.w && v0 + row < a.vrows && oy < a.h;
+            const int off = ((img * a.c_out + fbi * kMfmaFilters + kb * 4 + odd) * a.out_h + (oy >> 1)) * a.out_w + ((ox - odd) >> 1);
             const bool full = (fbi + 1) * kMfmaFilters <= a.c_out;
             stores_behind = 0;
             store_credit = NS - 1;
-            if (full && __builtin_amdgcn_ballot_w64(ok) != 0) stores_behind += 32;
+            if (full && __builtin_amdgcn_ballot_w64(ok) != 0) stores_behind += 16;
             const float floor1 = a.relu ? 0.0f : -65504.0f;
             clear_outside(0, fix, kill0, kill2);
             clear_outside(1, fix, kill0, kill2);
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    float v[2];
+                for (int r = 0; r < 16; r += 2) {
+                    float m[2];
 #pragma unroll
-                    for (int nt = 0; nt < 2; ++nt)
-                        v[nt] = acc[0][mt][nt][r] + k3_shl1(acc[1][mt][nt][r] + k3_shl1(acc[2][mt][nt][r]));
-                    float m = __builtin_fmaxf(v[0], v[1]);
-                    m = __builtin_fmaxf(m, k3_shl1(m));
-                    m = __builtin_fmaxf(m, floor1);
-                    const int f = mt * 32 + (r >> 2) * 8 + (r & 3);
-                    if (ok && (full || fbi * kMfmaFilters + f + kb * 4 < a.c_out)) yb[off + f * ohw] = (_Float16)m;
+                    for (int i = 0; i < 2; ++i) {
+                        float v[2];
+#pragma unroll
+                        for (int nt = 0; nt < 2; ++nt)
+                            v[nt] = acc[0][mt][nt][r + i] + k3_shl1(acc[1][mt][nt][r + i] + k3_shl1(acc[2][mt][nt][r + i]));
+                        m[i] = __builtin_fmaxf(v[0], v[1]);
+                        m[i] = __builtin_fmaxf(m[i], k3_shl1(m[i]));
+                        m[i] = __builtin_fmaxf(m[i], floor1);
+                    }
+                    // lane i <- lane i - 1: an odd lane receives filter r + 1 of the pooled column of its even neighbour
+                    const float up = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, m[1]), 0x138, 0xf, 0xf, true));
+                    const float val = odd ? up : m[0];
+                    const int f = mt * 32 + (r >> 2) * 8 + (r & 3);           // + odd: in `off`
+                    if (ok && (full || fbi * kMfmaFilters + f + odd + kb * 4 < a.c_out)) yb[off + f * ohw] = (_Float16)val;
                 }
             continue;
         }
@@ -569,7 +580,9 @@ void k3_mfma(const K3Args a) {
             // Partial sums of this item's chunks: the three tap columns combined as below, stored as binary32 into
             // the item's slab of the workspace, no bias, no activation (a second kernel adds the slabs up in
             // slab order).  A register holds one filter for 32 columns: lanes 0-31 write a 128-byte run of one
-            // filter's row, lanes 32-63 the same columns of the filter four further on.
+            // filter's row, lanes 32-63 the same columns of the filter four further on.  With an even image width two
+            // registers share a store instruction of twice the width: the even lanes store columns (c, c + 1) of the
+            // filter of register r, the odd lanes columns (c - 1, c) of the filter of register r + 1.
             float* wsb = k3_uniform_ptr(a.ws + (int64_t)ks_c * a.slab_elems);
             stores_behind = 0;
             store_credit = NS - 1;
@@ -585,10 +598,30 @@ void k3_mfma(const K3Args a) {
                 const bool ok = col < VALID && ox < a.w && v0 + row < a.vrows && oy < a.h;
                 const int off = ((img * a.c_out + fbi * kMfmaFilters + kb * 4) * a.h + oy) * a.w + ox;   // + (filter - 4 kb) * h * w
                 // a whole block of 64 filters inside the layer (wave-uniform): then every store instruction below has
-                // an active lane as soon as one column of this tile is an output, and all 32 are counted
+                // an active lane as soon as one column of this tile is an output, and all of them are counted
                 const bool full = (fbi + 1) * kMfmaFilters <= a.c_out;
-                if (full && __builtin_amdgcn_ballot_w64(ok) != 0) stores_behind += 32;
+                if (full && __builtin_amdgcn_ballot_w64(ok) != 0) stores_behind += wide_ok ? 16 : 32;
                 clear_outside(nt, fix, kill0, kill2);
+                if (wide_ok) {
+                    const int odd = col & 1;                              // VALID and w are even: an even column and the next one are outputs together
+                    const bool ok2 = col - odd < VALID && ox - odd < a.w && v0 + row < a.vrows && oy < a.h;
+                    const int off2 = off + odd * (hw - 1);                // the odd lane: the next filter, one column back
+#pragma unroll
+                    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                        for (int r = 0; r < 16; r += 2) {
+                            const float va = acc[0][mt][nt][r] + k3_shl1(acc[1][mt][nt][r] + k3_shl1(acc[2][mt][nt][r]));
+                            const float vb = acc[0][mt][nt][r + 1] + k3_shl1(acc[1][mt][nt][r + 1] + k3_shl1(acc[2][mt][nt][r + 1]));
+                            const float va_next = k3_shl1(va);            // lane i <- lane i + 1
+                            const float vb_prev = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, vb), 0x138, 0xf, 0xf, true));   // lane i <- lane i - 1
+                            k3_f2 pair;
+                            pair.x = odd ? vb_prev : va;
+                            pair.y = odd ? vb : va_next;
+                            const int f = mt * 32 + (r >> 2) * 8 + (r & 3);           // + odd (in off2) + 4 kb
+                            if (ok2 && (full || fbi * kMfmaFilters + f + odd + kb * 4 < a.c_out)) *reinterpret_cast<k3_f2*>(wsb + off2 + f * hw) = pair;
+                        }
+                    continue;
+                }
 #pragma unroll
                 for (int mt = 0; mt < 2; ++mt)
 #pragma unroll

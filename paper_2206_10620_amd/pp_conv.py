@@ -13,7 +13,7 @@ PP_FLAG_RELU, PP_FLAG_DENSE, PP_FLAG_HOST_ONLY, PP_FLAG_POOL2 = 1, 2, 4, 8
 
 # Bumped whenever the device code of the tiled kernel changes (measurements that are tied to a
 # kernel build, such as hardware-counter readings, are keyed by it).
-KERNEL_REVISION = "lib-2026-11-28-h"
+KERNEL_REVISION = "lib-2026-11-28-i"
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libpp_conv.so")
